@@ -66,8 +66,9 @@ def gaussian_mixture(n: int, dim: int, n_comp: int, center_std: float, sigma: fl
     for c, lo_r, hi_r in _chunks(n):
         g = _rng(seed, stream, c)
         m = hi_r - lo_r
-        comp = g.integers(0, n_comp, size=m)
-        z = g.standard_normal((m, dim), dtype=np.float32)
+        # always draw the whole chunk so that a shorter matrix is a prefix of a longer one
+        comp = g.integers(0, n_comp, size=_CHUNK)[:m]
+        z = g.standard_normal((_CHUNK, dim), dtype=np.float32)[:m]
         if std is None:
             z *= np.float32(sigma)
         else:
@@ -101,9 +102,10 @@ def sift_like(n: int, dim: int, n_comp: int, seed: int, stream: int,
     for c, lo_r, hi_r in _chunks(n):
         g = _rng(seed, stream, c)
         m = hi_r - lo_r
-        comp = g.integers(0, n_comp, size=m)
-        lat = g.standard_normal((m, latent_rank), dtype=np.float32)
-        x = g.standard_normal((m, dim), dtype=np.float32)
+        # always draw the whole chunk so that a shorter matrix is a prefix of a longer one
+        comp = g.integers(0, n_comp, size=_CHUNK)[:m]
+        lat = g.standard_normal((_CHUNK, latent_rank), dtype=np.float32)[:m]
+        x = g.standard_normal((_CHUNK, dim), dtype=np.float32)[:m]
         # process component by component to keep the low-rank product a GEMM
         order = np.argsort(comp, kind="stable")
         bounds = np.searchsorted(comp[order], np.arange(n_comp + 1))
