@@ -1,0 +1,164 @@
+/*
+ * cagra_hip.h -- C ABI of the MI355X (gfx950) CAGRA library.
+ *
+ * Two operations, following the paper's problem statement:
+ *   build : dataset[N, dim]            -> graph[N, degree]     (Sec. III-B)
+ *   search: graph, dataset, queries[B] -> ids[B, k], dists[B, k] (Sec. IV)
+ * plus the exhaustive search of Eq. 1 (ground truth for recall, Eq. 2) and
+ * the single build stages, exported so that each can be checked on its own.
+ *
+ * Conventions for every entry point
+ *   - Every pointer named below is DEVICE memory owned by the caller unless it
+ *     says "host".  The library never allocates or frees device memory and
+ *     keeps no pointer after the call returns.  Scratch space is passed in as
+ *     `workspace` (device, 256-byte aligned), sized by the matching
+ *     *_workspace_bytes() function.
+ *   - Matrices are row-major fp32; `ld` is the row stride in elements
+ *     (ld >= dim).  dim and ld must be multiples of 4 and the base pointers
+ *     16-byte aligned (rows are fetched with 16-byte loads, Sec. IV-B.1).
+ *   - Graphs are row-major uint32 node ids, values < N, N <= 2^31 - 1
+ *     (one bit of the index word carries the parent flag, Sec. IV-B.4).
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     Calls only enqueue work on that stream and return without waiting;
+ *     outputs are valid once the stream has reached that point.
+ *   - Return value: 0 on success, a negative cagra_status otherwise.  On any
+ *     error nothing has been launched and no output has been touched.
+ *   - Distances: CAGRA_L2 is the squared Euclidean distance (no root; the
+ *     order of neighbours is the same), CAGRA_IP is 0 - <x, q>, so that
+ *     smaller is closer for both.  Ties are ordered by smaller id.
+ */
+#ifndef CAGRA_HIP_H
+#define CAGRA_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CAGRA_L2 = 0,
+    CAGRA_IP = 1
+} cagra_metric;
+
+typedef enum {
+    CAGRA_OK = 0,
+    CAGRA_ERR_NULL_POINTER = -1,
+    CAGRA_ERR_BAD_SHAPE = -2,      /* N, dim, ld, B out of range or misaligned */
+    CAGRA_ERR_BAD_DEGREE = -3,     /* degree / init_degree not usable */
+    CAGRA_ERR_BAD_TOPK = -4,       /* k, itopk, search_width out of range */
+    CAGRA_ERR_BAD_OPTION = -5,     /* a cagra_search_opts field is not supported */
+    CAGRA_ERR_WORKSPACE = -6,      /* workspace missing, misaligned or too small */
+    CAGRA_ERR_HASH_CAPACITY = -7,  /* visited table cannot hold itopk + interval * width * degree at load 1/2 */
+    CAGRA_ERR_LAUNCH = -8          /* the HIP runtime refused a launch */
+} cagra_status;
+
+#define CAGRA_INVALID_ID 0xFFFFFFFFu
+
+/* Search tunables (Sec. IV-B, IV-C).  A zero-initialised struct means "all automatic". */
+typedef struct {
+    uint64_t seed;            /* seed of the step-0 random sampling (Sec. IV-A step 0) */
+    int32_t max_iterations;   /* I_max; 0 => 2 * ceil(itopk / search_width) + 32 */
+    int32_t mode;             /* 0 automatic (Sec. IV-C.3), 1 single workgroup per query, 2 several */
+    int32_t team_size;        /* lanes per distance computation: 0 automatic, else 4, 8, 16 or 32 (Sec. IV-B.1) */
+    int32_t hash_bits;        /* single mode: log2 of the LDS visited table, 0 automatic, else 8..13 (Sec. IV-B.3) */
+    int32_t reset_interval;   /* single mode: passes between table resets, 0 automatic (largest that fits) */
+    int32_t wg_per_query;     /* multi mode: workgroups per query, 0 => search_width */
+    int32_t reserved;
+    uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
+                                 flags (bit 0: stopped by I_max, bit 1: visited table overflowed) */
+} cagra_search_opts;
+
+/* ---- search (Sec. IV-A steps 0-3; Sec. IV-C.1 single, IV-C.2 multi) ------------------------ */
+
+/*
+ * For each of the B queries: random sampling of search_width * degree seeds,
+ * then passes of {top-M update, parent selection, neighbour expansion, distance
+ * of first-time candidates} until no entry of the top-M list is left
+ * unexpanded or I_max passes were made; the first k of the top-M list are
+ * written.  ids[B, k] / dists[B, k] come out ascending by (distance, id);
+ * if fewer than k nodes were reached the tail is (CAGRA_INVALID_ID, FLT_MAX).
+ * Requirements: 1 <= k <= itopk; single mode: itopk <= 512 and
+ * search_width * degree <= 256; multi mode: see cagra_search_opts.
+ * B == 0 is allowed and does nothing.
+ */
+int cagra_search(const uint32_t *graph, int64_t N, int32_t degree,
+                 const float *dataset, int32_t dim, int64_t ld, cagra_metric metric,
+                 const float *queries, int64_t B, int64_t ld_queries,
+                 int32_t k, int32_t itopk, int32_t search_width,
+                 const cagra_search_opts *opts /* host, may be NULL */,
+                 uint32_t *ids_out, float *dists_out,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_t k,
+                                    int32_t itopk, int32_t search_width,
+                                    const cagra_search_opts *opts /* host, may be NULL */);
+
+/* Mode the automatic rule of Sec. IV-C.3 picks (1 single, 2 multi) for a batch of B on the
+ * current device: multi when B is below the number of compute units or itopk above 512. */
+int cagra_search_auto_mode(int64_t B, int32_t itopk);
+
+/* ---- exhaustive search (Eq. 1) -------------------------------------------------------------- */
+
+/*
+ * The k nearest dataset rows of every query by computing all N distances.
+ * exclude_self != 0 treats query b as dataset row (self_offset + b) and leaves
+ * that row out (used for the initial k-NN graph, Sec. III-B.1).
+ * ids[B, k], dists[B, k] (dists may be NULL) ascending by (distance, id).
+ * Distances are accumulated one dimension after the other with fused
+ * multiply-adds, so the result does not depend on tiling.  k <= 512, k <= N.
+ */
+int cagra_exact_search(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                       const float *queries, int64_t B, int64_t ld_queries,
+                       int32_t k, int32_t exclude_self, int64_t self_offset,
+                       uint32_t *ids_out, float *dists_out /* may be NULL */,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t cagra_exact_search_workspace_bytes(int64_t N, int64_t B, int32_t k);
+
+/* ---- graph construction (Sec. III-B) -------------------------------------------------------- */
+
+/*
+ * dataset -> CAGRA graph of out-degree `degree`: exact k-NN graph of degree
+ * init_degree (0 => 2 * degree) with rows sorted by distance (Sec. III-B.1),
+ * rank-based reordering and pruning (Eq. 3), reversed graph, interleaved merge
+ * (Sec. III-B.2).  degree must be even, 2 <= degree <= init_degree <= 512,
+ * init_degree < N.
+ */
+int cagra_build(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                int32_t degree, int32_t init_degree,
+                uint32_t *graph_out /* [N, degree] */,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t cagra_build_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree);
+
+/*
+ * The optimisation alone (Sec. III-B.2): sorted initial graph knn[N, init_degree]
+ * -> graph_out[N, degree].  Integer work only, no dataset access.
+ * The intermediate results can be read back for stage-wise checks when the
+ * optional outputs are given: pruned[N, degree], reversed[N, degree] (unused
+ * slots CAGRA_INVALID_ID) and reversed_len[N].
+ */
+int cagra_optimize(const uint32_t *knn, int64_t N, int32_t init_degree, int32_t degree,
+                   uint32_t *graph_out,
+                   uint32_t *pruned_out /* may be NULL */,
+                   uint32_t *reversed_out /* may be NULL */,
+                   uint32_t *reversed_len_out /* may be NULL */,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t cagra_optimize_workspace_bytes(int64_t N, int32_t init_degree, int32_t degree);
+
+/* ---- misc ------------------------------------------------------------------------------------ */
+
+/* Text for a cagra_status value (static storage, never NULL). */
+const char *cagra_strerror(int code);
+
+/* Seed of slot `slot` of query `query` as drawn by step 0 (host function; lets a caller
+ * reproduce the random sampling of Sec. IV-A without running a search). */
+uint32_t cagra_seed_id(uint64_t seed, uint64_t query, uint64_t slot, uint64_t N);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAGRA_HIP_H */

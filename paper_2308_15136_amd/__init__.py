@@ -1,0 +1,225 @@
+"""MI355X-native CAGRA (graph build + batched greedy graph search).
+
+Thin binding over the C ABI of include/cagra_hip.h: the functions below only
+marshal arguments (device pointers of torch tensors, sizes, the current HIP
+stream) into libcagra_hip.so; every step of the method runs in that library's
+gfx950 kernels.  There is no CPU fallback: if the library is missing the calls
+raise.
+
+Node ids travel as torch.int32 tensors holding the uint32 bit patterns of the
+C ABI (ids are below 2^31, the invalid id 0xFFFFFFFF reads as -1).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcagra_hip.so")
+
+L2 = 0
+IP = 1
+INVALID_ID = -1  # 0xFFFFFFFF seen through int32
+
+_lib = None
+
+
+class CagraError(RuntimeError):
+    pass
+
+
+class _SearchOpts(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("max_iterations", C.c_int32), ("mode", C.c_int32),
+                ("team_size", C.c_int32), ("hash_bits", C.c_int32), ("reset_interval", C.c_int32),
+                ("wg_per_query", C.c_int32), ("reserved", C.c_int32), ("stats", C.c_void_p)]
+
+
+def load_library():
+    """Load libcagra_hip.so (built by paper_2308_15136_amd.build) and declare its ABI."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise CagraError(f"{LIB_PATH} is missing: run `python -m paper_2308_15136_amd.build` "
+                         "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    opts_p = C.POINTER(_SearchOpts)
+    lib.cagra_strerror.restype = C.c_char_p
+    lib.cagra_strerror.argtypes = [C.c_int]
+    lib.cagra_seed_id.restype = C.c_uint32
+    lib.cagra_seed_id.argtypes = [C.c_uint64] * 4
+    lib.cagra_search_auto_mode.restype = C.c_int
+    lib.cagra_search_auto_mode.argtypes = [i64, i32]
+    lib.cagra_search.restype = C.c_int
+    lib.cagra_search.argtypes = [vp, i64, i32, vp, i32, i64, C.c_int, vp, i64, i64, i32, i32, i32,
+                                 opts_p, vp, vp, vp, sz, vp]
+    lib.cagra_search_workspace_bytes.restype = sz
+    lib.cagra_search_workspace_bytes.argtypes = [i64, i32, i64, i32, i32, i32, opts_p]
+    lib.cagra_exact_search.restype = C.c_int
+    lib.cagra_exact_search.argtypes = [vp, i64, i32, i64, C.c_int, vp, i64, i64, i32, i32, i64,
+                                       vp, vp, vp, sz, vp]
+    lib.cagra_exact_search_workspace_bytes.restype = sz
+    lib.cagra_exact_search_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.cagra_build.restype = C.c_int
+    lib.cagra_build.argtypes = [vp, i64, i32, i64, C.c_int, i32, i32, vp, vp, sz, vp]
+    lib.cagra_build_workspace_bytes.restype = sz
+    lib.cagra_build_workspace_bytes.argtypes = [i64, i32, i32, i32]
+    lib.cagra_optimize.restype = C.c_int
+    lib.cagra_optimize.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.cagra_optimize_workspace_bytes.restype = sz
+    lib.cagra_optimize_workspace_bytes.argtypes = [i64, i32, i32]
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().cagra_strerror(code).decode()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise CagraError(f"{what}: {strerror(rc)} (code {rc})")
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dev_f32(t, name):
+    torch = _torch()
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.dim() == 2
+            and t.stride(1) == 1):
+        raise TypeError(f"{name} must be a 2-D float32 device tensor with unit inner stride")
+    return t
+
+
+def _dev_i32(t, name):
+    torch = _torch()
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous int32 device tensor")
+    return t
+
+
+def _workspace(nbytes: int, device):
+    torch = _torch()
+    # torch's caching allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _stream(device) -> int:
+    return int(_torch().cuda.current_stream(device).cuda_stream)
+
+
+def seed_id(seed: int, query: int, slot: int, n: int) -> int:
+    return int(load_library().cagra_seed_id(seed, query, slot, n))
+
+
+def auto_mode(batch: int, itopk: int) -> int:
+    return int(load_library().cagra_search_auto_mode(batch, itopk))
+
+
+@dataclass
+class SearchOptions:
+    seed: int = 0
+    max_iterations: int = 0
+    mode: int = 0
+    team_size: int = 0
+    hash_bits: int = 0
+    reset_interval: int = 0
+    wg_per_query: int = 0
+
+
+def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,
+           options: Optional[SearchOptions] = None, return_stats: bool = False,
+           out: Optional[Tuple] = None, workspace=None):
+    """Batched greedy graph search: (ids[B, k] int32, dists[B, k] float32[, stats[B, 4] int32])."""
+    torch = _torch()
+    lib = load_library()
+    graph = _dev_i32(graph, "graph")
+    dataset = _dev_f32(dataset, "dataset")
+    queries = _dev_f32(queries, "queries")
+    dev = dataset.device
+    B = queries.shape[0]
+    o = options or SearchOptions()
+    stats = torch.zeros((B, 4), dtype=torch.int32, device=dev) if return_stats else None
+    copts = _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
+                        o.wg_per_query, 0, stats.data_ptr() if stats is not None else None)
+    if out is None:
+        ids = torch.empty((B, k), dtype=torch.int32, device=dev)
+        dists = torch.empty((B, k), dtype=torch.float32, device=dev)
+    else:
+        ids, dists = out
+    N, degree = graph.shape
+    if workspace is None:
+        workspace = _workspace(lib.cagra_search_workspace_bytes(N, degree, B, k, itopk, search_width,
+                                                                C.byref(copts)), dev)
+    rc = lib.cagra_search(graph.data_ptr(), N, degree, dataset.data_ptr(), dataset.shape[1],
+                          dataset.stride(0), metric, queries.data_ptr(), B, queries.stride(0),
+                          k, itopk, search_width, C.byref(copts), ids.data_ptr(), dists.data_ptr(),
+                          workspace.data_ptr(), workspace.numel(), _stream(dev))
+    _check(rc, "cagra_search")
+    return (ids, dists, stats) if return_stats else (ids, dists)
+
+
+def exact_search(dataset, queries, k: int, metric: int = L2, exclude_self: bool = False,
+                 self_offset: int = 0, return_dists: bool = True):
+    """Exhaustive k nearest neighbours (Eq. 1): (ids[B, k] int32, dists[B, k] float32)."""
+    torch = _torch()
+    lib = load_library()
+    dataset = _dev_f32(dataset, "dataset")
+    queries = _dev_f32(queries, "queries")
+    dev = dataset.device
+    B, N = queries.shape[0], dataset.shape[0]
+    ids = torch.empty((B, k), dtype=torch.int32, device=dev)
+    dists = torch.empty((B, k), dtype=torch.float32, device=dev) if return_dists else None
+    ws = _workspace(lib.cagra_exact_search_workspace_bytes(N, B, k), dev)
+    rc = lib.cagra_exact_search(dataset.data_ptr(), N, dataset.shape[1], dataset.stride(0), metric,
+                                queries.data_ptr(), B, queries.stride(0), k, int(exclude_self),
+                                self_offset, ids.data_ptr(),
+                                dists.data_ptr() if dists is not None else None,
+                                ws.data_ptr(), ws.numel(), _stream(dev))
+    _check(rc, "cagra_exact_search")
+    return (ids, dists) if return_dists else ids
+
+
+def build(dataset, degree: int, init_degree: int = 0, metric: int = L2):
+    """dataset[N, dim] -> CAGRA graph[N, degree] (int32 tensor)."""
+    torch = _torch()
+    lib = load_library()
+    dataset = _dev_f32(dataset, "dataset")
+    dev = dataset.device
+    N, dim = dataset.shape
+    graph = torch.empty((N, degree), dtype=torch.int32, device=dev)
+    ws = _workspace(lib.cagra_build_workspace_bytes(N, dim, degree, init_degree), dev)
+    rc = lib.cagra_build(dataset.data_ptr(), N, dim, dataset.stride(0), metric, degree, init_degree,
+                         graph.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev))
+    _check(rc, "cagra_build")
+    return graph
+
+
+def optimize(knn, degree: int, return_stages: bool = False):
+    """Sorted k-NN graph[N, init_degree] -> CAGRA graph[N, degree]; optionally also the
+    pruned graph, the reversed graph and its list lengths."""
+    torch = _torch()
+    lib = load_library()
+    knn = _dev_i32(knn, "knn")
+    dev = knn.device
+    N, init_degree = knn.shape
+    graph = torch.empty((N, degree), dtype=torch.int32, device=dev)
+    pruned = rev = rlen = None
+    if return_stages:
+        pruned = torch.empty((N, degree), dtype=torch.int32, device=dev)
+        rev = torch.empty((N, degree), dtype=torch.int32, device=dev)
+        rlen = torch.empty((N,), dtype=torch.int32, device=dev)
+    ws = _workspace(lib.cagra_optimize_workspace_bytes(N, init_degree, degree), dev)
+    rc = lib.cagra_optimize(knn.data_ptr(), N, init_degree, degree, graph.data_ptr(),
+                            pruned.data_ptr() if pruned is not None else None,
+                            rev.data_ptr() if rev is not None else None,
+                            rlen.data_ptr() if rlen is not None else None,
+                            ws.data_ptr(), ws.numel(), _stream(dev))
+    _check(rc, "cagra_optimize")
+    return (graph, pruned, rev, rlen) if return_stages else graph

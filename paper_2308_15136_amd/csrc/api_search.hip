@@ -1,0 +1,186 @@
+// C ABI: search entry points.  Host-side validation, automatic parameters and launch
+// geometry; every step of the search itself runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <mutex>
+
+#include "../../include/cagra_hip.h"
+#include "device_util.h"
+#include "search_params.h"
+
+namespace cagra {
+
+struct DeviceInfo {
+    int cus = 0;
+    size_t lds_per_cu = 0;
+};
+
+// Compute-unit count and LDS size of the current device, asked once per device.
+const DeviceInfo &device_info()
+{
+    static DeviceInfo info[64];
+    static std::once_flag once[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    std::call_once(once[dev], [dev]() {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+            info[dev].cus = prop.multiProcessorCount;
+            info[dev].lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+        }
+        if (info[dev].cus <= 0) info[dev].cus = 256;
+        if (info[dev].lds_per_cu < 65536) info[dev].lds_per_cu = 65536;
+    });
+    return info[dev];
+}
+
+static int auto_max_iterations(int itopk, int width) { return 2 * ((itopk + width - 1) / width) + 32; }
+
+// Smallest team whose lanes cover a row in at most four 16-byte loads each (Sec. IV-B.1).
+static int auto_team(int dim)
+{
+    int chunks = dim / 4;
+    for (int team = 4; team <= 32; team *= 2)
+        if ((chunks + team - 1) / team <= 4) return team;
+    return 32;
+}
+
+struct SinglePlan {
+    int mr, cr, hash_bits, reset_interval, team_log2, max_iterations;
+    size_t smem;
+    int off_query, off_newid, off_newdist, off_parents;
+};
+
+static int plan_single(int degree, int dim, int itopk, int width, const cagra_search_opts &o, SinglePlan &pl)
+{
+    if (itopk > 512) return CAGRA_ERR_BAD_TOPK;
+    const int n_cand = width * degree;
+    if (n_cand > 256) return CAGRA_ERR_BAD_TOPK;
+    int mr = (itopk + 63) / 64;
+    pl.mr = mr <= 1 ? 1 : mr <= 2 ? 2 : mr <= 4 ? 4 : 8;
+    pl.cr = n_cand <= 64 ? 1 : n_cand <= 128 ? 2 : 4;
+
+    int team = o.team_size == 0 ? auto_team(dim) : o.team_size;
+    if (team != 4 && team != 8 && team != 16 && team != 32) return CAGRA_ERR_BAD_OPTION;
+    pl.team_log2 = team == 4 ? 2 : team == 8 ? 3 : team == 16 ? 4 : 5;
+
+    if (o.max_iterations < 0) return CAGRA_ERR_BAD_OPTION;
+    pl.max_iterations = o.max_iterations == 0 ? auto_max_iterations(itopk, width) : o.max_iterations;
+
+    // visited table: must hold itopk + interval * n_cand ids at load <= 1/2 (Sec. IV-B.3)
+    int bits = o.hash_bits;
+    if (bits == 0) {
+        bits = 11;
+        while (bits < 13 && (1 << (bits - 1)) < itopk + n_cand) ++bits;
+    }
+    if (bits < 8 || bits > 13) return CAGRA_ERR_BAD_OPTION;
+    const int capacity = 1 << (bits - 1);
+    if (o.reset_interval < 0) return CAGRA_ERR_BAD_OPTION;
+    int interval = o.reset_interval;
+    if (interval == 0) interval = (capacity - itopk) / n_cand;
+    if (interval < 1 || itopk + (int64_t)interval * n_cand > capacity) return CAGRA_ERR_HASH_CAPACITY;
+    pl.hash_bits = bits;
+    pl.reset_interval = interval;
+
+    size_t off = (size_t)4 << bits;
+    pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
+    pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
+    pl.off_newdist = (int)off;    off += (size_t)4 * 64 * pl.cr;
+    pl.off_parents = (int)off;    off += (size_t)4 * 64;
+    pl.smem = off;
+    if (pl.smem > 64 * 1024) return CAGRA_ERR_BAD_SHAPE;  // dim too large for the LDS query copy
+    return CAGRA_OK;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace cagra
+
+using namespace cagra;
+
+extern "C" {
+
+const char *cagra_strerror(int code)
+{
+    switch (code) {
+        case CAGRA_OK: return "success";
+        case CAGRA_ERR_NULL_POINTER: return "a required pointer is NULL";
+        case CAGRA_ERR_BAD_SHAPE: return "N, dim, ld or B out of range, or rows not 16-byte aligned";
+        case CAGRA_ERR_BAD_DEGREE: return "degree / init_degree not usable";
+        case CAGRA_ERR_BAD_TOPK: return "k, itopk or search_width out of range";
+        case CAGRA_ERR_BAD_OPTION: return "unsupported value in cagra_search_opts";
+        case CAGRA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case CAGRA_ERR_HASH_CAPACITY: return "visited table too small for itopk + interval * width * degree";
+        case CAGRA_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown cagra status";
+}
+
+uint32_t cagra_seed_id(uint64_t seed, uint64_t query, uint64_t slot, uint64_t N)
+{
+    return seed_slot_id(seed_query_hash(seed, query), slot, N);
+}
+
+int cagra_search_auto_mode(int64_t B, int32_t itopk)
+{
+    return (B < device_info().cus || itopk > 512) ? 2 : 1;
+}
+
+size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_t k, int32_t itopk,
+                                    int32_t search_width, const cagra_search_opts *opts)
+{
+    (void)N; (void)degree; (void)B; (void)k; (void)itopk; (void)search_width; (void)opts;
+    return 256;  // the persistent-scheduling counter
+}
+
+int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *dataset, int32_t dim,
+                 int64_t ld, cagra_metric metric, const float *queries, int64_t B, int64_t ld_queries,
+                 int32_t k, int32_t itopk, int32_t search_width, const cagra_search_opts *opts,
+                 uint32_t *ids_out, float *dists_out, void *workspace, size_t workspace_bytes,
+                 void *hip_stream)
+{
+    cagra_search_opts o = {};
+    if (opts) o = *opts;
+    if (!graph || !dataset) return CAGRA_ERR_NULL_POINTER;
+    if (B > 0 && (!queries || !ids_out || !dists_out)) return CAGRA_ERR_NULL_POINTER;
+    if (N < 1 || N > 0x7FFFFFFFll || dim < 4 || (dim & 3) || ld < dim || (ld & 3) || B < 0 ||
+        B > 0x7FFFFFFFll || ld_queries < dim)
+        return CAGRA_ERR_BAD_SHAPE;
+    if (((uintptr_t)dataset & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
+    if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
+    if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
+    if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
+    if (o.mode < 0 || o.mode > 2) return CAGRA_ERR_BAD_OPTION;
+    if (o.mode == 2) return CAGRA_ERR_BAD_OPTION;  // multi-workgroup search not built yet
+    SinglePlan pl;
+    int rc = plan_single(degree, dim, itopk, search_width, o, pl);
+    if (rc != CAGRA_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+        workspace_bytes < cagra_search_workspace_bytes(N, degree, B, k, itopk, search_width, opts))
+        return CAGRA_ERR_WORKSPACE;
+    if (B == 0) return CAGRA_OK;
+
+    SingleParams P;
+    P.graph = graph; P.dataset = dataset; P.queries = queries;
+    P.ids_out = ids_out; P.dists_out = dists_out; P.stats = o.stats;
+    P.counter = static_cast<uint32_t *>(workspace);
+    P.N = N; P.B = B; P.ld = ld; P.ld_queries = ld_queries; P.seed = o.seed;
+    P.degree = degree; P.dim = dim; P.metric = (int)metric;
+    P.k = k; P.itopk = itopk; P.search_width = search_width;
+    P.max_iterations = pl.max_iterations; P.reset_interval = pl.reset_interval;
+    P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
+    P.off_query = pl.off_query; P.off_newid = pl.off_newid;
+    P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
+
+    const DeviceInfo &di = device_info();
+    // persistent grid: as many single-wavefront workgroups as fit (LDS-bound, at most 16 per CU)
+    int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
+    if (per_cu < 1) per_cu = 1;
+    int grid = (int)std::min<int64_t>(B, (int64_t)per_cu * di.cus);
+    hipError_t e = launch_search_single(P, pl.mr, pl.cr, grid, pl.smem, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+}
+
+}  // extern "C"

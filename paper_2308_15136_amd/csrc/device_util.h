@@ -1,0 +1,55 @@
+// Device-side helpers shared by the gfx950 kernels of this library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cagra {
+
+constexpr int kWave = 64;                      // CDNA wavefront width
+constexpr uint32_t kInvalidId = 0xFFFFFFFFu;
+constexpr uint32_t kFltMaxBits = 0x7F7FFFFFu;  // bit pattern of FLT_MAX
+
+// fp32 -> unsigned integer with the same order (and back).  -0 is folded into
+// +0 first so that equal distances always have equal keys.
+__device__ __forceinline__ uint32_t f32_to_ordered(float f)
+{
+    uint32_t u = __float_as_uint(f + 0.0f);
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_f32(uint32_t u)
+{
+    return __uint_as_float(u ^ (((u >> 31) - 1u) | 0x80000000u));
+}
+constexpr uint32_t kDummyHi = kFltMaxBits ^ 0x80000000u;  // ordered(FLT_MAX)
+
+// SplitMix64 output function; the step-0 seed of (query, slot) is two rounds of
+// it, scaled to [0, N) by a multiply-shift (Sec. IV-A step 0 only asks for "a
+// pseudo-random number generator").
+__host__ __device__ __forceinline__ uint64_t splitmix_fin(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__host__ __device__ __forceinline__ uint64_t seed_query_hash(uint64_t seed, uint64_t query)
+{
+    return splitmix_fin(seed + 0x9E3779B97F4A7C15ull * (query + 1));
+}
+__host__ __device__ __forceinline__ uint32_t seed_slot_id(uint64_t qhash, uint64_t slot, uint64_t N)
+{
+    uint64_t h = splitmix_fin(qhash + 0x9E3779B97F4A7C15ull * (slot + 1));
+    return (uint32_t)(((h >> 32) * N) >> 32);
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+__device__ __forceinline__ uint32_t shfl_xor_u32(uint32_t v, int mask)
+{
+    return (uint32_t)__shfl_xor((int)v, mask, kWave);
+}
+__device__ __forceinline__ uint32_t shfl_u32(uint32_t v, int src)
+{
+    return (uint32_t)__shfl((int)v, src, kWave);
+}
+
+}  // namespace cagra
