@@ -1,12 +1,175 @@
-// C ABI: build entry points (placeholder until the build kernels land).
+// C ABI: exhaustive search, graph optimisation and the whole build.  Host-side validation
+// and workspace carving only.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+
 #include "../../include/cagra_hip.h"
+#include "build_kernels.h"
+
+namespace cagra {
+
+static size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Rows of the distance block computed per pass: as many as fit in about 8 GiB.
+static int64_t exact_block_rows(int64_t N, int64_t B)
+{
+    const int64_t pitch = exact_search_pitch(N);
+    int64_t rows = ((int64_t)8 << 30) / (pitch * 4);
+    rows = std::max<int64_t>(128, rows / 128 * 128);
+    return std::min<int64_t>(rows, std::max<int64_t>(B, 1));
+}
+
+struct Carver {
+    unsigned char *p;
+    size_t used = 0;
+    explicit Carver(void *base) : p(static_cast<unsigned char *>(base)) {}
+    template <typename T> T *take(size_t n)
+    {
+        T *r = p ? reinterpret_cast<T *>(p + used) : nullptr;
+        used += up256(n * sizeof(T));
+        return r;
+    }
+};
+
+struct OptimizeCarve {
+    OptimizeScratch s;
+    uint32_t *pruned, *rev, *rev_len;
+    size_t bytes;
+};
+
+static OptimizeCarve carve_optimize(void *base, int64_t N, int degree)
+{
+    Carver c(base);
+    OptimizeCarve o;
+    o.s.indeg = c.take<uint32_t>(N);
+    o.s.cursor = c.take<uint32_t>(N);
+    o.s.offset = c.take<uint64_t>(N);
+    o.s.block_sum = c.take<uint64_t>((N + 1023) / 1024);
+    o.s.bucket = c.take<uint64_t>((size_t)N * degree);
+    o.pruned = c.take<uint32_t>((size_t)N * degree);
+    o.rev = c.take<uint32_t>((size_t)N * degree);
+    o.rev_len = c.take<uint32_t>(N);
+    o.bytes = c.used;
+    return o;
+}
+
+static int check_degrees(int64_t N, int32_t degree, int32_t init_degree)
+{
+    if (degree < 2 || (degree & 1) || degree > 256) return CAGRA_ERR_BAD_DEGREE;
+    if (init_degree < degree || init_degree > 512 || init_degree >= N) return CAGRA_ERR_BAD_DEGREE;
+    return CAGRA_OK;
+}
+
+static int check_matrix(const float *p, int64_t rows, int32_t dim, int64_t ld)
+{
+    if (rows < 0 || rows > 0x7FFFFFFFll || dim < 4 || (dim & 3) || ld < dim || (ld & 3)) return CAGRA_ERR_BAD_SHAPE;
+    if (((uintptr_t)p & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
+    return CAGRA_OK;
+}
+
+}  // namespace cagra
+
+using namespace cagra;
 
 extern "C" {
-int cagra_exact_search(const float *, int64_t, int32_t, int64_t, cagra_metric, const float *, int64_t, int64_t,
-                       int32_t, int32_t, int64_t, uint32_t *, float *, void *, size_t, void *) { return CAGRA_ERR_LAUNCH; }
-size_t cagra_exact_search_workspace_bytes(int64_t, int64_t, int32_t) { return 256; }
-int cagra_build(const float *, int64_t, int32_t, int64_t, cagra_metric, int32_t, int32_t, uint32_t *, void *, size_t, void *) { return CAGRA_ERR_LAUNCH; }
-size_t cagra_build_workspace_bytes(int64_t, int32_t, int32_t, int32_t) { return 256; }
-int cagra_optimize(const uint32_t *, int64_t, int32_t, int32_t, uint32_t *, uint32_t *, uint32_t *, uint32_t *, void *, size_t, void *) { return CAGRA_ERR_LAUNCH; }
-size_t cagra_optimize_workspace_bytes(int64_t, int32_t, int32_t) { return 256; }
+
+size_t cagra_exact_search_workspace_bytes(int64_t N, int64_t B, int32_t k)
+{
+    (void)k;
+    if (N < 1 || B < 0) return 256;
+    return up256((size_t)exact_block_rows(N, B) * (size_t)exact_search_pitch(N) * sizeof(float));
 }
+
+int cagra_exact_search(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                       const float *queries, int64_t B, int64_t ld_queries, int32_t k,
+                       int32_t exclude_self, int64_t self_offset, uint32_t *ids_out, float *dists_out,
+                       void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!dataset) return CAGRA_ERR_NULL_POINTER;
+    if (B > 0 && (!queries || !ids_out)) return CAGRA_ERR_NULL_POINTER;
+    if (N < 1) return CAGRA_ERR_BAD_SHAPE;
+    int rc = check_matrix(dataset, N, dim, ld);
+    if (rc == CAGRA_OK) rc = check_matrix(queries, B, dim, ld_queries);
+    if (rc != CAGRA_OK) return rc;
+    if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
+    if (k < 1 || k > 512 || k > N) return CAGRA_ERR_BAD_TOPK;
+    if (exclude_self && (self_offset < 0 || self_offset + B > N)) return CAGRA_ERR_BAD_SHAPE;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+        workspace_bytes < cagra_exact_search_workspace_bytes(N, B, k))
+        return CAGRA_ERR_WORKSPACE;
+    if (B == 0) return CAGRA_OK;
+    hipError_t e = launch_exact_search(dataset, N, dim, ld, (int)metric, queries, B, ld_queries, k,
+                                       exclude_self ? 1 : 0, self_offset, ids_out, dists_out,
+                                       static_cast<float *>(workspace), exact_block_rows(N, B),
+                                       static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+}
+
+size_t cagra_optimize_workspace_bytes(int64_t N, int32_t init_degree, int32_t degree)
+{
+    (void)init_degree;
+    if (N < 1 || degree < 1) return 256;
+    return carve_optimize(nullptr, N, degree).bytes;
+}
+
+int cagra_optimize(const uint32_t *knn, int64_t N, int32_t init_degree, int32_t degree,
+                   uint32_t *graph_out, uint32_t *pruned_out, uint32_t *reversed_out,
+                   uint32_t *reversed_len_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!knn || !graph_out) return CAGRA_ERR_NULL_POINTER;
+    if (N < 2 || N > 0x7FFFFFFFll) return CAGRA_ERR_BAD_SHAPE;
+    int rc = check_degrees(N, degree, init_degree);
+    if (rc != CAGRA_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+        workspace_bytes < cagra_optimize_workspace_bytes(N, init_degree, degree))
+        return CAGRA_ERR_WORKSPACE;
+    OptimizeCarve c = carve_optimize(workspace, N, degree);
+    hipError_t e = launch_optimize(knn, N, init_degree, degree, graph_out,
+                                   pruned_out ? pruned_out : c.pruned,
+                                   reversed_out ? reversed_out : c.rev,
+                                   reversed_len_out ? reversed_len_out : c.rev_len, c.s,
+                                   static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+}
+
+size_t cagra_build_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree)
+{
+    (void)dim;
+    if (init_degree == 0) init_degree = 2 * degree;
+    if (N < 1 || degree < 1) return 256;
+    const size_t knn = up256((size_t)N * init_degree * sizeof(uint32_t));
+    // the distance block is dead once the k-NN graph exists, so the optimisation reuses its space
+    return knn + std::max(cagra_exact_search_workspace_bytes(N, N, init_degree),
+                          cagra_optimize_workspace_bytes(N, init_degree, degree));
+}
+
+int cagra_build(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                int32_t degree, int32_t init_degree, uint32_t *graph_out, void *workspace,
+                size_t workspace_bytes, void *hip_stream)
+{
+    if (init_degree == 0) init_degree = 2 * degree;
+    if (!dataset || !graph_out) return CAGRA_ERR_NULL_POINTER;
+    if (N < 2) return CAGRA_ERR_BAD_SHAPE;
+    int rc = check_matrix(dataset, N, dim, ld);
+    if (rc != CAGRA_OK) return rc;
+    if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
+    rc = check_degrees(N, degree, init_degree);
+    if (rc != CAGRA_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+        workspace_bytes < cagra_build_workspace_bytes(N, dim, degree, init_degree))
+        return CAGRA_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint32_t *knn = static_cast<uint32_t *>(workspace);
+    unsigned char *rest = static_cast<unsigned char *>(workspace) + up256((size_t)N * init_degree * sizeof(uint32_t));
+    hipError_t e = launch_exact_search(dataset, N, dim, ld, (int)metric, dataset, N, ld, init_degree, 1, 0,
+                                       knn, nullptr, reinterpret_cast<float *>(rest),
+                                       exact_block_rows(N, N), stream);
+    if (e != hipSuccess) return CAGRA_ERR_LAUNCH;
+    OptimizeCarve c = carve_optimize(rest, N, degree);
+    e = launch_optimize(knn, N, init_degree, degree, graph_out, c.pruned, c.rev, c.rev_len, c.s, stream);
+    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+}
+
+}  // extern "C"

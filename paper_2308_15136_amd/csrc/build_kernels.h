@@ -1,0 +1,27 @@
+// Host-callable launchers of the build-side kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cagra {
+
+// Exhaustive search: `scratch` holds block_rows x exact_search_pitch(N) floats.
+int64_t exact_search_pitch(int64_t N);
+hipError_t launch_exact_search(const float *X, int64_t N, int dim, int64_t ldX, int metric,
+                               const float *Q, int64_t B, int64_t ldQ, int k, int exclude_self,
+                               int64_t self_offset, uint32_t *ids, float *dists, float *scratch,
+                               int64_t block_rows, hipStream_t stream);
+
+struct OptimizeScratch {
+    uint32_t *indeg;      // [N]
+    uint32_t *cursor;     // [N]
+    uint64_t *offset;     // [N]
+    uint64_t *block_sum;  // [ceil(N / 1024)]
+    uint64_t *bucket;     // [N * degree]
+};
+
+hipError_t launch_optimize(const uint32_t *knn, int64_t N, int d_init, int d, uint32_t *graph,
+                           uint32_t *pruned, uint32_t *rev, uint32_t *rev_len,
+                           const OptimizeScratch &s, hipStream_t stream);
+
+}  // namespace cagra

@@ -1,0 +1,115 @@
+"""GPU parity of the build side (exhaustive search, k-NN graph, optimisation, whole build)
+against the CPU oracle, through the C ABI.  Everything here is integer or decided by a
+fixed-order fp32 accumulation, so the bar is bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2308_15136_amd import datagen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cagra():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2308_15136_amd as m
+    m.load_library()
+    return m
+
+
+def _dev(a):
+    import torch
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("name,n,nq,k", [
+    ("tiny", 10_000, 100, 10),
+    ("tiny", 10_000, 37, 1),
+    ("deep1m", 5_003, 129, 100),       # N and B off the tile size
+    ("glove200", 3_000, 64, 512),      # inner product, largest k
+    ("sift1m", 4_097, 50, 64),
+])
+def test_exact_search_bit_exact(cagra, name, n, nq, k):
+    print(f"case exact {name} n={n} nq={nq} k={k}", flush=True)
+    w = datagen.workload(name, n=n, n_queries=nq)
+    ids, dists = cagra.exact_search(_dev(w.base), _dev(w.queries), k, w.metric)
+    ref_ids, ref_d = oracle.exact_search(w.base, w.queries, k, w.metric)
+    np.testing.assert_array_equal(_u32(ids), ref_ids)
+    np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
+
+
+@pytest.mark.parametrize("name,n,d_init", [("tiny", 10_000, 64), ("glove200", 2_500, 128), ("deep1m", 1_000, 512)])
+def test_knn_graph_bit_exact(cagra, name, n, d_init):
+    print(f"case knn {name} n={n} d_init={d_init}", flush=True)
+    w = datagen.workload(name, n=n, n_queries=1)
+    b = _dev(w.base)
+    ids = cagra.exact_search(b, b, d_init, w.metric, exclude_self=True, return_dists=False)
+    np.testing.assert_array_equal(_u32(ids), oracle.knn_graph(w.base, d_init, w.metric))
+    # a slice of rows addressed through self_offset
+    part = cagra.exact_search(b, b[100:300], d_init, w.metric, exclude_self=True, self_offset=100,
+                              return_dists=False)
+    np.testing.assert_array_equal(_u32(part), _u32(ids)[100:300])
+
+
+def _stagewise(cagra, g0, d):
+    graph, pruned, rev, rlen = cagra.optimize(_dev(g0), d, return_stages=True)
+    cnt = oracle.detour_count(g0)
+    o_pr = oracle.prune(g0, cnt, d)
+    o_rev, o_len = oracle.reverse(o_pr)
+    o_graph = oracle.merge(o_pr, o_rev, o_len)
+    np.testing.assert_array_equal(_u32(pruned), o_pr)
+    np.testing.assert_array_equal(_u32(rlen), o_len)
+    np.testing.assert_array_equal(_u32(rev), o_rev)
+    np.testing.assert_array_equal(_u32(graph), o_graph)
+
+
+@pytest.mark.parametrize("name,n,d", [("tiny", 10_000, 32), ("sift1m", 6_000, 64), ("deep1m", 3_000, 2),
+                                      ("glove200", 1_500, 128)])
+def test_optimize_stagewise_bit_exact(cagra, name, n, d):
+    print(f"case optimize {name} n={n} d={d}", flush=True)
+    w = datagen.workload(name, n=n, n_queries=1)
+    _stagewise(cagra, oracle.knn_graph(w.base, 2 * d, w.metric), d)
+
+
+def test_optimize_with_hub_nodes(cagra):
+    # node 0 is everybody's first neighbour, node 1 everybody's second: in-degrees of N-1,
+    # far beyond the reversed list's cap and the select kernel's pool.
+    n, d_init, d = 5_000, 16, 8
+    rng = np.random.default_rng(3)
+    g0 = np.empty((n, d_init), np.uint32)
+    for x in range(n):
+        head = [v for v in (0, 1) if v != x]
+        pool = np.setdiff1d(rng.choice(n, size=d_init + 3, replace=False), np.array(head + [x]))
+        g0[x] = head + pool[: d_init - len(head)].tolist()
+    print("case optimize hubs", flush=True)
+    _stagewise(cagra, g0, d)
+
+
+@pytest.mark.parametrize("name,n,d,d_init", [("tiny", 10_000, 32, 0), ("sift1m", 20_000, 64, 0),
+                                             ("glove200", 4_000, 16, 48)])
+def test_build_bit_exact(cagra, name, n, d, d_init):
+    print(f"case build {name} n={n} d={d}", flush=True)
+    w = datagen.workload(name, n=n, n_queries=1)
+    g = cagra.build(_dev(w.base), d, d_init, w.metric)
+    np.testing.assert_array_equal(_u32(g), oracle.build(w.base, d, d_init, w.metric))
+
+
+def test_build_rejections(cagra):
+    w = datagen.workload("tiny", n=500, n_queries=1)
+    b = _dev(w.base)
+    for d, di in [(7, 14), (0, 0), (32, 16), (300, 600), (250, 512 + 2)]:
+        with pytest.raises(cagra.CagraError):
+            cagra.build(b, d, di)
+    with pytest.raises(cagra.CagraError):
+        cagra.exact_search(b, b, 513)
+    with pytest.raises(cagra.CagraError):
+        cagra.build(b[:, :30], 8, 16)          # dim not a multiple of 4
