@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the CAGRA search hot path on one MI355X.
+
+A "step" is one pass of the whole hot path -- the single-workgroup search of the full
+query batch, steps 0-3 of Sec. IV-A until convergence -- over the large-batch workload
+(1M x 128 integer-valued fp32 rows, 10,000 queries, degree-64 graph, k = 10), with
+dataset, graph and queries already resident in HBM.  The graph is built once, untimed,
+by the library's own build; the exact neighbours for recall (Eq. 2) come from the
+library's exhaustive search.  itopk is swept and the timed steps use the smallest itopk
+whose recall@10 reaches the target (0.95).
+
+Prints ONE JSON line (see the keys below).  `roofline` prices the search kernel against
+the HBM peak with the bytes the algorithm has to move (dataset rows of first-time
+candidates, graph rows of parents, queries, results), counted inside the kernel.
+`cpu_baseline` times the CPU oracle on a sample of the same queries with the same graph.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+TARGET_RECALL = 0.95
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def recall_at_k(found: np.ndarray, truth: np.ndarray) -> float:
+    hit = 0
+    for f, t in zip(found, truth):
+        hit += len(np.intersect1d(f, t, assume_unique=False))
+    return hit / float(truth.size)
+
+
+def algorithmic_bytes(stats: np.ndarray, dim: int, degree: int, k: int) -> dict:
+    n_dist = int(stats[:, 2].astype(np.int64).sum())
+    n_parent = int(stats[:, 1].astype(np.int64).sum())
+    B = stats.shape[0]
+    vec = n_dist * dim * 4
+    total = vec + n_parent * degree * 4 + B * dim * 4 + B * k * 8
+    return {"vector_bytes": vec, "total_bytes": total, "n_dist": n_dist, "n_parent": n_parent,
+            "iterations_mean": float(stats[:, 0].mean()), "hit_cap": int((stats[:, 3] & 1).sum())}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="sift1m")
+    ap.add_argument("--n", type=int, default=0, help="shrink the base set (debugging only)")
+    ap.add_argument("--queries", type=int, default=0)
+    ap.add_argument("--itopk", type=int, default=0, help="skip the sweep and time this itopk")
+    ap.add_argument("--cpu-sample", type=int, default=2000, help="queries given to the CPU oracle")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch from rocprofv3 counters, copied into roofline.traffic")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; queries are independent, so more GPUs would "
+            "each take a slice of the batch, but no multi-GPU path is part of it.")
+        return 2
+
+    import torch
+    import paper_2308_15136_amd as cagra
+    from paper_2308_15136_amd import datagen
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the search has no CPU fallback")
+        return 1
+    cagra.load_library()
+    dev = torch.device("cuda:0")
+
+    t0 = time.time()
+    w = datagen.workload(args.workload, n=args.n or None, n_queries=args.queries or None)
+    N, dim = w.base.shape
+    B = w.queries.shape[0]
+    log(f"[bench] workload {w.name}: base {N}x{dim}, {B} queries, degree {w.degree}, "
+        f"generated in {time.time() - t0:.1f}s")
+    base = torch.from_numpy(w.base).to(dev)
+    queries = torch.from_numpy(w.queries).to(dev)
+
+    t0 = time.time()
+    graph = cagra.build(base, w.degree, w.init_degree, w.metric)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    log(f"[bench] graph built on the GPU in {build_s:.1f}s")
+
+    t0 = time.time()
+    gt = cagra.exact_search(base, queries, w.k, w.metric, return_dists=False)
+    torch.cuda.synchronize()
+    gt_np = gt.cpu().numpy().view(np.uint32)
+    log(f"[bench] exact neighbours in {time.time() - t0:.1f}s")
+
+    opts = cagra.SearchOptions(seed=20230815, mode=1)
+    ws = torch.empty(4096, dtype=torch.uint8, device=dev)
+    ids = torch.empty((B, w.k), dtype=torch.int32, device=dev)
+    dists = torch.empty((B, w.k), dtype=torch.float32, device=dev)
+
+    def run(itopk, stats=False):
+        return cagra.search(graph, base, queries, w.k, itopk, w.search_width, w.metric, opts,
+                            return_stats=stats, out=(ids, dists), workspace=ws)
+
+    def timed(itopk, steps, warmup):
+        for _ in range(warmup):
+            run(itopk)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_start = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            run(itopk)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t_start) * 1e3 / steps
+        return wall_ms, e0.elapsed_time(e1) / steps
+
+    # ---- sweep itopk: (recall, QPS) pairs ----------------------------------------------------
+    sweep = []
+    sweep_list = (args.itopk,) if args.itopk else w.itopk
+    for M in sweep_list:
+        _, _, st = run(M, stats=True)
+        torch.cuda.synchronize()
+        rec = recall_at_k(ids.cpu().numpy().view(np.uint32), gt_np)
+        wall_ms, dev_ms = timed(M, 5, 2)
+        ab = algorithmic_bytes(st.cpu().numpy().view(np.uint32), dim, w.degree, w.k)
+        sweep.append({"itopk": M, "recall": round(rec, 5), "qps": round(B / (wall_ms * 1e-3), 1),
+                      "kernel_ms": round(dev_ms, 4),
+                      "vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
+                      "iterations": round(ab["iterations_mean"], 2),
+                      "n_dist_per_query": round(ab["n_dist"] / B, 1)})
+        log(f"[bench] itopk {M}: recall@{w.k} {rec:.4f}  {sweep[-1]['qps']:.0f} QPS  "
+            f"{sweep[-1]['vector_GBs']:.0f} GB/s gathered")
+    ok = [s for s in sweep if s["recall"] >= TARGET_RECALL]
+    chosen = ok[0] if ok else sweep[-1]
+    M = chosen["itopk"]
+    qps_at_target = None
+    idx = sweep.index(chosen)
+    if ok and idx > 0 and sweep[idx - 1]["recall"] < TARGET_RECALL:
+        lo, hi = sweep[idx - 1], chosen
+        f = (TARGET_RECALL - lo["recall"]) / (hi["recall"] - lo["recall"])
+        qps_at_target = lo["qps"] + f * (hi["qps"] - lo["qps"])
+
+    # ---- the timed region ---------------------------------------------------------------------
+    _, _, st = run(M, stats=True)
+    torch.cuda.synchronize()
+    st_np = st.cpu().numpy().view(np.uint32)
+    ab = algorithmic_bytes(st_np, dim, w.degree, w.k)
+    gpu_ids = ids.cpu().numpy().view(np.uint32).copy()
+    gpu_d = dists.cpu().numpy().copy()
+    rec = recall_at_k(gpu_ids, gt_np)
+    wall_ms, dev_ms = timed(M, args.steps, args.warmup)
+    value = B / (wall_ms * 1e-3)
+    achieved = ab["total_bytes"] / (dev_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "QPS at recall@10>=0.95 (1Mx128, batch 10k)", "value": round(value, 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={N} dim={dim} fp32 integer-valued 0..255, B={B}, "
+                               f"degree={w.degree} (init {w.init_degree}), k={w.k}, itopk={M}, "
+                               f"search_width={w.search_width}, single-workgroup mode",
+                   "itopk": M, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
+                   "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
+                   "graph_build_s": round(build_s, 2)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": args.traffic_bytes,
+                     "kernel": "search_single_kernel", "kernel_ms": round(dev_ms, 4),
+                     "algorithmic_bytes_per_launch": ab["total_bytes"],
+                     "gathered_vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
+                     "n_dist_per_query": round(ab["n_dist"] / B, 1),
+                     "iterations_per_query": round(ab["iterations_mean"], 2),
+                     "queries_stopped_by_cap": ab["hit_cap"]},
+        "sweep": sweep,
+    }
+
+    # ---- CPU oracle on a sample of the same queries (rank 0, N = 1 only) -----------------------
+    if not args.no_cpu:
+        import oracle
+        ns = min(args.cpu_sample, B)
+        g_np = graph.cpu().numpy().view(np.uint32)
+        oracle.search(g_np, w.base, w.queries[:64], w.k, M, w.search_width, w.metric, seed=opts.seed)  # warm-up
+        t0 = time.perf_counter()
+        o_ids, o_d, o_st = oracle.search(g_np, w.base, w.queries[:ns], w.k, M, w.search_width, w.metric,
+                                         seed=opts.seed, return_stats=True)
+        cpu_s = time.perf_counter() - t0
+        inter = sum(len(np.intersect1d(a, b)) for a, b in zip(gpu_ids[:ns], o_ids))
+        same = gpu_ids[:ns] == o_ids
+        rel = float(np.max(np.abs(gpu_d[:ns] - o_d)[same] / np.maximum(np.abs(o_d[same]), 1e-30))) if same.any() else 0.0
+        out["cpu_baseline"] = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": f"first {ns} of the {B} queries, same graph, "
+                               f"itopk={M}, OpenMP over queries, {cpu_s:.2f}s"}
+        out["parity_at_full_size"] = {"sample": ns, "id_agreement": round(inter / float(ns * w.k), 6),
+                                      "positionwise_equal": round(float(same.mean()), 6),
+                                      "max_rel_dist_err": rel,
+                                      "oracle_recall": round(recall_at_k(o_ids, gt_np[:ns]), 5),
+                                      "gpu_recall_same_sample": round(recall_at_k(gpu_ids[:ns], gt_np[:ns]), 5)}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

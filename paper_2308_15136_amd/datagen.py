@@ -80,45 +80,68 @@ def gaussian_mixture(n: int, dim: int, n_comp: int, center_std: float, sigma: fl
     return out
 
 
-def sift_like(n: int, dim: int, n_comp: int, seed: int, stream: int,
-              latent_rank: int = 12) -> np.ndarray:
-    """Integer-valued rows in 0..255 stored as fp32 (stand-in for SIFT-1M).
+def latent_mixture(n: int, dim: int, n_comp: int, rank: int, spread: float, noise: float,
+                   seed: int, stream: int, log_var_range: Optional[tuple] = None) -> np.ndarray:
+    """Rows of a Gaussian mixture whose components share a low-dimensional structure.
 
-    Each of n_comp components has a non-negative heavy-tailed centre (gamma
-    distributed, scaled per dimension) and a Gaussian spread made of a
-    low-rank part (latent_rank directions, which gives the data a local
-    intrinsic dimension like that of real descriptors) plus per-dimension
-    noise proportional to the centre.  Values are shifted down, rounded and
-    clipped to [0, 255], which leaves many exact zeros.
+    A latent point z = mu_c + e lives in R^rank: component means mu_c ~ N(0, spread^2 I),
+    e ~ N(0, I) (or N(0, diag(v_c)) with per-component variances log-uniform in
+    log_var_range).  The row is z A + noise * N(0, I_dim) with one fixed random map
+    A[rank, dim] (entries N(0, 1/rank)).  In R^dim this is a mixture of n_comp Gaussians
+    with low-rank-plus-isotropic covariances; neighbouring components overlap when
+    `spread` is around 1-2, which keeps the k-NN graph of the rows connected the way
+    the graphs of real descriptor sets are, instead of falling apart into islands.
     """
     g0 = _rng(seed, 0, 0)
-    dim_scale = np.exp(0.5 * g0.standard_normal(dim))
-    centers = g0.gamma(0.8, 34.0, size=(n_comp, dim)) * dim_scale
-    basis = g0.standard_normal((n_comp, latent_rank, dim)) * (0.22 * centers[:, None, :] + 4.0)
-    noise_std = (0.05 * centers + 1.5).astype(np.float32)
-    centers = centers.astype(np.float32)
-    basis = basis.astype(np.float32)
+    mu = (g0.standard_normal((n_comp, rank)) * spread).astype(np.float32)
+    A = (g0.standard_normal((rank, dim)) / np.sqrt(rank)).astype(np.float32)
+    std = None
+    if log_var_range is not None:
+        lo, hi = log_var_range
+        std = np.sqrt(np.exp(g0.uniform(np.log(lo), np.log(hi), size=(n_comp, rank)))).astype(np.float32)
     out = np.empty((n, dim), dtype=np.float32)
     for c, lo_r, hi_r in _chunks(n):
         g = _rng(seed, stream, c)
         m = hi_r - lo_r
         # always draw the whole chunk so that a shorter matrix is a prefix of a longer one
         comp = g.integers(0, n_comp, size=_CHUNK)[:m]
-        lat = g.standard_normal((_CHUNK, latent_rank), dtype=np.float32)[:m]
-        x = g.standard_normal((_CHUNK, dim), dtype=np.float32)[:m]
-        # process component by component to keep the low-rank product a GEMM
-        order = np.argsort(comp, kind="stable")
-        bounds = np.searchsorted(comp[order], np.arange(n_comp + 1))
-        for k in range(n_comp):
-            idx = order[bounds[k]:bounds[k + 1]]
-            if idx.size == 0:
-                continue
-            x[idx] = x[idx] * noise_std[k] + lat[idx] @ basis[k] + centers[k]
-        x -= np.float32(6.0)
-        np.rint(x, out=x)
-        np.clip(x, 0.0, 255.0, out=x)
+        z = g.standard_normal((_CHUNK, rank), dtype=np.float32)[:m]
+        e = g.standard_normal((_CHUNK, dim), dtype=np.float32)[:m]
+        if std is not None:
+            z *= std[comp]
+        z += mu[comp]
+        x = z @ A
+        x += np.float32(noise) * e
         out[lo_r:hi_r] = x
     return out
+
+
+def sift_like(n: int, dim: int, n_comp: int, seed: int, stream: int,
+              rank: int = 64, spread: float = 1.5, noise: float = 0.3) -> np.ndarray:
+    """Integer-valued rows in 0..255 stored as fp32 (stand-in for SIFT-1M).
+
+    A latent mixture (see latent_mixture) is scaled per dimension (log-normal scales, so
+    a few dimensions carry most of the energy), shifted by a heavy-tailed per-dimension
+    offset, rounded and clipped to [0, 255].  The clipping at zero leaves many exact
+    zeros and a heavy right tail, like gradient-histogram descriptors.
+    """
+    g0 = _rng(seed, 7, 0)
+    dim_scale = (42.0 * np.exp(0.45 * g0.standard_normal(dim))).astype(np.float32)
+    offset = (g0.gamma(0.9, 24.0, size=dim) - 6.0).astype(np.float32)
+    x = latent_mixture(n, dim, n_comp, rank, spread, noise, seed, stream)
+    x *= dim_scale / np.float32(np.sqrt(1.0 + spread * spread))
+    x += offset
+    np.rint(x, out=x)
+    np.clip(x, 0.0, 255.0, out=x)
+    return x
+
+
+def unit_mixture(n: int, dim: int, n_comp: int, rank: int, spread: float, noise: float,
+                 seed: int, stream: int, log_var_range: Optional[tuple] = None) -> np.ndarray:
+    """Latent Gaussian mixture rows scaled to unit L2 norm (stand-in for DEEP / GloVe)."""
+    x = latent_mixture(n, dim, n_comp, rank, spread, noise, seed, stream, log_var_range)
+    _normalize_rows(x)
+    return x
 
 
 @dataclass
@@ -155,21 +178,21 @@ def workload(name: str, n: Optional[int] = None, n_queries: Optional[int] = None
     if name == "deep1m":        # large batch, lower dim: 1M x 96 unit norm
         n = n or 1_000_000
         b = n_queries or 10_000
-        base = gaussian_mixture(n, 96, 1024, 1.0, 0.6, seed=2, stream=1, unit_norm=True)
-        qs = gaussian_mixture(b, 96, 1024, 1.0, 0.6, seed=2, stream=2, unit_norm=True)
+        base = unit_mixture(n, 96, 1024, 40, 1.5, 0.1, seed=2, stream=1)
+        qs = unit_mixture(b, 96, 1024, 40, 1.5, 0.1, seed=2, stream=2)
         return Workload(name, base, qs, L2, 32, 64, 10, (64, 128, 256, 512))
     if name == "glove200":      # angular, higher dim: 1,183,514 x 200, inner product
         n = n or 1_183_514
         b = n_queries or 10_000
-        kw = dict(seed=3, unit_norm=True, log_var_range=(0.1, 10.0))
-        base = gaussian_mixture(n, 200, 2000, 1.0, 0.35, stream=1, **kw)
-        qs = gaussian_mixture(b, 200, 2000, 1.0, 0.35, stream=2, **kw)
+        kw = dict(seed=3, log_var_range=(0.1, 10.0))
+        base = unit_mixture(n, 200, 2000, 128, 1.5, 0.1, stream=1, **kw)
+        qs = unit_mixture(b, 200, 2000, 128, 1.5, 0.1, stream=2, **kw)
         return Workload(name, base, qs, IP, 64, 128, 10, (128, 256, 512))
     if name == "deep10m":       # small batch / scale: 10M x 96 unit norm
         n = n or 10_000_000
         b = n_queries or 1_000
-        base = gaussian_mixture(n, 96, 4096, 1.0, 0.6, seed=4, stream=1, unit_norm=True)
-        qs = gaussian_mixture(b, 96, 4096, 1.0, 0.6, seed=4, stream=2, unit_norm=True)
+        base = unit_mixture(n, 96, 4096, 40, 1.5, 0.1, seed=4, stream=1)
+        qs = unit_mixture(b, 96, 4096, 40, 1.5, 0.1, seed=4, stream=2)
         return Workload(name, base, qs, L2, 32, 64, 10, (64, 128, 256), search_width=4)
     raise ValueError(f"unknown workload {name!r}")
 
