@@ -66,6 +66,8 @@ def main() -> int:
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from rocprofv3 counters, copied into roofline.traffic")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference dispatch for rocprofv3 counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; queries are independent, so more GPUs would "
@@ -207,6 +209,12 @@ def main() -> int:
                                       "max_rel_dist_err": rel,
                                       "oracle_recall": round(recall_at_k(o_ids, gt_np[:ns]), 5),
                                       "gpu_recall_same_sample": round(recall_at_k(gpu_ids[:ns], gt_np[:ns]), 5)}
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(out), flush=True)
     return 0
 

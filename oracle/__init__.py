@@ -49,7 +49,7 @@ def _load():
         lib.oracle_distance.argtypes = [f32p, f32p, i32, i32]
         lib.oracle_exact_search.argtypes = [f32p, i64, i32, i32, f32p, i64, i32, u32p, f32p]
         lib.oracle_knn_graph.argtypes = [f32p, i64, i32, i32, i64p, i64, i32, u32p, f32p]
-        lib.oracle_detour_count.argtypes = [u32p, i64, i32, u32p]
+        lib.oracle_detour_count.argtypes = [u32p, i64, i32, i64p, i64, u32p]
         lib.oracle_prune.argtypes = [u32p, u32p, i64, i32, i32, u32p]
         lib.oracle_reverse.argtypes = [u32p, i64, i32, u32p, u32p]
         lib.oracle_merge.argtypes = [u32p, u32p, u32p, i64, i32, u32p]
@@ -129,11 +129,14 @@ def knn_graph(base, d_init: int, metric: int = L2, rows=None, return_dists: bool
     return (g0, gd) if return_dists else g0
 
 
-def detour_count(g0):
+def detour_count(g0, rows=None):
+    """Eq. 3 counts for every node, or for the listed nodes only (same values, fewer rows)."""
     g0 = _u32(g0)
-    cnt = np.empty_like(g0)
+    rows_a = None if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    n = g0.shape[0] if rows_a is None else rows_a.shape[0]
+    cnt = np.empty((n, g0.shape[1]), np.uint32)
     _check(_load().oracle_detour_count(_p(g0, C.c_uint32), g0.shape[0], g0.shape[1],
-                                       _p(cnt, C.c_uint32)), "detour_count")
+                                       _p(rows_a, C.c_int64), n, _p(cnt, C.c_uint32)), "detour_count")
     return cnt
 
 

@@ -167,11 +167,15 @@ int oracle_knn_graph(const float *X, int64_t N, int32_t dim, int32_t metric,
 /* ---- Sec. III-B.2, Eq. 3 with ranks as weights ------------------------------ */
 /* count[X][j] = number of two-hop routes X -> Z -> Y (Y = G0[X][j]) with
  * max(rank of Z in X's list, rank of Y in Z's list) < j. */
-int oracle_detour_count(const uint32_t *g0, int64_t N, int32_t d_init, uint32_t *count)
+/* rows == NULL: all N nodes, count[N][d_init]; else count[n_rows][d_init] for the listed nodes. */
+int oracle_detour_count(const uint32_t *g0, int64_t N, int32_t d_init, const int64_t *rows,
+                        int64_t n_rows, uint32_t *count)
 {
     if (!g0 || !count || N < 1 || d_init < 1) return -1;
+    if (!rows) n_rows = N;
 #pragma omp parallel for schedule(dynamic, 64)
-    for (int64_t x = 0; x < N; ++x) {
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const int64_t x = rows ? rows[t] : t;
         const uint32_t *lx = g0 + (size_t)x * d_init;
         for (int j = 0; j < d_init; ++j) {
             uint32_t y = lx[j];
@@ -182,7 +186,7 @@ int oracle_detour_count(const uint32_t *g0, int64_t N, int32_t d_init, uint32_t 
                     if (lz[l] == y) { ++c; break; }
                 }
             }
-            count[(size_t)x * d_init + j] = c;
+            count[(size_t)t * d_init + j] = c;
         }
     }
     return 0;
@@ -267,7 +271,7 @@ int oracle_optimize(const uint32_t *g0, int64_t N, int32_t d_init, int32_t d, ui
     uint32_t *rev_len = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);
     int rc = -2;
     if (count && pruned && rev && rev_len) {
-        rc = oracle_detour_count(g0, N, d_init, count);
+        rc = oracle_detour_count(g0, N, d_init, NULL, N, count);
         if (!rc) rc = oracle_prune(g0, count, N, d_init, d, pruned);
         if (!rc) rc = oracle_reverse(pruned, N, d, rev, rev_len);
         if (!rc) rc = oracle_merge(pruned, rev, rev_len, N, d, graph);

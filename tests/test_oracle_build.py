@@ -211,3 +211,11 @@ def test_two_hop_bound():
         for z in g[x]:
             two |= set(g[z].tolist())
         assert len(two) <= d + d * d
+
+
+def test_detour_count_rows_subset_equals_full():
+    base = datagen.gaussian_mixture(400, 8, 3, 1.0, 1.0, seed=17, stream=1)
+    g0 = oracle.knn_graph(base, 12)
+    full = oracle.detour_count(g0)
+    rows = np.array([399, 0, 17, 200], np.int64)
+    np.testing.assert_array_equal(oracle.detour_count(g0, rows=rows), full[rows])
