@@ -96,6 +96,58 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+struct MultiPlan {
+    int mr, cr, workers, itopk_local, hash_bits, team_log2, max_iterations;
+    size_t smem, table_bytes, list_bytes, done_bytes;
+    int off_query, off_newid, off_newdist, off_parents;
+};
+
+// Several workgroups per query (Sec. IV-C.2).  Every worker expands one parent per pass and
+// keeps a list of max(k, 32, ceil(itopk / workers)) entries; the shared table is sized for
+// twice the ids the workers can ever offer (Sec. IV-B.3).
+static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int width,
+                      const cagra_search_opts &o, MultiPlan &pl)
+{
+    if (o.wg_per_query < 0 || o.wg_per_query > 1024) return CAGRA_ERR_BAD_OPTION;
+    pl.workers = o.wg_per_query == 0 ? width : o.wg_per_query;
+    if (pl.workers > 1024 || B * pl.workers > 0x7FFFFFFFll) return CAGRA_ERR_BAD_OPTION;
+    int local = (itopk + pl.workers - 1) / pl.workers;
+    local = std::max(local, std::max(k, 32));
+    if (local > 512) return CAGRA_ERR_BAD_TOPK;
+    if (degree > 256) return CAGRA_ERR_BAD_DEGREE;
+    pl.itopk_local = local;
+    int mr = (local + 63) / 64;
+    pl.mr = mr <= 1 ? 1 : mr <= 2 ? 2 : mr <= 4 ? 4 : 8;
+    pl.cr = degree <= 64 ? 1 : degree <= 128 ? 2 : 4;
+    int team = o.team_size == 0 ? auto_team(dim) : o.team_size;
+    if (team != 4 && team != 8 && team != 16 && team != 32) return CAGRA_ERR_BAD_OPTION;
+    pl.team_log2 = team == 4 ? 2 : team == 8 ? 3 : team == 16 ? 4 : 5;
+    if (o.max_iterations < 0) return CAGRA_ERR_BAD_OPTION;
+    pl.max_iterations = o.max_iterations == 0 ? auto_max_iterations(local, 1) : o.max_iterations;
+    const int64_t offered = (int64_t)pl.workers * degree * ((int64_t)pl.max_iterations + 1);
+    int bits = 10;
+    while (bits < 27 && ((int64_t)1 << bits) < 2 * offered) ++bits;
+    if (bits > 26) return CAGRA_ERR_HASH_CAPACITY;
+    pl.hash_bits = bits;
+    pl.table_bytes = align256(((size_t)B << bits) * 4);
+    pl.list_bytes = align256((size_t)B * pl.workers * 64 * pl.mr * 8);
+    pl.done_bytes = align256((size_t)B * 4);
+    size_t off = 0;
+    pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
+    pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
+    pl.off_newdist = (int)off;    off += (size_t)4 * 64 * pl.cr;
+    pl.off_parents = (int)off;    off += (size_t)4 * 64;
+    pl.smem = off;
+    if (pl.smem > 64 * 1024) return CAGRA_ERR_BAD_SHAPE;
+    return CAGRA_OK;
+}
+
+static int resolve_mode(const cagra_search_opts &o, int64_t B, int itopk)
+{
+    if (o.mode == 1 || o.mode == 2) return o.mode;
+    return (B < device_info().cus || itopk > 512) ? 2 : 1;
+}
+
 }  // namespace cagra
 
 using namespace cagra;
@@ -125,14 +177,21 @@ uint32_t cagra_seed_id(uint64_t seed, uint64_t query, uint64_t slot, uint64_t N)
 
 int cagra_search_auto_mode(int64_t B, int32_t itopk)
 {
-    return (B < device_info().cus || itopk > 512) ? 2 : 1;
+    cagra_search_opts o = {};
+    return resolve_mode(o, B, itopk);
 }
 
 size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_t k, int32_t itopk,
                                     int32_t search_width, const cagra_search_opts *opts)
 {
-    (void)N; (void)degree; (void)B; (void)k; (void)itopk; (void)search_width; (void)opts;
-    return 256;  // the persistent-scheduling counter
+    (void)N;
+    cagra_search_opts o = {};
+    if (opts) o = *opts;
+    if (B < 1 || degree < 1 || k < 1 || itopk < 1 || search_width < 1) return 256;
+    if (resolve_mode(o, B, itopk) == 1) return 256;  // the persistent-scheduling counter
+    MultiPlan pl;
+    if (plan_multi(degree, 4, B, k, itopk, search_width, o, pl) != CAGRA_OK) return 256;
+    return pl.table_bytes + pl.list_bytes + pl.done_bytes;
 }
 
 int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *dataset, int32_t dim,
@@ -153,22 +212,42 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *
     if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
     if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
     if (o.mode < 0 || o.mode > 2) return CAGRA_ERR_BAD_OPTION;
-    if (o.mode == 2) return CAGRA_ERR_BAD_OPTION;  // multi-workgroup search not built yet
+    if (B == 0) return CAGRA_OK;
+    const int mode = resolve_mode(o, B, itopk);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    SearchParams P = {};
+    P.graph = graph; P.dataset = dataset; P.queries = queries;
+    P.ids_out = ids_out; P.dists_out = dists_out; P.stats = o.stats;
+    P.N = N; P.B = B; P.ld = ld; P.ld_queries = ld_queries; P.seed = o.seed;
+    P.degree = degree; P.dim = dim; P.metric = (int)metric; P.k = k;
+
+    if (mode == 2) {
+        MultiPlan pl;
+        int rc = plan_multi(degree, dim, B, k, itopk, search_width, o, pl);
+        if (rc != CAGRA_OK) return rc;
+        if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+            workspace_bytes < pl.table_bytes + pl.list_bytes + pl.done_bytes)
+            return CAGRA_ERR_WORKSPACE;
+        unsigned char *w = static_cast<unsigned char *>(workspace);
+        P.tables = reinterpret_cast<uint32_t *>(w);
+        P.lists = reinterpret_cast<uint64_t *>(w + pl.table_bytes);
+        P.done = reinterpret_cast<uint32_t *>(w + pl.table_bytes + pl.list_bytes);
+        P.itopk = pl.itopk_local; P.search_width = 1; P.workers = pl.workers;
+        P.max_iterations = pl.max_iterations; P.reset_interval = 0;
+        P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
+        P.off_query = pl.off_query; P.off_newid = pl.off_newid;
+        P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
+        hipError_t e = launch_search_multi(P, pl.mr, pl.cr, pl.smem, stream);
+        return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+    }
+
     SinglePlan pl;
     int rc = plan_single(degree, dim, itopk, search_width, o, pl);
     if (rc != CAGRA_OK) return rc;
-    if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
-        workspace_bytes < cagra_search_workspace_bytes(N, degree, B, k, itopk, search_width, opts))
-        return CAGRA_ERR_WORKSPACE;
-    if (B == 0) return CAGRA_OK;
-
-    SingleParams P;
-    P.graph = graph; P.dataset = dataset; P.queries = queries;
-    P.ids_out = ids_out; P.dists_out = dists_out; P.stats = o.stats;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < 256) return CAGRA_ERR_WORKSPACE;
     P.counter = static_cast<uint32_t *>(workspace);
-    P.N = N; P.B = B; P.ld = ld; P.ld_queries = ld_queries; P.seed = o.seed;
-    P.degree = degree; P.dim = dim; P.metric = (int)metric;
-    P.k = k; P.itopk = itopk; P.search_width = search_width;
+    P.itopk = itopk; P.search_width = search_width; P.workers = 1;
     P.max_iterations = pl.max_iterations; P.reset_interval = pl.reset_interval;
     P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
     P.off_query = pl.off_query; P.off_newid = pl.off_newid;
@@ -179,7 +258,7 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *
     int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
     if (per_cu < 1) per_cu = 1;
     int grid = (int)std::min<int64_t>(B, (int64_t)per_cu * di.cus);
-    hipError_t e = launch_search_single(P, pl.mr, pl.cr, grid, pl.smem, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_search_single(P, pl.mr, pl.cr, grid, pl.smem, stream);
     return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
 }
 

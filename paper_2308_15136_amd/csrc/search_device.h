@@ -1,0 +1,137 @@
+// Device code shared by the search kernels: 64-bit (distance, id) keys held in register
+// pairs, wavefront-wide bitonic sort / merge (Sec. IV-B.2), the LDS visited table
+// (Sec. IV-B.3).  Element e of a list lives in lane e % 64, register e / 64.
+#pragma once
+#include "device_util.h"
+
+namespace cagra {
+
+// ---- 64-bit keys spread over two 32-bit registers ------------------------------------------
+
+__device__ __forceinline__ bool key_less(uint32_t ahi, uint32_t alo, uint32_t bhi, uint32_t blo)
+{
+    return (((uint64_t)ahi << 32) | alo) < (((uint64_t)bhi << 32) | blo);
+}
+
+// Compare-exchange with the lane `j` apart; keep_min lanes keep the smaller key.
+__device__ __forceinline__ void ce_lanes(uint32_t &hi, uint32_t &lo, int j, bool keep_min)
+{
+    uint32_t phi = shfl_xor_u32(hi, j), plo = shfl_xor_u32(lo, j);
+    bool pless = key_less(phi, plo, hi, lo);
+    bool take = keep_min ? pless : !pless;
+    hi = take ? phi : hi;
+    lo = take ? plo : lo;
+}
+
+// Compare-exchange between two registers of the same lane.
+__device__ __forceinline__ void ce_regs(uint32_t &ahi, uint32_t &alo, uint32_t &bhi, uint32_t &blo, bool a_min)
+{
+    bool bless = key_less(bhi, blo, ahi, alo);
+    bool swap = a_min ? bless : !bless;
+    uint32_t th = ahi, tl = alo;
+    ahi = swap ? bhi : ahi;
+    alo = swap ? blo : alo;
+    bhi = swap ? th : bhi;
+    blo = swap ? tl : blo;
+}
+
+// Bitonic merge of a bitonic sequence of 64*R elements (register-major layout) into
+// ascending (ASC) or descending order.
+template <int R, bool ASC>
+__device__ __forceinline__ void bitonic_merge(uint32_t (&hi)[R], uint32_t (&lo)[R], int lane)
+{
+#pragma unroll
+    for (int jr = R / 2; jr >= 1; jr >>= 1) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if ((r & jr) == 0) ce_regs(hi[r], lo[r], hi[r | jr], lo[r | jr], ASC);
+    }
+#pragma unroll
+    for (int j = 32; j >= 1; j >>= 1) {
+        bool keep_min = ((lane & j) == 0) == ASC;
+#pragma unroll
+        for (int r = 0; r < R; ++r) ce_lanes(hi[r], lo[r], j, keep_min);
+    }
+}
+
+// Full bitonic sort, ascending, of 64*R elements.
+template <int R>
+__device__ __forceinline__ void bitonic_sort(uint32_t (&hi)[R], uint32_t (&lo)[R], int lane)
+{
+#pragma unroll
+    for (int k = 2; k <= 64 * R; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j >= 1; j >>= 1) {
+            if (j >= 64) {
+                const int jr = j / 64;
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    if ((r & jr) == 0) {
+                        bool asc = ((r * 64) & k) == 0;
+                        ce_regs(hi[r], lo[r], hi[r | jr], lo[r | jr], asc);
+                    }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    int e = r * 64 + lane;
+                    bool keep_min = ((e & j) == 0) == ((e & k) == 0);
+                    ce_lanes(hi[r], lo[r], j, keep_min);
+                }
+            }
+        }
+    }
+}
+
+// Step 1 (Sec. IV-A, IV-B.2): sorted candidates c (ascending) merged into the sorted top-M
+// list t; t keeps the 64*MR smallest.  Only the min(CR, MR) lowest candidate registers can
+// matter.  The largest 64*C elements of t are replaced by the 64*C smallest of (those, c);
+// that block is sorted descending so that t as a whole is bitonic, then merged.
+template <int MR, int CR>
+__device__ __forceinline__ void merge_into_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR],
+                                                uint32_t (&chi)[CR], uint32_t (&clo)[CR], int lane)
+{
+    constexpr int C = CR < MR ? CR : MR;
+    uint32_t bhi[C], blo[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        uint32_t phi = shfl_u32(chi[C - 1 - i], 63 - lane);
+        uint32_t plo = shfl_u32(clo[C - 1 - i], 63 - lane);
+        bool pless = key_less(phi, plo, thi[MR - C + i], tlo[MR - C + i]);
+        bhi[i] = pless ? phi : thi[MR - C + i];
+        blo[i] = pless ? plo : tlo[MR - C + i];
+    }
+    if constexpr (C == MR) {
+        bitonic_merge<C, true>(bhi, blo, lane);
+#pragma unroll
+        for (int i = 0; i < C; ++i) { thi[i] = bhi[i]; tlo[i] = blo[i]; }
+    } else {
+        bitonic_merge<C, false>(bhi, blo, lane);
+#pragma unroll
+        for (int i = 0; i < C; ++i) { thi[MR - C + i] = bhi[i]; tlo[MR - C + i] = blo[i]; }
+        bitonic_merge<MR, true>(thi, tlo, lane);
+    }
+}
+
+// ---- visited table (Sec. IV-B.3) -------------------------------------------------------------
+
+__device__ __forceinline__ uint32_t hash_slot(uint32_t id, int bits)
+{
+    return (id * 2654435761u) >> (32 - bits);
+}
+
+// true if id was not in the table (and is now).  `overflow` is raised if no free slot exists.
+__device__ __forceinline__ bool visited_insert(uint32_t *table, int bits, uint32_t id, bool &overflow)
+{
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t s = hash_slot(id, bits);
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        uint32_t old = atomicCAS(&table[s], kInvalidId, id);
+        if (old == kInvalidId) return true;
+        if (old == id) return false;
+        s = (s + 1) & mask;
+    }
+    overflow = true;
+    return true;
+}
+
+}  // namespace cagra

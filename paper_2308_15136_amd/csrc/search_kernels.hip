@@ -1,0 +1,373 @@
+// CAGRA search kernels for gfx950 (Sec. IV-A, IV-B, IV-C).
+//
+// One wavefront (64 lanes) runs the whole loop of steps 0-3 for one query (single mode)
+// or for one worker of a query (multi mode):
+//   - top-M list and candidate list live in registers, one 64-bit key per element: high
+//     word = order-preserving image of the fp32 distance, low word = (node id << 1) |
+//     parent flag.  One unsigned 64-bit compare is the (distance, id) order; the flag bit
+//     sits below the id so it cannot change that order (Sec. IV-B.4 keeps the flag in the
+//     index word as well).  Element e of a list is held by lane e % 64 in register e / 64.
+//   - step 1 is a bitonic sort of the candidates followed by a bitonic merge into the
+//     sorted top-M list (Sec. IV-B.2).
+//   - distances are computed by teams of 4/8/16/32 lanes, one dataset row per team,
+//     16-byte loads, butterfly reduction (Sec. IV-B.1).
+// Single mode (Sec. IV-C.1): workgroups are persistent and pull query indices from a
+// device counter; the visited table is an open-addressing hash in LDS that is cleared
+// every `reset_interval` passes and re-filled with the current top-M ids (forgettable
+// management, Sec. IV-B.3).
+// Multi mode (Sec. IV-C.2): `workers` workgroups per query, each with one parent per pass,
+// its own seeds and its own list, sharing one visited table in device memory; the last
+// worker of a query to finish merges the lists and writes the result.
+#include "device_util.h"
+#include "search_device.h"
+#include "search_params.h"
+
+namespace cagra {
+
+// true if id was not in the device-memory table (and is now)
+__device__ __forceinline__ bool visited_insert_global(uint32_t *table, int bits, uint32_t id, bool &overflow)
+{
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t s = hash_slot(id, bits);
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        uint32_t old = atomicCAS(&table[s], kInvalidId, id);
+        if (old == kInvalidId) return true;
+        if (old == id) return false;
+        s = (s + 1) & mask;
+    }
+    overflow = true;
+    return true;
+}
+
+struct QueryStats {
+    uint32_t n_iter, n_parent, n_dist, flags;
+};
+
+// The search of one (query, worker): on return thi/tlo hold the sorted top-M list.
+// `table` is the LDS table (single) or this query's device-memory table (multi).
+template <int MR, int CR, bool MULTI>
+__device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, int worker,
+                                            uint32_t *table, float *qlds, uint32_t *newid,
+                                            float *newdist, uint32_t *parents,
+                                            const int (&slot_parent)[CR], const int (&slot_nbr)[CR],
+                                            uint32_t (&thi)[MR], uint32_t (&tlo)[MR], QueryStats &qs)
+{
+    const int lane = lane_id();
+    const int team_log2 = P.team_log2;
+    const int team = 1 << team_log2;
+    const int n_teams = kWave >> team_log2;
+    const int g = lane >> team_log2;       // team of this lane
+    const int t = lane & (team - 1);       // lane within the team
+    const int n_cand = P.search_width * P.degree;
+    const int nchunk = P.dim >> 2;         // 16-byte pieces per row
+    const int table_words = 1 << P.hash_bits;
+
+    const float *q = P.queries + (size_t)qi * P.ld_queries;
+    for (int j = lane; j < P.dim; j += kWave) qlds[j] = q[j];
+    if (!MULTI)
+        for (int j = lane; j < table_words; j += kWave) table[j] = kInvalidId;
+
+    uint32_t chi[CR], clo[CR];
+#pragma unroll
+    for (int r = 0; r < MR; ++r) { thi[r] = kDummyHi; tlo[r] = kInvalidId; }
+
+    // step 0: random sampling (Sec. IV-A); worker w draws slots w * n_cand ...
+    const uint64_t qh = seed_query_hash(P.seed, qi);
+    uint32_t raw[CR];
+#pragma unroll
+    for (int r = 0; r < CR; ++r) {
+        int c = r * 64 + lane;
+        raw[r] = c < n_cand ? seed_slot_id(qh, (uint64_t)worker * n_cand + c, (uint64_t)P.N) : kInvalidId;
+    }
+    __syncthreads();
+
+    uint32_t n_iter = 0, n_parent_total = 0, n_dist_total = 0, flags = 0;
+    bool overflow = false;
+
+    for (int it = 0;; ++it) {
+        // ---- step 3: first-time test, compaction, team distances -------------------------
+        int n_new = 0;
+#pragma unroll
+        for (int r = 0; r < CR; ++r) {
+            bool isnew = false;
+            if (raw[r] != kInvalidId)
+                isnew = MULTI ? visited_insert_global(table, P.hash_bits, raw[r], overflow)
+                              : visited_insert(table, P.hash_bits, raw[r], overflow);
+            uint64_t m = __ballot(isnew);
+            int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                   __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (isnew) newid[pos] = raw[r];
+            n_new += __popcll(m);
+        }
+        __syncthreads();
+        n_dist_total += (uint32_t)n_new;
+
+        for (int c0 = 0; c0 < n_new; c0 += 2 * n_teams) {
+            // two dataset rows per team in flight
+            const int ca = c0 + g, cb = c0 + n_teams + g;
+            const bool va = ca < n_new, vb = cb < n_new;
+            const float *rowa = P.dataset + (size_t)(va ? newid[ca] : 0u) * P.ld;
+            const float *rowb = P.dataset + (size_t)(vb ? newid[cb] : 0u) * P.ld;
+            float acca = 0.f, accb = 0.f;
+            for (int base = 0; base < nchunk; base += 4 * team) {
+                float4 xa[4], xb[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int ch = base + i * team + t;
+                    bool in = ch < nchunk;
+                    xa[i] = (va && in) ? *reinterpret_cast<const float4 *>(rowa + 4 * ch) : make_float4(0, 0, 0, 0);
+                    xb[i] = (vb && in) ? *reinterpret_cast<const float4 *>(rowb + 4 * ch) : make_float4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int ch = base + i * team + t;
+                    if (ch < nchunk) {
+                        float4 qv = *reinterpret_cast<const float4 *>(qlds + 4 * ch);
+                        if (P.metric == 0) {
+                            float d0 = xa[i].x - qv.x, d1 = xa[i].y - qv.y, d2 = xa[i].z - qv.z, d3 = xa[i].w - qv.w;
+                            acca = fmaf(d0, d0, acca); acca = fmaf(d1, d1, acca);
+                            acca = fmaf(d2, d2, acca); acca = fmaf(d3, d3, acca);
+                            float e0 = xb[i].x - qv.x, e1 = xb[i].y - qv.y, e2 = xb[i].z - qv.z, e3 = xb[i].w - qv.w;
+                            accb = fmaf(e0, e0, accb); accb = fmaf(e1, e1, accb);
+                            accb = fmaf(e2, e2, accb); accb = fmaf(e3, e3, accb);
+                        } else {
+                            acca = fmaf(xa[i].x, qv.x, acca); acca = fmaf(xa[i].y, qv.y, acca);
+                            acca = fmaf(xa[i].z, qv.z, acca); acca = fmaf(xa[i].w, qv.w, acca);
+                            accb = fmaf(xb[i].x, qv.x, accb); accb = fmaf(xb[i].y, qv.y, accb);
+                            accb = fmaf(xb[i].z, qv.z, accb); accb = fmaf(xb[i].w, qv.w, accb);
+                        }
+                    }
+                }
+            }
+            for (int s = 1; s < team; s <<= 1) {
+                acca += __shfl_xor(acca, s, kWave);
+                accb += __shfl_xor(accb, s, kWave);
+            }
+            if (P.metric != 0) { acca = 0.0f - acca; accb = 0.0f - accb; }
+            if (t == 0) {
+                if (va) newdist[ca] = acca;
+                if (vb) newdist[cb] = accb;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < CR; ++r) {
+            int c = r * 64 + lane;
+            bool v = c < n_new;
+            chi[r] = v ? f32_to_ordered(newdist[c]) : kDummyHi;
+            clo[r] = v ? (newid[c] << 1) : kInvalidId;
+        }
+
+        // ---- step 1: top-M update (skipped when no candidate can enter) -------------------
+        {
+            const int last = P.itopk - 1;
+            uint32_t whi = shfl_u32(thi[MR - 1], last & 63), wlo = shfl_u32(tlo[MR - 1], last & 63);
+            bool any = false;
+#pragma unroll
+            for (int r = 0; r < CR; ++r) any |= key_less(chi[r], clo[r], whi, wlo);
+            if (__ballot(any) != 0ull) {
+                bitonic_sort<CR>(chi, clo, lane);
+                merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
+                // logical length is itopk: the padding of the last register stays dummy
+                if ((MR - 1) * 64 + lane >= P.itopk) { thi[MR - 1] = kDummyHi; tlo[MR - 1] = kInvalidId; }
+            }
+        }
+        if (it == P.max_iterations) { flags |= 1u; break; }
+
+        // ---- forgettable management: periodic reset (Sec. IV-B.3), single mode only ------
+        if (!MULTI && P.reset_interval > 0 && it > 0 && (it % P.reset_interval) == 0) {
+            __syncthreads();
+            for (int j = lane; j < table_words; j += kWave) table[j] = kInvalidId;
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < MR; ++r)
+                if (tlo[r] != kInvalidId) (void)visited_insert(table, P.hash_bits, tlo[r] >> 1, overflow);
+        }
+
+        // ---- step 2: parents = first search_width entries without the flag ----------------
+        int n_par = 0;
+#pragma unroll
+        for (int r = 0; r < MR; ++r) {
+            uint64_t m = __ballot((tlo[r] & 1u) == 0u);
+            while (m != 0ull && n_par < P.search_width) {
+                int l = __builtin_ctzll(m);
+                m &= m - 1;
+                uint32_t w = __builtin_amdgcn_readlane(tlo[r], l);
+                if (lane == l) tlo[r] |= 1u;
+                if (lane == 0) parents[n_par] = w >> 1;
+                ++n_par;
+            }
+        }
+        if (n_par == 0) break;
+        n_parent_total += (uint32_t)n_par;
+        ++n_iter;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < CR; ++r) {
+            bool v = slot_parent[r] < n_par;
+            raw[r] = v ? P.graph[(size_t)parents[v ? slot_parent[r] : 0] * P.degree + slot_nbr[r]] : kInvalidId;
+        }
+    }
+    if (__ballot(overflow) != 0ull) flags |= 2u;
+    qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
+}
+
+// First k of the sorted list -> ids / dists (Sec. IV-A, last sentence).
+template <int MR>
+__device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
+                                             const uint32_t (&thi)[MR], const uint32_t (&tlo)[MR])
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int r = 0; r < MR; ++r) {
+        int e = r * 64 + lane;
+        if (e < P.k) {
+            bool valid = tlo[r] != kInvalidId;
+            P.ids_out[(size_t)qi * P.k + e] = valid ? (tlo[r] >> 1) : kInvalidId;
+            P.dists_out[(size_t)qi * P.k + e] = valid ? ordered_to_f32(thi[r]) : __uint_as_float(kFltMaxBits);
+        }
+    }
+}
+
+#define CAGRA_LDS_VIEWS                                                          \
+    extern __shared__ __align__(16) unsigned char smem[];                       \
+    float *qlds = reinterpret_cast<float *>(smem + P.off_query);               \
+    uint32_t *newid = reinterpret_cast<uint32_t *>(smem + P.off_newid);        \
+    float *newdist = reinterpret_cast<float *>(smem + P.off_newdist);          \
+    uint32_t *parents = reinterpret_cast<uint32_t *>(smem + P.off_parents);    \
+    const int lane = lane_id();                                                  \
+    int slot_parent[CR], slot_nbr[CR];                                           \
+    _Pragma("unroll") for (int r = 0; r < CR; ++r) {                             \
+        int c = r * 64 + lane;                                                   \
+        slot_parent[r] = c / P.degree;                                           \
+        slot_nbr[r] = c - slot_parent[r] * P.degree;                             \
+    }
+
+template <int MR, int CR>
+__global__ void __launch_bounds__(kWave)
+search_single_kernel(const SearchParams P)
+{
+    CAGRA_LDS_VIEWS
+    uint32_t *table = reinterpret_cast<uint32_t *>(smem);
+    for (;;) {
+        // persistent scheduling: next query
+        uint32_t qi = 0;
+        if (lane == 0) qi = atomicAdd(P.counter, 1u);
+        qi = __builtin_amdgcn_readfirstlane(qi);
+        if ((int64_t)qi >= P.B) break;
+        uint32_t thi[MR], tlo[MR];
+        QueryStats qs;
+        search_body<MR, CR, false>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+                                   thi, tlo, qs);
+        write_result<MR>(P, qi, thi, tlo);
+        if (P.stats != nullptr && lane == 0) {
+            uint32_t *s = P.stats + (size_t)qi * 4;
+            s[0] = qs.n_iter; s[1] = qs.n_parent; s[2] = qs.n_dist; s[3] = qs.flags;
+        }
+        __syncthreads();
+    }
+}
+
+template <int MR, int CR>
+__global__ void __launch_bounds__(kWave)
+search_multi_kernel(const SearchParams P)
+{
+    CAGRA_LDS_VIEWS
+    const uint32_t qi = blockIdx.x / (uint32_t)P.workers;
+    const int worker = (int)(blockIdx.x - qi * (uint32_t)P.workers);
+    uint32_t *table = P.tables + ((size_t)qi << P.hash_bits);
+    uint32_t thi[MR], tlo[MR];
+    QueryStats qs;
+    search_body<MR, CR, true>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+                              thi, tlo, qs);
+    if (P.stats != nullptr && lane == 0) {
+        uint32_t *s = P.stats + (size_t)qi * 4;
+        atomicMax(&s[0], qs.n_iter);
+        atomicAdd(&s[1], qs.n_parent);
+        atomicAdd(&s[2], qs.n_dist);
+        atomicOr(&s[3], qs.flags);
+    }
+    // publish this worker's list, then see whether every worker of the query has done so
+    uint64_t *mine = P.lists + ((size_t)qi * P.workers + worker) * (64 * MR);
+#pragma unroll
+    for (int r = 0; r < MR; ++r) mine[r * 64 + lane] = ((uint64_t)thi[r] << 32) | tlo[r];
+    __threadfence();
+    uint32_t ticket = 0;
+    if (lane == 0) ticket = atomicAdd(&P.done[qi], 1u);
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket != (uint32_t)P.workers - 1u) return;
+    __threadfence();
+    // last worker: fold the other lists into its own, one bitonic merge each
+    for (int w = 0; w < P.workers; ++w) {
+        if (w == worker) continue;
+        const uint64_t *other = P.lists + ((size_t)qi * P.workers + w) * (64 * MR);
+        uint32_t ohi[MR], olo[MR];
+#pragma unroll
+        for (int r = 0; r < MR; ++r) {
+            uint64_t key = __builtin_nontemporal_load(other + r * 64 + lane);
+            ohi[r] = (uint32_t)(key >> 32);
+            olo[r] = (uint32_t)key;
+        }
+        merge_into_topm<MR, MR>(thi, tlo, ohi, olo, lane);
+    }
+    write_result<MR>(P, qi, thi, tlo);
+}
+
+__global__ void zero_counter_kernel(uint32_t *counter) { *counter = 0u; }
+
+// multi mode: empty visited tables, zero the per-query counters and the statistics
+__global__ void multi_init_kernel(uint32_t *tables, size_t table_words_total, uint32_t *done, uint32_t *stats, int64_t B)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < table_words_total) tables[i] = kInvalidId;
+    if (i < (size_t)B) done[i] = 0u;
+    if (stats != nullptr && i < (size_t)B * 4) stats[i] = 0u;
+}
+
+template <int MR, int CR>
+static hipError_t launch_single_one(const SearchParams &P, int grid, size_t smem, hipStream_t stream)
+{
+    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, stream, P.counter);
+    hipLaunchKernelGGL((search_single_kernel<MR, CR>), dim3(grid), dim3(kWave), smem, stream, P);
+    return hipGetLastError();
+}
+
+template <int MR, int CR>
+static hipError_t launch_multi_one(const SearchParams &P, size_t smem, hipStream_t stream)
+{
+    const size_t words = (size_t)P.B << P.hash_bits;
+    const size_t n = words > (size_t)P.B * 4 ? words : (size_t)P.B * 4;
+    hipLaunchKernelGGL(multi_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                       P.tables, words, P.done, P.stats, P.B);
+    hipLaunchKernelGGL((search_multi_kernel<MR, CR>), dim3((unsigned)(P.B * P.workers)), dim3(kWave), smem, stream, P);
+    return hipGetLastError();
+}
+
+#define CAGRA_DISPATCH(FN, ...)                                                          \
+    switch (mr * 8 + cr) {                                                               \
+        case 1 * 8 + 1: return FN<1, 1>(__VA_ARGS__);                                    \
+        case 1 * 8 + 2: return FN<1, 2>(__VA_ARGS__);                                    \
+        case 1 * 8 + 4: return FN<1, 4>(__VA_ARGS__);                                    \
+        case 2 * 8 + 1: return FN<2, 1>(__VA_ARGS__);                                    \
+        case 2 * 8 + 2: return FN<2, 2>(__VA_ARGS__);                                    \
+        case 2 * 8 + 4: return FN<2, 4>(__VA_ARGS__);                                    \
+        case 4 * 8 + 1: return FN<4, 1>(__VA_ARGS__);                                    \
+        case 4 * 8 + 2: return FN<4, 2>(__VA_ARGS__);                                    \
+        case 4 * 8 + 4: return FN<4, 4>(__VA_ARGS__);                                    \
+        case 8 * 8 + 1: return FN<8, 1>(__VA_ARGS__);                                    \
+        case 8 * 8 + 2: return FN<8, 2>(__VA_ARGS__);                                    \
+        case 8 * 8 + 4: return FN<8, 4>(__VA_ARGS__);                                    \
+    }                                                                                    \
+    return hipErrorInvalidValue;
+
+hipError_t launch_search_single(const SearchParams &P, int mr, int cr, int grid, size_t smem, hipStream_t stream)
+{
+    CAGRA_DISPATCH(launch_single_one, P, grid, smem, stream)
+}
+
+hipError_t launch_search_multi(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream)
+{
+    CAGRA_DISPATCH(launch_multi_one, P, smem, stream)
+}
+
+}  // namespace cagra

@@ -1,28 +1,35 @@
-// Kernel argument blocks of the search kernels (host fills, device reads).
+// Kernel argument block of the search kernels (host fills, device reads).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace cagra {
 
-struct SingleParams {
+struct SearchParams {
     const uint32_t *graph;
     const float *dataset;
     const float *queries;
     uint32_t *ids_out;
     float *dists_out;
     uint32_t *stats;      // optional [B, 4]
-    uint32_t *counter;    // persistent-scheduling query counter (workspace)
+    uint32_t *counter;    // single mode: persistent-scheduling query counter (workspace)
+    // multi mode (workspace): one visited table per query, every worker's final list, and a
+    // per-query count of workers that have finished
+    uint32_t *tables;     // [B, 1 << hash_bits]
+    uint64_t *lists;      // [B, workers, 64 * MR]
+    uint32_t *done;       // [B]
     int64_t N, B, ld, ld_queries;
     uint64_t seed;
     int32_t degree, dim, metric;
-    int32_t k, itopk, search_width;
+    int32_t k, itopk, search_width;   // multi mode: itopk is the per-worker list length, width is 1
+    int32_t workers;                  // multi mode: workgroups per query
     int32_t max_iterations, reset_interval, hash_bits, team_log2;
     // byte offsets into the dynamic LDS block
     int32_t off_query, off_newid, off_newdist, off_parents;
 };
 
-hipError_t launch_search_single(const SingleParams &P, int mr, int cr, int grid, size_t smem,
+hipError_t launch_search_single(const SearchParams &P, int mr, int cr, int grid, size_t smem,
                                 hipStream_t stream);
+hipError_t launch_search_multi(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream);
 
 }  // namespace cagra
