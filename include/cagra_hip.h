@@ -50,7 +50,7 @@ typedef enum {
     CAGRA_ERR_BAD_TOPK = -4,       /* k, itopk, search_width out of range */
     CAGRA_ERR_BAD_OPTION = -5,     /* a cagra_search_opts field is not supported */
     CAGRA_ERR_WORKSPACE = -6,      /* workspace missing, misaligned or too small */
-    CAGRA_ERR_HASH_CAPACITY = -7,  /* visited table cannot hold itopk + interval * width * degree at load 1/2 */
+    CAGRA_ERR_HASH_CAPACITY = -7,  /* visited table cannot hold itopk + interval * width * degree at load 7/8 */
     CAGRA_ERR_LAUNCH = -8          /* the HIP runtime refused a launch */
 } cagra_status;
 
@@ -62,8 +62,10 @@ typedef struct {
     int32_t max_iterations;   /* I_max; 0 => 2 * ceil(itopk / search_width) + 32 */
     int32_t mode;             /* 0 automatic (Sec. IV-C.3), 1 single workgroup per query, 2 several */
     int32_t team_size;        /* lanes per distance computation: 0 automatic, else 4, 8, 16 or 32 (Sec. IV-B.1) */
-    int32_t hash_bits;        /* single mode: log2 of the LDS visited table, 0 automatic, else 8..13 (Sec. IV-B.3) */
-    int32_t reset_interval;   /* single mode: passes between table resets, 0 automatic (largest that fits) */
+    int32_t hash_bits;        /* single mode: log2 of the LDS visited table, 8..13 (Sec. IV-B.3); 0 automatic
+                                 (the library picks a size, not necessarily a power of two) */
+    int32_t reset_interval;   /* single mode: passes between table resets, 0 automatic (the largest for which
+                                 itopk + interval * search_width * degree stays within 7/8 of the table) */
     int32_t wg_per_query;     /* multi mode: workgroups per query, 0 => search_width */
     int32_t reserved;
     uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
@@ -94,6 +96,25 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree,
 size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_t k,
                                     int32_t itopk, int32_t search_width,
                                     const cagra_search_opts *opts /* host, may be NULL */);
+
+/* What a search with these arguments would run with (host function, nothing is launched):
+ * the resolved mode and every automatic parameter.  Same argument checks as cagra_search. */
+typedef struct {
+    int32_t mode;             /* 1 single, 2 multi */
+    int32_t team_size;        /* lanes per distance computation */
+    int32_t table_entries;    /* visited table entries (LDS per workgroup, or device memory per query) */
+    int32_t reset_interval;   /* single mode: passes between resets; 0 in multi mode (never reset) */
+    int32_t max_iterations;   /* I_max */
+    int32_t wg_per_query;     /* workers per query (1 in single mode) */
+    int32_t itopk_local;      /* list length per worker: itopk in single mode,
+                                 max(k, 32, ceil(itopk / workers)) in multi mode */
+    int32_t lds_bytes;        /* dynamic LDS per workgroup */
+    int32_t workgroups;       /* launch size */
+} cagra_search_plan;
+
+int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,
+                          int32_t search_width, const cagra_search_opts *opts /* host, may be NULL */,
+                          cagra_search_plan *plan_out /* host */);
 
 /* Mode the automatic rule of Sec. IV-C.3 picks (1 single, 2 multi) for a batch of B on the
  * current device: multi when B is below the number of compute units or itopk above 512. */

@@ -36,6 +36,12 @@ class _SearchOpts(C.Structure):
                 ("wg_per_query", C.c_int32), ("reserved", C.c_int32), ("stats", C.c_void_p)]
 
 
+class _SearchPlan(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("mode", "team_size", "table_entries", "reset_interval",
+                                         "max_iterations", "wg_per_query", "itopk_local", "lds_bytes",
+                                         "workgroups")]
+
+
 def load_library():
     """Load libcagra_hip.so (built by paper_2308_15136_amd.build) and declare its ABI."""
     global _lib
@@ -56,6 +62,8 @@ def load_library():
     lib.cagra_search.restype = C.c_int
     lib.cagra_search.argtypes = [vp, i64, i32, vp, i32, i64, C.c_int, vp, i64, i64, i32, i32, i32,
                                  opts_p, vp, vp, vp, sz, vp]
+    lib.cagra_search_describe.restype = C.c_int
+    lib.cagra_search_describe.argtypes = [i32, i32, i64, i32, i32, i32, opts_p, C.POINTER(_SearchPlan)]
     lib.cagra_search_workspace_bytes.restype = sz
     lib.cagra_search_workspace_bytes.argtypes = [i64, i32, i64, i32, i32, i32, opts_p]
     lib.cagra_exact_search.restype = C.c_int
@@ -133,6 +141,21 @@ class SearchOptions:
     wg_per_query: int = 0
 
 
+def _copts(o: "SearchOptions", stats_ptr=None) -> _SearchOpts:
+    return _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
+                       o.wg_per_query, 0, stats_ptr)
+
+
+def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width: int = 1,
+             options: Optional["SearchOptions"] = None) -> dict:
+    """The resolved mode and automatic parameters a search with these arguments would use."""
+    plan = _SearchPlan()
+    copts = _copts(options or SearchOptions())
+    _check(load_library().cagra_search_describe(degree, dim, batch, k, itopk, search_width,
+                                                C.byref(copts), C.byref(plan)), "cagra_search_describe")
+    return {n: int(getattr(plan, n)) for n, _ in _SearchPlan._fields_}
+
+
 def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,
            options: Optional[SearchOptions] = None, return_stats: bool = False,
            out: Optional[Tuple] = None, workspace=None):
@@ -146,8 +169,7 @@ def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, m
     B = queries.shape[0]
     o = options or SearchOptions()
     stats = torch.zeros((B, 4), dtype=torch.int32, device=dev) if return_stats else None
-    copts = _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
-                        o.wg_per_query, 0, stats.data_ptr() if stats is not None else None)
+    copts = _copts(o, stats.data_ptr() if stats is not None else None)
     if out is None:
         ids = torch.empty((B, k), dtype=torch.int32, device=dev)
         dists = torch.empty((B, k), dtype=torch.float32, device=dev)

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstdint>
 #include <mutex>
 
@@ -48,7 +49,7 @@ static int auto_team(int dim)
 }
 
 struct SinglePlan {
-    int mr, cr, hash_bits, reset_interval, team_log2, max_iterations;
+    int mr, cr, table_words, reset_interval, team_log2, max_iterations;
     size_t smem;
     int off_query, off_newid, off_newdist, off_parents;
 };
@@ -69,22 +70,28 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
     if (o.max_iterations < 0) return CAGRA_ERR_BAD_OPTION;
     pl.max_iterations = o.max_iterations == 0 ? auto_max_iterations(itopk, width) : o.max_iterations;
 
-    // visited table: must hold itopk + interval * n_cand ids at load <= 1/2 (Sec. IV-B.3)
-    int bits = o.hash_bits;
-    if (bits == 0) {
-        bits = 11;
-        while (bits < 13 && (1 << (bits - 1)) < itopk + n_cand) ++bits;
+    // Visited table in LDS (Sec. IV-B.3).  Between two resets it receives at most
+    // itopk + interval * n_cand ids; probing in LDS is cheap, so it may fill up to 7/8.
+    // Automatic size: 3072 entries (12 KB leaves room for 11 wavefronts per CU, where the
+    // gather bandwidth is still saturated, and keeps enough history that few distances are
+    // computed twice), more if eight passes would not fit, at most 8192.
+    int words;
+    if (o.hash_bits == 0) {
+        const int want = ((itopk + 8 * n_cand) * 8 / 7 + 63) & ~63;
+        words = std::min(8192, std::max(3072, want));
+    } else {
+        if (o.hash_bits < 8 || o.hash_bits > 13) return CAGRA_ERR_BAD_OPTION;
+        words = 1 << o.hash_bits;
     }
-    if (bits < 8 || bits > 13) return CAGRA_ERR_BAD_OPTION;
-    const int capacity = 1 << (bits - 1);
+    const int capacity = words / 8 * 7;
     if (o.reset_interval < 0) return CAGRA_ERR_BAD_OPTION;
     int interval = o.reset_interval;
     if (interval == 0) interval = (capacity - itopk) / n_cand;
     if (interval < 1 || itopk + (int64_t)interval * n_cand > capacity) return CAGRA_ERR_HASH_CAPACITY;
-    pl.hash_bits = bits;
+    pl.table_words = words;
     pl.reset_interval = interval;
 
-    size_t off = (size_t)4 << bits;
+    size_t off = (size_t)4 * words;
     pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
     pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
     pl.off_newdist = (int)off;    off += (size_t)4 * 64 * pl.cr;
@@ -194,6 +201,40 @@ size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_
     return pl.table_bytes + pl.list_bytes + pl.done_bytes;
 }
 
+int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,
+                          int32_t search_width, const cagra_search_opts *opts, cagra_search_plan *plan)
+{
+    cagra_search_opts o = {};
+    if (opts) o = *opts;
+    if (!plan) return CAGRA_ERR_NULL_POINTER;
+    if (dim < 4 || (dim & 3) || B < 0) return CAGRA_ERR_BAD_SHAPE;
+    if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
+    if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
+    if (o.mode < 0 || o.mode > 2) return CAGRA_ERR_BAD_OPTION;
+    cagra_search_plan out = {};
+    out.mode = resolve_mode(o, B, itopk);
+    const DeviceInfo &di = device_info();
+    if (out.mode == 2) {
+        MultiPlan pl;
+        int rc = plan_multi(degree, dim, std::max<int64_t>(B, 1), k, itopk, search_width, o, pl);
+        if (rc != CAGRA_OK) return rc;
+        out.team_size = 1 << pl.team_log2; out.table_entries = 1 << pl.hash_bits; out.reset_interval = 0;
+        out.max_iterations = pl.max_iterations; out.wg_per_query = pl.workers; out.itopk_local = pl.itopk_local;
+        out.lds_bytes = (int32_t)pl.smem; out.workgroups = (int32_t)(B * pl.workers);
+    } else {
+        SinglePlan pl;
+        int rc = plan_single(degree, dim, itopk, search_width, o, pl);
+        if (rc != CAGRA_OK) return rc;
+        out.team_size = 1 << pl.team_log2; out.table_entries = pl.table_words; out.reset_interval = pl.reset_interval;
+        out.max_iterations = pl.max_iterations; out.wg_per_query = 1; out.itopk_local = itopk;
+        out.lds_bytes = (int32_t)pl.smem;
+        int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
+        out.workgroups = (int32_t)std::min<int64_t>(B, (int64_t)std::max(per_cu, 1) * di.cus);
+    }
+    *plan = out;
+    return CAGRA_OK;
+}
+
 int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *dataset, int32_t dim,
                  int64_t ld, cagra_metric metric, const float *queries, int64_t B, int64_t ld_queries,
                  int32_t k, int32_t itopk, int32_t search_width, const cagra_search_opts *opts,
@@ -249,7 +290,7 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *
     P.counter = static_cast<uint32_t *>(workspace);
     P.itopk = itopk; P.search_width = search_width; P.workers = 1;
     P.max_iterations = pl.max_iterations; P.reset_interval = pl.reset_interval;
-    P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
+    P.table_words = pl.table_words; P.team_log2 = pl.team_log2;
     P.off_query = pl.off_query; P.off_newid = pl.off_newid;
     P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
 

@@ -119,16 +119,22 @@ __device__ __forceinline__ uint32_t hash_slot(uint32_t id, int bits)
     return (id * 2654435761u) >> (32 - bits);
 }
 
-// true if id was not in the table (and is now).  `overflow` is raised if no free slot exists.
-__device__ __forceinline__ bool visited_insert(uint32_t *table, int bits, uint32_t id, bool &overflow)
+// Slot of id in a table of `words` entries (any size): multiplicative hash scaled by multiply-shift.
+__device__ __forceinline__ uint32_t hash_slot_words(uint32_t id, uint32_t words)
 {
-    const uint32_t mask = (1u << bits) - 1u;
-    uint32_t s = hash_slot(id, bits);
-    for (uint32_t probe = 0; probe <= mask; ++probe) {
+    return (uint32_t)(((uint64_t)(id * 2654435761u) * words) >> 32);
+}
+
+// LDS table of `words` ids, linear probing.  true if id was not in the table (and is now).
+// `overflow` is raised if no free slot exists.
+__device__ __forceinline__ bool visited_insert(uint32_t *table, uint32_t words, uint32_t id, bool &overflow)
+{
+    uint32_t s = hash_slot_words(id, words);
+    for (uint32_t probe = 0; probe < words; ++probe) {
         uint32_t old = atomicCAS(&table[s], kInvalidId, id);
         if (old == kInvalidId) return true;
         if (old == id) return false;
-        s = (s + 1) & mask;
+        s = s + 1 == words ? 0u : s + 1;
     }
     overflow = true;
     return true;

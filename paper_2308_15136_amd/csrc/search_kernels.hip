@@ -60,7 +60,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     const int t = lane & (team - 1);       // lane within the team
     const int n_cand = P.search_width * P.degree;
     const int nchunk = P.dim >> 2;         // 16-byte pieces per row
-    const int table_words = 1 << P.hash_bits;
+    const int table_words = P.table_words;   // single mode: LDS table
 
     const float *q = P.queries + (size_t)qi * P.ld_queries;
     for (int j = lane; j < P.dim; j += kWave) qlds[j] = q[j];
@@ -92,7 +92,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
             bool isnew = false;
             if (raw[r] != kInvalidId)
                 isnew = MULTI ? visited_insert_global(table, P.hash_bits, raw[r], overflow)
-                              : visited_insert(table, P.hash_bits, raw[r], overflow);
+                              : visited_insert(table, (uint32_t)table_words, raw[r], overflow);
             uint64_t m = __ballot(isnew);
             int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
                                    __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
@@ -181,7 +181,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
             __syncthreads();
 #pragma unroll
             for (int r = 0; r < MR; ++r)
-                if (tlo[r] != kInvalidId) (void)visited_insert(table, P.hash_bits, tlo[r] >> 1, overflow);
+                if (tlo[r] != kInvalidId) (void)visited_insert(table, (uint32_t)table_words, tlo[r] >> 1, overflow);
         }
 
         // ---- step 2: parents = first search_width entries without the flag ----------------

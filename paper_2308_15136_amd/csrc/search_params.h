@@ -23,7 +23,9 @@ struct SearchParams {
     int32_t degree, dim, metric;
     int32_t k, itopk, search_width;   // multi mode: itopk is the per-worker list length, width is 1
     int32_t workers;                  // multi mode: workgroups per query
-    int32_t max_iterations, reset_interval, hash_bits, team_log2;
+    int32_t max_iterations, reset_interval, team_log2;
+    int32_t hash_bits;                // multi mode: log2 of each device-memory table
+    int32_t table_words;              // single mode: entries of the LDS table (multiple of 64)
     // byte offsets into the dynamic LDS block
     int32_t off_query, off_newid, off_newdist, off_parents;
 };

@@ -54,3 +54,17 @@ def test_validation_rejects_before_touching_the_device():
     assert lib.cagra_build(None, 10, 8, 8, 0, 4, 8, None, None, 0, None) == -1
     assert lib.cagra_optimize(None, 10, 8, 4, None, None, None, None, None, 0, None) == -1
     assert lib.cagra_exact_search(None, 10, 8, 8, 0, None, 1, 8, 1, 0, 0, None, None, None, 0, None) == -1
+
+
+def test_describe_reports_the_automatic_parameters():
+    import paper_2308_15136_amd as m
+    p = m.describe(64, 128, 10_000, 10, 128, 1, m.SearchOptions(mode=1))
+    assert p["mode"] == 1 and p["team_size"] == 8 and p["max_iterations"] == 2 * 128 + 32
+    assert p["table_entries"] % 64 == 0
+    assert 128 + p["reset_interval"] * 64 <= p["table_entries"] // 8 * 7
+    q = m.describe(32, 96, 1, 10, 64, 4, m.SearchOptions(mode=2))
+    assert q["mode"] == 2 and q["wg_per_query"] == 4 and q["itopk_local"] == 32
+    assert q["table_entries"] >= 2 * 4 * 32 * (q["max_iterations"] + 1)     # Sec. IV-B.3: at least twice
+    assert m.describe(32, 200, 10_000, 10, 64, 1, m.SearchOptions(mode=1))["team_size"] == 16
+    with pytest.raises(m.CagraError):
+        m.describe(32, 96, 10, 100, 64, 1)          # k > itopk

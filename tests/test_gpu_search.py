@@ -114,16 +114,22 @@ def test_search_matches_oracle(cagra, name, n, nq, degree, k, itopk, width, exac
         assert np.all(st[:, 2] >= ref_st[:, 2])
 
 
-@pytest.mark.parametrize("hash_bits,interval", [(9, 1), (10, 2), (11, 0), (13, 0), (13, 40)])
+@pytest.mark.parametrize("hash_bits,interval", [(9, 1), (10, 2), (11, 0), (13, 0), (13, 40), (0, 0), (0, 3),
+                                                (8, 2)])
 def test_forgettable_table_does_not_change_results(cagra, hash_bits, interval):
     # Sec. IV-B.3: table size and reset interval change the work, not the answer; with the same
     # reset schedule the number of distance computations equals the oracle's simulated forgetting.
     w, g, gt = _setup("sift1m", 20_000, 300, 64)
     gd, bd, qd = _to_dev(w, g)
     opts = cagra.SearchOptions(seed=7, mode=1, hash_bits=hash_bits, reset_interval=interval)
+    plan = cagra.describe(64, 128, 300, 10, 64, 1, opts)
+    entries = (1 << hash_bits) if hash_bits else plan["table_entries"]
+    assert plan["mode"] == 1 and plan["table_entries"] == entries
+    eff = plan["reset_interval"]
+    assert eff == (interval if interval else (entries // 8 * 7 - 64) // 64)
     ids, dists, st = cagra.search(gd, bd, qd, 10, 64, 1, w.metric, opts, return_stats=True)
     st = st.cpu().numpy().view(np.uint32)
-    eff = interval if interval else ((1 << (hash_bits - 1)) - 64) // 64
+    assert not np.any(st[:, 3] & 2)
     ref_ids, ref_d, ref_st = oracle.search(g, w.base, w.queries, 10, 64, 1, w.metric, seed=7,
                                            reset_interval=eff, return_stats=True)
     np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), ref_ids)
@@ -178,7 +184,7 @@ def test_empty_batch_and_rejections(cagra):
     with pytest.raises(cagra.CagraError):
         cagra.search(gd, bd, qd, 10, 64, 1, options=cagra.SearchOptions(mode=1, team_size=3))
     with pytest.raises(cagra.CagraError):
-        cagra.search(gd, bd, qd, 10, 128, 1, options=cagra.SearchOptions(mode=1, hash_bits=8))  # too small
+        cagra.search(gd, bd, qd, 10, 200, 1, options=cagra.SearchOptions(mode=1, hash_bits=8))  # too small
     with pytest.raises(cagra.CagraError):
         cagra.search(gd, bd, qd, 10, 1024, 1, options=cagra.SearchOptions(mode=1))  # single mode: M <= 512
     torch.cuda.synchronize()
