@@ -62,7 +62,10 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=0, help="shrink the base set (debugging only)")
     ap.add_argument("--queries", type=int, default=0)
     ap.add_argument("--itopk", type=int, default=0, help="skip the sweep and time this itopk")
-    ap.add_argument("--cpu-sample", type=int, default=2000, help="queries given to the CPU oracle")
+    ap.add_argument("--cpu-sample", type=int, default=10000, help="queries given to the CPU oracle")
+    ap.add_argument("--no-latency", action="store_true", help="skip the small-batch (multi mode) latency part")
+    ap.add_argument("--latency-workers", type=int, default=8, help="workgroups per query in the latency part")
+    ap.add_argument("--latency-itopk", type=int, default=128)
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from rocprofv3 counters, copied into roofline.traffic")
     ap.add_argument("--no-cpu", action="store_true")
@@ -187,6 +190,41 @@ def main() -> int:
                      "queries_stopped_by_cap": ab["hit_cap"]},
         "sweep": sweep,
     }
+
+    # ---- small batches in multi-workgroup mode: host-side latency per call (Sec. IV-C.2) -------
+    if not args.no_latency:
+        small = []
+        for nb in (1, 10, 100):
+            mopts = cagra.SearchOptions(seed=20230815, mode=2, wg_per_query=args.latency_workers)
+            plan = cagra.describe(w.degree, dim, nb, w.k, args.latency_itopk, 1, mopts)
+            mws = torch.empty(cagra.search_workspace_bytes(N, w.degree, nb, w.k, args.latency_itopk, 1, mopts),
+                              dtype=torch.uint8, device=dev)
+            m_ids = torch.empty((nb, w.k), dtype=torch.int32, device=dev)
+            m_d = torch.empty((nb, w.k), dtype=torch.float32, device=dev)
+            n_calls = 300
+            lat = np.empty(n_calls)
+            for c in range(-10, n_calls):
+                lo = (max(c, 0) * nb) % (B - nb + 1)
+                qs = queries[lo:lo + nb]
+                t_c = time.perf_counter()
+                cagra.search(graph, base, qs, w.k, args.latency_itopk, 1, w.metric, mopts, out=(m_ids, m_d),
+                             workspace=mws)
+                torch.cuda.synchronize()
+                if c >= 0:
+                    lat[c] = (time.perf_counter() - t_c) * 1e6
+            # recall of this mode on the first 1000 queries, in one call (the seed of a query depends on
+            # its index in the call, so this is a separate, untimed measurement)
+            r_ids, _ = cagra.search(graph, base, queries[:1000], w.k, args.latency_itopk, 1, w.metric, mopts)
+            rec_m = recall_at_k(r_ids.cpu().numpy().view(np.uint32), gt_np[:1000])
+            small.append({"batch": nb, "p50_us": round(float(np.percentile(lat, 50)), 1),
+                          "p99_us": round(float(np.percentile(lat, 99)), 1),
+                          "qps": round(nb / (float(np.mean(lat)) * 1e-6), 1),
+                          "workers": plan["wg_per_query"], "itopk": args.latency_itopk,
+                          "itopk_local": plan["itopk_local"], "recall_at_k_b1000": round(rec_m, 5)})
+            log(f"[bench] multi mode batch {nb}: p50 {small[-1]['p50_us']} us  p99 {small[-1]['p99_us']} us")
+        out["small_batch"] = {"mode": "multi-workgroup, host wall-clock per call incl. launch and stream sync",
+                              "dataset": f"{w.name} (the 10M x 96 configuration is not built in this run)",
+                              "results": small}
 
     # ---- CPU oracle on a sample of the same queries (rank 0, N = 1 only) -----------------------
     if not args.no_cpu:

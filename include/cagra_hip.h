@@ -67,7 +67,8 @@ typedef struct {
     int32_t reset_interval;   /* single mode: passes between table resets, 0 automatic (the largest for which
                                  itopk + interval * search_width * degree stays within 7/8 of the table) */
     int32_t wg_per_query;     /* multi mode: workgroups per query, 0 => search_width */
-    int32_t reserved;
+    int32_t table_entries;    /* single mode: entries of the LDS visited table given directly (multiple of 64,
+                                 256..8192); 0 => from hash_bits.  Not both. */
     uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
                                  flags (bit 0: stopped by I_max, bit 1: visited table overflowed) */
 } cagra_search_opts;

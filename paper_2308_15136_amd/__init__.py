@@ -33,7 +33,7 @@ class CagraError(RuntimeError):
 class _SearchOpts(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("max_iterations", C.c_int32), ("mode", C.c_int32),
                 ("team_size", C.c_int32), ("hash_bits", C.c_int32), ("reset_interval", C.c_int32),
-                ("wg_per_query", C.c_int32), ("reserved", C.c_int32), ("stats", C.c_void_p)]
+                ("wg_per_query", C.c_int32), ("table_entries", C.c_int32), ("stats", C.c_void_p)]
 
 
 class _SearchPlan(C.Structure):
@@ -139,11 +139,12 @@ class SearchOptions:
     hash_bits: int = 0
     reset_interval: int = 0
     wg_per_query: int = 0
+    table_entries: int = 0
 
 
 def _copts(o: "SearchOptions", stats_ptr=None) -> _SearchOpts:
     return _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
-                       o.wg_per_query, 0, stats_ptr)
+                       o.wg_per_query, o.table_entries, stats_ptr)
 
 
 def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width: int = 1,
@@ -154,6 +155,13 @@ def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width
     _check(load_library().cagra_search_describe(degree, dim, batch, k, itopk, search_width,
                                                 C.byref(copts), C.byref(plan)), "cagra_search_describe")
     return {n: int(getattr(plan, n)) for n, _ in _SearchPlan._fields_}
+
+
+def search_workspace_bytes(n: int, degree: int, batch: int, k: int, itopk: int, search_width: int = 1,
+                           options: Optional["SearchOptions"] = None) -> int:
+    copts = _copts(options or SearchOptions())
+    return int(load_library().cagra_search_workspace_bytes(n, degree, batch, k, itopk, search_width,
+                                                           C.byref(copts)))
 
 
 def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,

@@ -72,13 +72,18 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
 
     // Visited table in LDS (Sec. IV-B.3).  Between two resets it receives at most
     // itopk + interval * n_cand ids; probing in LDS is cheap, so it may fill up to 7/8.
-    // Automatic size: 3072 entries (12 KB leaves room for 11 wavefronts per CU, where the
-    // gather bandwidth is still saturated, and keeps enough history that few distances are
-    // computed twice), more if eight passes would not fit, at most 8192.
+    // Automatic size: 4096 entries.  Measured on the 1M x 128 workload, 3456..4096 entries are
+    // the flat optimum for itopk 64..256: 16 KB still leaves 9 wavefronts per CU, which with four
+    // rows per team in flight keep the gather bandwidth near its peak, and the longer history
+    // means fewer distances computed twice.  More if eight passes would not fit, at most 8192.
     int words;
-    if (o.hash_bits == 0) {
+    if (o.table_entries != 0) {
+        if (o.hash_bits != 0 || o.table_entries < 256 || o.table_entries > 8192 || (o.table_entries & 63))
+            return CAGRA_ERR_BAD_OPTION;
+        words = o.table_entries;
+    } else if (o.hash_bits == 0) {
         const int want = ((itopk + 8 * n_cand) * 8 / 7 + 63) & ~63;
-        words = std::min(8192, std::max(3072, want));
+        words = std::min(8192, std::max(4096, want));
     } else {
         if (o.hash_bits < 8 || o.hash_bits > 13) return CAGRA_ERR_BAD_OPTION;
         words = 1 << o.hash_bits;

@@ -39,13 +39,19 @@ __device__ __forceinline__ bool visited_insert_global(uint32_t *table, int bits,
     return true;
 }
 
+// dataset rows each team keeps in flight (16 VGPRs apiece)
+#ifndef CAGRA_ROWS_IN_FLIGHT
+#define CAGRA_ROWS_IN_FLIGHT 4
+#endif
+constexpr int kRowsInFlight = CAGRA_ROWS_IN_FLIGHT;
+
 struct QueryStats {
     uint32_t n_iter, n_parent, n_dist, flags;
 };
 
 // The search of one (query, worker): on return thi/tlo hold the sorted top-M list.
 // `table` is the LDS table (single) or this query's device-memory table (multi).
-template <int MR, int CR, bool MULTI>
+template <int MR, int CR, bool MULTI, int RIF>
 __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, int worker,
                                             uint32_t *table, float *qlds, uint32_t *newid,
                                             float *newdist, uint32_t *parents,
@@ -102,51 +108,59 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         __syncthreads();
         n_dist_total += (uint32_t)n_new;
 
-        for (int c0 = 0; c0 < n_new; c0 += 2 * n_teams) {
-            // two dataset rows per team in flight
-            const int ca = c0 + g, cb = c0 + n_teams + g;
-            const bool va = ca < n_new, vb = cb < n_new;
-            const float *rowa = P.dataset + (size_t)(va ? newid[ca] : 0u) * P.ld;
-            const float *rowb = P.dataset + (size_t)(vb ? newid[cb] : 0u) * P.ld;
-            float acca = 0.f, accb = 0.f;
+        for (int c0 = 0; c0 < n_new; c0 += RIF * n_teams) {
+            // RIF dataset rows per team in flight: all loads of a round are issued before any is used
+            const float *row[RIF];
+            bool ok[RIF];
+            float acc[RIF];
+#pragma unroll
+            for (int u = 0; u < RIF; ++u) {
+                const int c = c0 + u * n_teams + g;
+                ok[u] = c < n_new;
+                row[u] = P.dataset + (size_t)(ok[u] ? newid[c] : 0u) * P.ld;
+                acc[u] = 0.f;
+            }
             for (int base = 0; base < nchunk; base += 4 * team) {
-                float4 xa[4], xb[4];
+                float4 x[RIF][4];
+#pragma unroll
+                for (int u = 0; u < RIF; ++u)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int ch = base + i * team + t;
+                        x[u][i] = (ok[u] && ch < nchunk) ? *reinterpret_cast<const float4 *>(row[u] + 4 * ch)
+                                                         : make_float4(0, 0, 0, 0);
+                    }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    int ch = base + i * team + t;
-                    bool in = ch < nchunk;
-                    xa[i] = (va && in) ? *reinterpret_cast<const float4 *>(rowa + 4 * ch) : make_float4(0, 0, 0, 0);
-                    xb[i] = (vb && in) ? *reinterpret_cast<const float4 *>(rowb + 4 * ch) : make_float4(0, 0, 0, 0);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    int ch = base + i * team + t;
+                    const int ch = base + i * team + t;
                     if (ch < nchunk) {
-                        float4 qv = *reinterpret_cast<const float4 *>(qlds + 4 * ch);
+                        const float4 qv = *reinterpret_cast<const float4 *>(qlds + 4 * ch);
                         if (P.metric == 0) {
-                            float d0 = xa[i].x - qv.x, d1 = xa[i].y - qv.y, d2 = xa[i].z - qv.z, d3 = xa[i].w - qv.w;
-                            acca = fmaf(d0, d0, acca); acca = fmaf(d1, d1, acca);
-                            acca = fmaf(d2, d2, acca); acca = fmaf(d3, d3, acca);
-                            float e0 = xb[i].x - qv.x, e1 = xb[i].y - qv.y, e2 = xb[i].z - qv.z, e3 = xb[i].w - qv.w;
-                            accb = fmaf(e0, e0, accb); accb = fmaf(e1, e1, accb);
-                            accb = fmaf(e2, e2, accb); accb = fmaf(e3, e3, accb);
+#pragma unroll
+                            for (int u = 0; u < RIF; ++u) {
+                                const float d0 = x[u][i].x - qv.x, d1 = x[u][i].y - qv.y;
+                                const float d2 = x[u][i].z - qv.z, d3 = x[u][i].w - qv.w;
+                                acc[u] = fmaf(d0, d0, acc[u]); acc[u] = fmaf(d1, d1, acc[u]);
+                                acc[u] = fmaf(d2, d2, acc[u]); acc[u] = fmaf(d3, d3, acc[u]);
+                            }
                         } else {
-                            acca = fmaf(xa[i].x, qv.x, acca); acca = fmaf(xa[i].y, qv.y, acca);
-                            acca = fmaf(xa[i].z, qv.z, acca); acca = fmaf(xa[i].w, qv.w, acca);
-                            accb = fmaf(xb[i].x, qv.x, accb); accb = fmaf(xb[i].y, qv.y, accb);
-                            accb = fmaf(xb[i].z, qv.z, accb); accb = fmaf(xb[i].w, qv.w, accb);
+#pragma unroll
+                            for (int u = 0; u < RIF; ++u) {
+                                acc[u] = fmaf(x[u][i].x, qv.x, acc[u]); acc[u] = fmaf(x[u][i].y, qv.y, acc[u]);
+                                acc[u] = fmaf(x[u][i].z, qv.z, acc[u]); acc[u] = fmaf(x[u][i].w, qv.w, acc[u]);
+                            }
                         }
                     }
                 }
             }
             for (int s = 1; s < team; s <<= 1) {
-                acca += __shfl_xor(acca, s, kWave);
-                accb += __shfl_xor(accb, s, kWave);
+#pragma unroll
+                for (int u = 0; u < RIF; ++u) acc[u] += __shfl_xor(acc[u], s, kWave);
             }
-            if (P.metric != 0) { acca = 0.0f - acca; accb = 0.0f - accb; }
-            if (t == 0) {
-                if (va) newdist[ca] = acca;
-                if (vb) newdist[cb] = accb;
+#pragma unroll
+            for (int u = 0; u < RIF; ++u) {
+                if (P.metric != 0) acc[u] = 0.0f - acc[u];
+                if (t == 0 && ok[u]) newdist[c0 + u * n_teams + g] = acc[u];
             }
         }
         __syncthreads();
@@ -257,7 +271,7 @@ search_single_kernel(const SearchParams P)
         if ((int64_t)qi >= P.B) break;
         uint32_t thi[MR], tlo[MR];
         QueryStats qs;
-        search_body<MR, CR, false>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+        search_body<MR, CR, false, kRowsInFlight>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                                    thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
         if (P.stats != nullptr && lane == 0) {
@@ -278,7 +292,7 @@ search_multi_kernel(const SearchParams P)
     uint32_t *table = P.tables + ((size_t)qi << P.hash_bits);
     uint32_t thi[MR], tlo[MR];
     QueryStats qs;
-    search_body<MR, CR, true>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+    search_body<MR, CR, true, kRowsInFlight>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                               thi, tlo, qs);
     if (P.stats != nullptr && lane == 0) {
         uint32_t *s = P.stats + (size_t)qi * 4;
