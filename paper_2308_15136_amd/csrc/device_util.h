@@ -52,4 +52,28 @@ __device__ __forceinline__ uint32_t shfl_u32(uint32_t v, int src)
     return (uint32_t)__shfl((int)v, src, kWave);
 }
 
+// Value of `v` in another lane of the same 16-lane row, by a DPP move (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <-> 7 - i within each group of 8
+constexpr int kDppMirror = 0x140;       // lane i <-> 15 - i within each row of 16
+
+// Sum over the 2^team_log2 lanes of a team (teams are aligned groups of 4, 8, 16 or 32 lanes;
+// Sec. IV-B.1).  Each step adds the partial sum of the other half; after the first two steps
+// all lanes of a quad agree, so mirrored partners serve as well as xor partners.
+__device__ __forceinline__ float team_sum(float v, int team_log2)
+{
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    if (team_log2 >= 3) v += dpp_f32<kDppHalfMirror>(v);
+    if (team_log2 >= 4) v += dpp_f32<kDppMirror>(v);
+    if (team_log2 >= 5) v += __shfl_xor(v, 16, kWave);
+    return v;
+}
+
 }  // namespace cagra

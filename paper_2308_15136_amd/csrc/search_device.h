@@ -112,6 +112,30 @@ __device__ __forceinline__ void merge_into_topm(uint32_t (&thi)[MR], uint32_t (&
     }
 }
 
+// Ordered insertion of one key (wavefront-uniform) into the sorted list t: entries from its
+// position on move up by one element (one lane to the right, lane 63 into lane 0 of the next
+// register), the last element of the list falls off.
+template <int MR>
+__device__ __forceinline__ void insert_into_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR],
+                                                 uint32_t khi, uint32_t klo, int lane)
+{
+    int pos = 0;   // entries smaller than the key form a prefix of the sorted list
+#pragma unroll
+    for (int r = 0; r < MR; ++r) pos += __popcll(__ballot(key_less(thi[r], tlo[r], khi, klo)));
+#pragma unroll
+    for (int r = MR - 1; r >= 0; --r) {
+        // what arrives in lane 0: the last element of the register below (untouched so far)
+        const uint32_t carry_hi = r > 0 ? __builtin_amdgcn_readlane(thi[r > 0 ? r - 1 : 0], 63) : 0u;
+        const uint32_t carry_lo = r > 0 ? __builtin_amdgcn_readlane(tlo[r > 0 ? r - 1 : 0], 63) : 0u;
+        // DPP wave_shr:1 -- lane i takes lane i-1, lane 0 keeps `old` (the carry)
+        const uint32_t up_hi = (uint32_t)__builtin_amdgcn_update_dpp((int)carry_hi, (int)thi[r], 0x138, 0xF, 0xF, false);
+        const uint32_t up_lo = (uint32_t)__builtin_amdgcn_update_dpp((int)carry_lo, (int)tlo[r], 0x138, 0xF, 0xF, false);
+        const int e = r * 64 + lane;
+        thi[r] = e > pos ? up_hi : (e == pos ? khi : thi[r]);
+        tlo[r] = e > pos ? up_lo : (e == pos ? klo : tlo[r]);
+    }
+}
+
 // ---- visited table (Sec. IV-B.3) -------------------------------------------------------------
 
 __device__ __forceinline__ uint32_t hash_slot(uint32_t id, int bits)

@@ -44,6 +44,13 @@ __device__ __forceinline__ bool visited_insert_global(uint32_t *table, int bits,
 #define CAGRA_ROWS_IN_FLIGHT 4
 #endif
 constexpr int kRowsInFlight = CAGRA_ROWS_IN_FLIGHT;
+constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, registers do not
+
+// at most this many winning candidates are inserted one by one; more go through sort + merge
+#ifndef CAGRA_INSERT_LIMIT
+#define CAGRA_INSERT_LIMIT 8
+#endif
+constexpr int kInsertLimit = CAGRA_INSERT_LIMIT;
 
 struct QueryStats {
     uint32_t n_iter, n_parent, n_dist, flags;
@@ -89,6 +96,10 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 
     uint32_t n_iter = 0, n_parent_total = 0, n_dist_total = 0, flags = 0;
     bool overflow = false;
+    uint32_t ahead[CR];                  // graph row read ahead for the likely next parent
+    uint32_t ahead_id = kInvalidId;
+#pragma unroll
+    for (int r = 0; r < CR; ++r) ahead[r] = kInvalidId;
 
     for (int it = 0;; ++it) {
         // ---- step 3: first-time test, compaction, team distances -------------------------
@@ -99,9 +110,9 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
             if (raw[r] != kInvalidId)
                 isnew = MULTI ? visited_insert_global(table, P.hash_bits, raw[r], overflow)
                               : visited_insert(table, (uint32_t)table_words, raw[r], overflow);
-            uint64_t m = __ballot(isnew);
-            int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                   __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            const uint64_t m = __ballot(isnew);
+            const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                         __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
             if (isnew) newid[pos] = raw[r];
             n_new += __popcll(m);
         }
@@ -153,10 +164,9 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                     }
                 }
             }
-            for (int s = 1; s < team; s <<= 1) {
+            // butterfly over the team's lanes; every lane ends with the same bits
 #pragma unroll
-                for (int u = 0; u < RIF; ++u) acc[u] += __shfl_xor(acc[u], s, kWave);
-            }
+            for (int u = 0; u < RIF; ++u) acc[u] = team_sum(acc[u], team_log2);
 #pragma unroll
             for (int u = 0; u < RIF; ++u) {
                 if (P.metric != 0) acc[u] = 0.0f - acc[u];
@@ -175,15 +185,43 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         // ---- step 1: top-M update (skipped when no candidate can enter) -------------------
         {
             const int last = P.itopk - 1;
-            uint32_t whi = shfl_u32(thi[MR - 1], last & 63), wlo = shfl_u32(tlo[MR - 1], last & 63);
-            bool any = false;
+            // key of the last logical entry (the list's registers are padded to a power of two)
+            uint32_t whi = kDummyHi, wlo = kInvalidId;
 #pragma unroll
-            for (int r = 0; r < CR; ++r) any |= key_less(chi[r], clo[r], whi, wlo);
-            if (__ballot(any) != 0ull) {
-                bitonic_sort<CR>(chi, clo, lane);
-                merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
-                // logical length is itopk: the padding of the last register stays dummy
-                if ((MR - 1) * 64 + lane >= P.itopk) { thi[MR - 1] = kDummyHi; tlo[MR - 1] = kInvalidId; }
+            for (int r = 0; r < MR; ++r)
+                if (r == (last >> 6)) {
+                    whi = __builtin_amdgcn_readlane(thi[r], last & 63);
+                    wlo = __builtin_amdgcn_readlane(tlo[r], last & 63);
+                }
+            uint64_t better[CR];
+            int n_better = 0;
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                better[r] = __ballot(key_less(chi[r], clo[r], whi, wlo));
+                n_better += __popcll(better[r]);
+            }
+            if (n_better != 0) {
+                if (n_better <= kInsertLimit) {
+                    // few winners (the usual case once the list has settled): one ordered
+                    // insertion each instead of the sorting network
+#pragma unroll
+                    for (int r = 0; r < CR; ++r) {
+                        uint64_t m = better[r];
+                        while (m != 0ull) {
+                            const int l = __builtin_ctzll(m);
+                            m &= m - 1;
+                            insert_into_topm<MR>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
+                                                 __builtin_amdgcn_readlane(clo[r], l), lane);
+                        }
+                    }
+                } else {
+                    bitonic_sort<CR>(chi, clo, lane);
+                    merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
+                }
+                // logical length is itopk: whatever lies beyond it is padding and stays dummy
+#pragma unroll
+                for (int r = 0; r < MR; ++r)
+                    if (r * 64 + lane >= P.itopk) { thi[r] = kDummyHi; tlo[r] = kInvalidId; }
             }
         }
         if (it == P.max_iterations) { flags |= 1u; break; }
@@ -216,10 +254,37 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         n_parent_total += (uint32_t)n_par;
         ++n_iter;
         __syncthreads();
+        if (P.search_width == 1) {
+            // One parent per pass: its graph row was usually fetched a pass ago (see below).
+            const uint32_t par = parents[0];
+            if (par == ahead_id) {
 #pragma unroll
-        for (int r = 0; r < CR; ++r) {
-            bool v = slot_parent[r] < n_par;
-            raw[r] = v ? P.graph[(size_t)parents[v ? slot_parent[r] : 0] * P.degree + slot_nbr[r]] : kInvalidId;
+                for (int r = 0; r < CR; ++r) raw[r] = ahead[r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < CR; ++r)
+                    raw[r] = slot_parent[r] == 0 ? P.graph[(size_t)par * P.degree + slot_nbr[r]] : kInvalidId;
+            }
+            // Read ahead: unless this pass finds something closer, the next parent is the first
+            // entry still without the flag; its row travels while this pass computes distances.
+            ahead_id = kInvalidId;
+#pragma unroll
+            for (int r = 0; r < MR; ++r) {
+                const uint64_t m = __ballot((tlo[r] & 1u) == 0u);
+                if (ahead_id == kInvalidId && m != 0ull)
+                    ahead_id = __builtin_amdgcn_readlane(tlo[r], __builtin_ctzll(m)) >> 1;
+            }
+            if (ahead_id != kInvalidId) {
+#pragma unroll
+                for (int r = 0; r < CR; ++r)
+                    ahead[r] = slot_parent[r] == 0 ? P.graph[(size_t)ahead_id * P.degree + slot_nbr[r]] : kInvalidId;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                bool v = slot_parent[r] < n_par;
+                raw[r] = v ? P.graph[(size_t)parents[v ? slot_parent[r] : 0] * P.degree + slot_nbr[r]] : kInvalidId;
+            }
         }
     }
     if (__ballot(overflow) != 0ull) flags |= 2u;
@@ -292,7 +357,7 @@ search_multi_kernel(const SearchParams P)
     uint32_t *table = P.tables + ((size_t)qi << P.hash_bits);
     uint32_t thi[MR], tlo[MR];
     QueryStats qs;
-    search_body<MR, CR, true, kRowsInFlight>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+    search_body<MR, CR, true, kRowsInFlightMulti>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                               thi, tlo, qs);
     if (P.stats != nullptr && lane == 0) {
         uint32_t *s = P.stats + (size_t)qi * 4;

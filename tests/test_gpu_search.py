@@ -87,6 +87,9 @@ CASES = [
     ("tiny", 10_000, 100, 32, 32, 256, 4, False),     # 128 candidates per pass
     ("sift1m", 20_000, 300, 64, 10, 64, 1, True),     # integer data: bit-exact
     ("sift1m", 20_000, 300, 64, 10, 192, 1, True),
+    ("sift1m", 20_000, 300, 64, 10, 150, 1, True),    # list registers padded from 3 to 4: 150 < 192
+    ("sift1m", 20_000, 300, 64, 40, 300, 1, True),    # padded from 5 to 8 registers
+    ("sift1m", 20_000, 300, 64, 10, 65, 2, True),
     ("sift1m", 20_000, 300, 64, 100, 512, 2, True),
     ("sift1m", 20_000, 300, 64, 1, 1, 1, True),       # degenerate: M = k = 1
     ("deep1m", 20_000, 300, 32, 10, 128, 1, False),
