@@ -42,6 +42,15 @@ typedef enum {
     CAGRA_IP = 1
 } cagra_metric;
 
+/* Storage type of the dataset rows given to the search (Sec. IV-C.1: lower-precision storage
+ * relieves the memory-bandwidth limit).  Rows are widened to fp32 in registers and distances
+ * are accumulated in fp32 whatever the storage type; queries are always fp32. */
+typedef enum {
+    CAGRA_F32 = 0,
+    CAGRA_F16 = 1,   /* IEEE binary16 */
+    CAGRA_U8 = 2     /* unsigned bytes 0..255, used as their integer values */
+} cagra_dtype;
+
 typedef enum {
     CAGRA_OK = 0,
     CAGRA_ERR_NULL_POINTER = -1,
@@ -69,6 +78,8 @@ typedef struct {
     int32_t wg_per_query;     /* multi mode: workgroups per query, 0 => search_width */
     int32_t table_entries;    /* single mode: entries of the LDS visited table given directly (multiple of 64,
                                  256..8192); 0 => from hash_bits.  Not both. */
+    int32_t dataset_type;     /* a cagra_dtype: storage type of the rows behind `dataset` (0 = fp32) */
+    int32_t reserved;
     uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
                                  flags (bit 0: stopped by I_max, bit 1: visited table overflowed) */
 } cagra_search_opts;
@@ -82,12 +93,15 @@ typedef struct {
  * unexpanded or I_max passes were made; the first k of the top-M list are
  * written.  ids[B, k] / dists[B, k] come out ascending by (distance, id);
  * if fewer than k nodes were reached the tail is (CAGRA_INVALID_ID, FLT_MAX).
+ * dim and ld (in elements) must be multiples of the elements in 16 bytes of the storage type
+ * (4 for fp32, 8 for fp16, 16 for uint8).
  * Requirements: 1 <= k <= itopk; single mode: itopk <= 512 and
  * search_width * degree <= 256; multi mode: see cagra_search_opts.
  * B == 0 is allowed and does nothing.
  */
 int cagra_search(const uint32_t *graph, int64_t N, int32_t degree,
-                 const float *dataset, int32_t dim, int64_t ld, cagra_metric metric,
+                 const void *dataset /* rows of opts->dataset_type, fp32 if opts is NULL */,
+                 int32_t dim, int64_t ld, cagra_metric metric,
                  const float *queries, int64_t B, int64_t ld_queries,
                  int32_t k, int32_t itopk, int32_t search_width,
                  const cagra_search_opts *opts /* host, may be NULL */,
@@ -170,6 +184,13 @@ int cagra_optimize(const uint32_t *knn, int64_t N, int32_t init_degree, int32_t 
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 size_t cagra_optimize_workspace_bytes(int64_t N, int32_t init_degree, int32_t degree);
+
+/* ---- dataset storage ------------------------------------------------------------------------- */
+
+/* fp32 rows -> fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255).
+ * src[N, dim] with stride ld_src, dst[N, dim] of dst_type with stride ld_dst (both in elements). */
+int cagra_convert_dataset(const float *src, int64_t N, int32_t dim, int64_t ld_src, cagra_dtype dst_type,
+                          void *dst, int64_t ld_dst, void *hip_stream);
 
 /* ---- misc ------------------------------------------------------------------------------------ */
 

@@ -13,6 +13,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import dataclasses
 from dataclasses import dataclass
 from typing import Optional, Tuple
 
@@ -21,6 +22,9 @@ LIB_PATH = os.path.join(_PKG, "libcagra_hip.so")
 
 L2 = 0
 IP = 1
+F32 = 0
+F16 = 1
+U8 = 2
 INVALID_ID = -1  # 0xFFFFFFFF seen through int32
 
 _lib = None
@@ -33,7 +37,8 @@ class CagraError(RuntimeError):
 class _SearchOpts(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("max_iterations", C.c_int32), ("mode", C.c_int32),
                 ("team_size", C.c_int32), ("hash_bits", C.c_int32), ("reset_interval", C.c_int32),
-                ("wg_per_query", C.c_int32), ("table_entries", C.c_int32), ("stats", C.c_void_p)]
+                ("wg_per_query", C.c_int32), ("table_entries", C.c_int32), ("dataset_type", C.c_int32),
+                ("reserved", C.c_int32), ("stats", C.c_void_p)]
 
 
 class _SearchPlan(C.Structure):
@@ -66,6 +71,8 @@ def load_library():
     lib.cagra_search_describe.argtypes = [i32, i32, i64, i32, i32, i32, opts_p, C.POINTER(_SearchPlan)]
     lib.cagra_search_workspace_bytes.restype = sz
     lib.cagra_search_workspace_bytes.argtypes = [i64, i32, i64, i32, i32, i32, opts_p]
+    lib.cagra_convert_dataset.restype = C.c_int
+    lib.cagra_convert_dataset.argtypes = [vp, i64, i32, i64, C.c_int, vp, i64, vp]
     lib.cagra_exact_search.restype = C.c_int
     lib.cagra_exact_search.argtypes = [vp, i64, i32, i64, C.c_int, vp, i64, i64, i32, i32, i64,
                                        vp, vp, vp, sz, vp]
@@ -105,6 +112,26 @@ def _dev_f32(t, name):
     return t
 
 
+def _dev_dataset(t):
+    """A dataset for the search: float32, float16 or uint8 rows; returns (tensor, cagra_dtype)."""
+    torch = _torch()
+    kinds = {torch.float32: F32, torch.float16: F16, torch.uint8: U8}
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype in kinds and t.dim() == 2 and t.stride(1) == 1):
+        raise TypeError("dataset must be a 2-D float32 / float16 / uint8 device tensor with unit inner stride")
+    return t, kinds[t.dtype]
+
+
+def convert_dataset(dataset, dtype: int):
+    """fp32 dataset -> fp16 or uint8 copy (rounded to nearest even; uint8 clamped to 0..255)."""
+    torch = _torch()
+    dataset = _dev_f32(dataset, "dataset")
+    out = torch.empty(dataset.shape, dtype={F16: torch.float16, U8: torch.uint8}[dtype], device=dataset.device)
+    _check(load_library().cagra_convert_dataset(dataset.data_ptr(), dataset.shape[0], dataset.shape[1],
+                                                dataset.stride(0), dtype, out.data_ptr(), out.stride(0),
+                                                _stream(dataset.device)), "cagra_convert_dataset")
+    return out
+
+
 def _dev_i32(t, name):
     torch = _torch()
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
@@ -140,11 +167,12 @@ class SearchOptions:
     reset_interval: int = 0
     wg_per_query: int = 0
     table_entries: int = 0
+    dataset_type: int = 0      # F32 / F16 / U8; search() sets it from the dataset tensor's dtype
 
 
 def _copts(o: "SearchOptions", stats_ptr=None) -> _SearchOpts:
     return _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
-                       o.wg_per_query, o.table_entries, stats_ptr)
+                       o.wg_per_query, o.table_entries, o.dataset_type, 0, stats_ptr)
 
 
 def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width: int = 1,
@@ -171,11 +199,11 @@ def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, m
     torch = _torch()
     lib = load_library()
     graph = _dev_i32(graph, "graph")
-    dataset = _dev_f32(dataset, "dataset")
+    dataset, dtype = _dev_dataset(dataset)
     queries = _dev_f32(queries, "queries")
     dev = dataset.device
     B = queries.shape[0]
-    o = options or SearchOptions()
+    o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype)
     stats = torch.zeros((B, 4), dtype=torch.int32, device=dev) if return_stats else None
     copts = _copts(o, stats.data_ptr() if stats is not None else None)
     if out is None:

@@ -40,12 +40,17 @@ const DeviceInfo &device_info()
 static int auto_max_iterations(int itopk, int width) { return 2 * ((itopk + width - 1) / width) + 32; }
 
 // Smallest team whose lanes cover a row in at most four 16-byte loads each (Sec. IV-B.1).
-static int auto_team(int dim)
+static int auto_team(int chunks)
 {
-    int chunks = dim / 4;
     for (int team = 4; team <= 32; team *= 2)
         if ((chunks + team - 1) / team <= 4) return team;
     return 32;
+}
+
+// elements of the dataset's storage type in one 16-byte piece (0 for an unknown type)
+static int elems_per_piece(int dataset_type)
+{
+    return dataset_type == CAGRA_F32 ? 4 : dataset_type == CAGRA_F16 ? 8 : dataset_type == CAGRA_U8 ? 16 : 0;
 }
 
 struct SinglePlan {
@@ -56,6 +61,7 @@ struct SinglePlan {
 
 static int plan_single(int degree, int dim, int itopk, int width, const cagra_search_opts &o, SinglePlan &pl)
 {
+    const int pieces = dim / elems_per_piece(o.dataset_type);   // 16-byte pieces per dataset row
     if (itopk > 512) return CAGRA_ERR_BAD_TOPK;
     const int n_cand = width * degree;
     if (n_cand > 256) return CAGRA_ERR_BAD_TOPK;
@@ -63,7 +69,7 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
     pl.mr = mr <= 1 ? 1 : mr <= 2 ? 2 : mr <= 4 ? 4 : 8;
     pl.cr = n_cand <= 64 ? 1 : n_cand <= 128 ? 2 : 4;
 
-    int team = o.team_size == 0 ? auto_team(dim) : o.team_size;
+    int team = o.team_size == 0 ? auto_team(pieces) : o.team_size;
     if (team != 4 && team != 8 && team != 16 && team != 32) return CAGRA_ERR_BAD_OPTION;
     pl.team_log2 = team == 4 ? 2 : team == 8 ? 3 : team == 16 ? 4 : 5;
 
@@ -120,6 +126,7 @@ struct MultiPlan {
 static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int width,
                       const cagra_search_opts &o, MultiPlan &pl)
 {
+    const int pieces = dim / elems_per_piece(o.dataset_type);
     if (o.wg_per_query < 0 || o.wg_per_query > 1024) return CAGRA_ERR_BAD_OPTION;
     pl.workers = o.wg_per_query == 0 ? width : o.wg_per_query;
     if (pl.workers > 1024 || B * pl.workers > 0x7FFFFFFFll) return CAGRA_ERR_BAD_OPTION;
@@ -131,7 +138,7 @@ static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int widt
     int mr = (local + 63) / 64;
     pl.mr = mr <= 1 ? 1 : mr <= 2 ? 2 : mr <= 4 ? 4 : 8;
     pl.cr = degree <= 64 ? 1 : degree <= 128 ? 2 : 4;
-    int team = o.team_size == 0 ? auto_team(dim) : o.team_size;
+    int team = o.team_size == 0 ? auto_team(pieces) : o.team_size;
     if (team != 4 && team != 8 && team != 16 && team != 32) return CAGRA_ERR_BAD_OPTION;
     pl.team_log2 = team == 4 ? 2 : team == 8 ? 3 : team == 16 ? 4 : 5;
     if (o.max_iterations < 0) return CAGRA_ERR_BAD_OPTION;
@@ -200,9 +207,10 @@ size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_
     cagra_search_opts o = {};
     if (opts) o = *opts;
     if (B < 1 || degree < 1 || k < 1 || itopk < 1 || search_width < 1) return 256;
+    if (elems_per_piece(o.dataset_type) == 0) return 256;
     if (resolve_mode(o, B, itopk) == 1) return 256;  // the persistent-scheduling counter
     MultiPlan pl;
-    if (plan_multi(degree, 4, B, k, itopk, search_width, o, pl) != CAGRA_OK) return 256;
+    if (plan_multi(degree, 16, B, k, itopk, search_width, o, pl) != CAGRA_OK) return 256;
     return pl.table_bytes + pl.list_bytes + pl.done_bytes;
 }
 
@@ -212,7 +220,8 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
     cagra_search_opts o = {};
     if (opts) o = *opts;
     if (!plan) return CAGRA_ERR_NULL_POINTER;
-    if (dim < 4 || (dim & 3) || B < 0) return CAGRA_ERR_BAD_SHAPE;
+    if (elems_per_piece(o.dataset_type) == 0) return CAGRA_ERR_BAD_OPTION;
+    if (dim < 4 || (dim % elems_per_piece(o.dataset_type)) || B < 0) return CAGRA_ERR_BAD_SHAPE;
     if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
     if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
     if (o.mode < 0 || o.mode > 2) return CAGRA_ERR_BAD_OPTION;
@@ -240,7 +249,7 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
     return CAGRA_OK;
 }
 
-int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *dataset, int32_t dim,
+int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const void *dataset, int32_t dim,
                  int64_t ld, cagra_metric metric, const float *queries, int64_t B, int64_t ld_queries,
                  int32_t k, int32_t itopk, int32_t search_width, const cagra_search_opts *opts,
                  uint32_t *ids_out, float *dists_out, void *workspace, size_t workspace_bytes,
@@ -250,7 +259,9 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *
     if (opts) o = *opts;
     if (!graph || !dataset) return CAGRA_ERR_NULL_POINTER;
     if (B > 0 && (!queries || !ids_out || !dists_out)) return CAGRA_ERR_NULL_POINTER;
-    if (N < 1 || N > 0x7FFFFFFFll || dim < 4 || (dim & 3) || ld < dim || (ld & 3) || B < 0 ||
+    const int epp = elems_per_piece(o.dataset_type);
+    if (epp == 0) return CAGRA_ERR_BAD_OPTION;
+    if (N < 1 || N > 0x7FFFFFFFll || dim < 4 || (dim % epp) || ld < dim || (ld % epp) || B < 0 ||
         B > 0x7FFFFFFFll || ld_queries < dim)
         return CAGRA_ERR_BAD_SHAPE;
     if (((uintptr_t)dataset & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
@@ -284,7 +295,9 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *
         P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
         P.off_query = pl.off_query; P.off_newid = pl.off_newid;
         P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
-        hipError_t e = launch_search_multi(P, pl.mr, pl.cr, pl.smem, stream);
+        hipError_t e = o.dataset_type == CAGRA_F32   ? launch_search_multi_f32(P, pl.mr, pl.cr, pl.smem, stream)
+                       : o.dataset_type == CAGRA_F16 ? launch_search_multi_f16(P, pl.mr, pl.cr, pl.smem, stream)
+                                                     : launch_search_multi_u8(P, pl.mr, pl.cr, pl.smem, stream);
         return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
     }
 
@@ -304,7 +317,20 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const float *
     int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
     if (per_cu < 1) per_cu = 1;
     int grid = (int)std::min<int64_t>(B, (int64_t)per_cu * di.cus);
-    hipError_t e = launch_search_single(P, pl.mr, pl.cr, grid, pl.smem, stream);
+    hipError_t e = o.dataset_type == CAGRA_F32   ? launch_search_single_f32(P, pl.mr, pl.cr, grid, pl.smem, stream)
+                   : o.dataset_type == CAGRA_F16 ? launch_search_single_f16(P, pl.mr, pl.cr, grid, pl.smem, stream)
+                                                 : launch_search_single_u8(P, pl.mr, pl.cr, grid, pl.smem, stream);
+    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+}
+
+int cagra_convert_dataset(const float *src, int64_t N, int32_t dim, int64_t ld_src, cagra_dtype dst_type,
+                          void *dst, int64_t ld_dst, void *hip_stream)
+{
+    if (!src || !dst) return CAGRA_ERR_NULL_POINTER;
+    if (dst_type != CAGRA_F16 && dst_type != CAGRA_U8) return CAGRA_ERR_BAD_OPTION;
+    if (N < 0 || N > 0x7FFFFFFFll || dim < 1 || ld_src < dim || ld_dst < dim) return CAGRA_ERR_BAD_SHAPE;
+    if (N == 0) return CAGRA_OK;
+    hipError_t e = launch_convert(src, N, dim, ld_src, (int)dst_type, dst, ld_dst, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
 }
 

@@ -1,6 +1,7 @@
 // Device-side helpers shared by the gfx950 kernels of this library.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 namespace cagra {

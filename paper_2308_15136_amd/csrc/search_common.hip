@@ -1,0 +1,59 @@
+// Small helper kernels of the search entry points, shared by all dataset storage types, and
+// the conversion of an fp32 dataset to the narrower storage types.
+#include "device_util.h"
+#include "search_params.h"
+
+namespace cagra {
+
+__global__ void zero_counter_kernel(uint32_t *counter) { *counter = 0u; }
+
+// multi mode: empty visited tables, zero the per-query counters and the statistics
+__global__ void multi_init_kernel(uint32_t *tables, size_t table_words_total, uint32_t *done, uint32_t *stats, int64_t B)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < table_words_total) tables[i] = kInvalidId;
+    if (i < (size_t)B) done[i] = 0u;
+    if (stats != nullptr && i < (size_t)B * 4) stats[i] = 0u;
+}
+
+void launch_zero_counter(uint32_t *counter, hipStream_t stream)
+{
+    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, stream, counter);
+}
+
+void launch_multi_init(const SearchParams &P, hipStream_t stream)
+{
+    const size_t words = (size_t)P.B << P.hash_bits;
+    const size_t n = words > (size_t)P.B * 4 ? words : (size_t)P.B * 4;
+    hipLaunchKernelGGL(multi_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                       P.tables, words, P.done, P.stats, P.B);
+}
+
+// fp32 -> fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255)
+__global__ void convert_kernel(const float *__restrict__ src, int64_t rows, int dim, int64_t ld_src,
+                               int elem, void *__restrict__ dst, int64_t ld_dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows * dim) return;
+    const int64_t r = i / dim;
+    const int c = (int)(i - r * dim);
+    const float v = src[r * ld_src + c];
+    if (elem == 1) {
+        static_cast<__half *>(dst)[r * ld_dst + c] = __float2half_rn(v);
+    } else {
+        float t = rintf(v);
+        t = t < 0.f ? 0.f : (t > 255.f ? 255.f : t);
+        static_cast<unsigned char *>(dst)[r * ld_dst + c] = (unsigned char)t;
+    }
+}
+
+hipError_t launch_convert(const float *src, int64_t rows, int dim, int64_t ld_src, int elem, void *dst,
+                          int64_t ld_dst, hipStream_t stream)
+{
+    const int64_t n = rows * dim;
+    hipLaunchKernelGGL(convert_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, src, rows, dim,
+                       ld_src, elem, dst, ld_dst);
+    return hipGetLastError();
+}
+
+}  // namespace cagra

@@ -18,11 +18,43 @@
 // Multi mode (Sec. IV-C.2): `workers` workgroups per query, each with one parent per pass,
 // its own seeds and its own list, sharing one visited table in device memory; the last
 // worker of a query to finish merges the lists and writes the result.
+//
+// This file is the implementation shared by the three storage types of the dataset; it is
+// included by search_kernels_f32.hip, _f16.hip and _u8.hip, each of which sets CAGRA_ELEM
+// (0 fp32, 1 fp16, 2 uint8).  Rows are always fetched as 16-byte pieces and widened to fp32
+// in registers; distances are accumulated in fp32 (Sec. IV-C.1, last paragraph: lower
+// precision storage relieves the memory-bandwidth limit).
 #include "device_util.h"
 #include "search_device.h"
 #include "search_params.h"
 
+#ifndef CAGRA_ELEM
+#error "include this file from search_kernels_<type>.hip"
+#endif
+
 namespace cagra {
+
+constexpr int kElem = CAGRA_ELEM;
+constexpr int kElemsPerPiece = kElem == 0 ? 4 : kElem == 1 ? 8 : 16;   // elements in 16 bytes
+constexpr int kElemBytes = 16 / kElemsPerPiece;
+
+// The i-th group of four consecutive elements of a 16-byte piece, widened to fp32.
+__device__ __forceinline__ float4 widen4(const uint4 &p, int i)
+{
+    const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+    if constexpr (kElem == 0) {
+        return make_float4(__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3]));
+    } else if constexpr (kElem == 1) {
+        const uint32_t a = w[2 * i], b = w[2 * i + 1];
+        return make_float4(__half2float(__ushort_as_half((unsigned short)(a & 0xFFFFu))),
+                           __half2float(__ushort_as_half((unsigned short)(a >> 16))),
+                           __half2float(__ushort_as_half((unsigned short)(b & 0xFFFFu))),
+                           __half2float(__ushort_as_half((unsigned short)(b >> 16))));
+    } else {
+        const uint32_t a = w[i];
+        return make_float4((float)(a & 0xFFu), (float)((a >> 8) & 0xFFu), (float)((a >> 16) & 0xFFu), (float)(a >> 24));
+    }
+}
 
 // true if id was not in the device-memory table (and is now)
 __device__ __forceinline__ bool visited_insert_global(uint32_t *table, int bits, uint32_t id, bool &overflow)
@@ -72,7 +104,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     const int g = lane >> team_log2;       // team of this lane
     const int t = lane & (team - 1);       // lane within the team
     const int n_cand = P.search_width * P.degree;
-    const int nchunk = P.dim >> 2;         // 16-byte pieces per row
+    const int nchunk = P.dim / kElemsPerPiece;   // 16-byte pieces per row
     const int table_words = P.table_words;   // single mode: LDS table
 
     const float *q = P.queries + (size_t)qi * P.ld_queries;
@@ -121,44 +153,48 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 
         for (int c0 = 0; c0 < n_new; c0 += RIF * n_teams) {
             // RIF dataset rows per team in flight: all loads of a round are issued before any is used
-            const float *row[RIF];
+            const unsigned char *row[RIF];
             bool ok[RIF];
             float acc[RIF];
 #pragma unroll
             for (int u = 0; u < RIF; ++u) {
                 const int c = c0 + u * n_teams + g;
                 ok[u] = c < n_new;
-                row[u] = P.dataset + (size_t)(ok[u] ? newid[c] : 0u) * P.ld;
+                row[u] = static_cast<const unsigned char *>(P.dataset) + (size_t)(ok[u] ? newid[c] : 0u) * P.ld * kElemBytes;
                 acc[u] = 0.f;
             }
             for (int base = 0; base < nchunk; base += 4 * team) {
-                float4 x[RIF][4];
+                uint4 x[RIF][4];
 #pragma unroll
                 for (int u = 0; u < RIF; ++u)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int ch = base + i * team + t;
-                        x[u][i] = (ok[u] && ch < nchunk) ? *reinterpret_cast<const float4 *>(row[u] + 4 * ch)
-                                                         : make_float4(0, 0, 0, 0);
+                        x[u][i] = (ok[u] && ch < nchunk) ? *reinterpret_cast<const uint4 *>(row[u] + 16 * ch)
+                                                         : make_uint4(0, 0, 0, 0);
                     }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int ch = base + i * team + t;
                     if (ch < nchunk) {
-                        const float4 qv = *reinterpret_cast<const float4 *>(qlds + 4 * ch);
-                        if (P.metric == 0) {
 #pragma unroll
-                            for (int u = 0; u < RIF; ++u) {
-                                const float d0 = x[u][i].x - qv.x, d1 = x[u][i].y - qv.y;
-                                const float d2 = x[u][i].z - qv.z, d3 = x[u][i].w - qv.w;
-                                acc[u] = fmaf(d0, d0, acc[u]); acc[u] = fmaf(d1, d1, acc[u]);
-                                acc[u] = fmaf(d2, d2, acc[u]); acc[u] = fmaf(d3, d3, acc[u]);
-                            }
-                        } else {
+                        for (int h = 0; h < kElemsPerPiece / 4; ++h) {
+                            const float4 qv = *reinterpret_cast<const float4 *>(qlds + kElemsPerPiece * ch + 4 * h);
+                            if (P.metric == 0) {
 #pragma unroll
-                            for (int u = 0; u < RIF; ++u) {
-                                acc[u] = fmaf(x[u][i].x, qv.x, acc[u]); acc[u] = fmaf(x[u][i].y, qv.y, acc[u]);
-                                acc[u] = fmaf(x[u][i].z, qv.z, acc[u]); acc[u] = fmaf(x[u][i].w, qv.w, acc[u]);
+                                for (int u = 0; u < RIF; ++u) {
+                                    const float4 xv = widen4(x[u][i], h);
+                                    const float d0 = xv.x - qv.x, d1 = xv.y - qv.y, d2 = xv.z - qv.z, d3 = xv.w - qv.w;
+                                    acc[u] = fmaf(d0, d0, acc[u]); acc[u] = fmaf(d1, d1, acc[u]);
+                                    acc[u] = fmaf(d2, d2, acc[u]); acc[u] = fmaf(d3, d3, acc[u]);
+                                }
+                            } else {
+#pragma unroll
+                                for (int u = 0; u < RIF; ++u) {
+                                    const float4 xv = widen4(x[u][i], h);
+                                    acc[u] = fmaf(xv.x, qv.x, acc[u]); acc[u] = fmaf(xv.y, qv.y, acc[u]);
+                                    acc[u] = fmaf(xv.z, qv.z, acc[u]); acc[u] = fmaf(xv.w, qv.w, acc[u]);
+                                }
                             }
                         }
                     }
@@ -322,7 +358,7 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
         slot_nbr[r] = c - slot_parent[r] * P.degree;                             \
     }
 
-template <int MR, int CR>
+template <int ELEM, int MR, int CR>
 __global__ void __launch_bounds__(kWave)
 search_single_kernel(const SearchParams P)
 {
@@ -347,7 +383,7 @@ search_single_kernel(const SearchParams P)
     }
 }
 
-template <int MR, int CR>
+template <int ELEM, int MR, int CR>
 __global__ void __launch_bounds__(kWave)
 search_multi_kernel(const SearchParams P)
 {
@@ -392,36 +428,24 @@ search_multi_kernel(const SearchParams P)
     write_result<MR>(P, qi, thi, tlo);
 }
 
-__global__ void zero_counter_kernel(uint32_t *counter) { *counter = 0u; }
-
-// multi mode: empty visited tables, zero the per-query counters and the statistics
-__global__ void multi_init_kernel(uint32_t *tables, size_t table_words_total, uint32_t *done, uint32_t *stats, int64_t B)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < table_words_total) tables[i] = kInvalidId;
-    if (i < (size_t)B) done[i] = 0u;
-    if (stats != nullptr && i < (size_t)B * 4) stats[i] = 0u;
-}
-
 template <int MR, int CR>
 static hipError_t launch_single_one(const SearchParams &P, int grid, size_t smem, hipStream_t stream)
 {
-    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, stream, P.counter);
-    hipLaunchKernelGGL((search_single_kernel<MR, CR>), dim3(grid), dim3(kWave), smem, stream, P);
+    launch_zero_counter(P.counter, stream);
+    hipLaunchKernelGGL((search_single_kernel<kElem, MR, CR>), dim3(grid), dim3(kWave), smem, stream, P);
     return hipGetLastError();
 }
 
 template <int MR, int CR>
 static hipError_t launch_multi_one(const SearchParams &P, size_t smem, hipStream_t stream)
 {
-    const size_t words = (size_t)P.B << P.hash_bits;
-    const size_t n = words > (size_t)P.B * 4 ? words : (size_t)P.B * 4;
-    hipLaunchKernelGGL(multi_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
-                       P.tables, words, P.done, P.stats, P.B);
-    hipLaunchKernelGGL((search_multi_kernel<MR, CR>), dim3((unsigned)(P.B * P.workers)), dim3(kWave), smem, stream, P);
+    launch_multi_init(P, stream);
+    hipLaunchKernelGGL((search_multi_kernel<kElem, MR, CR>), dim3((unsigned)(P.B * P.workers)), dim3(kWave), smem, stream, P);
     return hipGetLastError();
 }
 
+#define CAGRA_CAT_(a, b) a##b
+#define CAGRA_CAT(a, b) CAGRA_CAT_(a, b)
 #define CAGRA_DISPATCH(FN, ...)                                                          \
     switch (mr * 8 + cr) {                                                               \
         case 1 * 8 + 1: return FN<1, 1>(__VA_ARGS__);                                    \
@@ -439,12 +463,12 @@ static hipError_t launch_multi_one(const SearchParams &P, size_t smem, hipStream
     }                                                                                    \
     return hipErrorInvalidValue;
 
-hipError_t launch_search_single(const SearchParams &P, int mr, int cr, int grid, size_t smem, hipStream_t stream)
+hipError_t CAGRA_CAT(launch_search_single_, CAGRA_ELEM_NAME)(const SearchParams &P, int mr, int cr, int grid, size_t smem, hipStream_t stream)
 {
     CAGRA_DISPATCH(launch_single_one, P, grid, smem, stream)
 }
 
-hipError_t launch_search_multi(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream)
+hipError_t CAGRA_CAT(launch_search_multi_, CAGRA_ELEM_NAME)(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream)
 {
     CAGRA_DISPATCH(launch_multi_one, P, smem, stream)
 }

@@ -7,7 +7,7 @@ namespace cagra {
 
 struct SearchParams {
     const uint32_t *graph;
-    const float *dataset;
+    const void *dataset;  // rows of fp32, fp16 or uint8, see the kernel's element type
     const float *queries;
     uint32_t *ids_out;
     float *dists_out;
@@ -30,8 +30,19 @@ struct SearchParams {
     int32_t off_query, off_newid, off_newdist, off_parents;
 };
 
-hipError_t launch_search_single(const SearchParams &P, int mr, int cr, int grid, size_t smem,
-                                hipStream_t stream);
-hipError_t launch_search_multi(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream);
+// One launcher pair per storage type of the dataset (fp32, fp16, uint8).
+#define CAGRA_DECLARE_LAUNCHERS(T)                                                                  \
+    hipError_t launch_search_single_##T(const SearchParams &P, int mr, int cr, int grid, size_t smem, \
+                                        hipStream_t stream);                                        \
+    hipError_t launch_search_multi_##T(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream);
+CAGRA_DECLARE_LAUNCHERS(f32)
+CAGRA_DECLARE_LAUNCHERS(f16)
+CAGRA_DECLARE_LAUNCHERS(u8)
+#undef CAGRA_DECLARE_LAUNCHERS
+
+void launch_zero_counter(uint32_t *counter, hipStream_t stream);
+void launch_multi_init(const SearchParams &P, hipStream_t stream);
+hipError_t launch_convert(const float *src, int64_t rows, int dim, int64_t ld_src, int elem, void *dst,
+                          int64_t ld_dst, hipStream_t stream);
 
 }  // namespace cagra
