@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from rocprofv3 counters, copied into roofline.traffic")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-storage", action="store_true", help="skip the fp16 / uint8 storage part")
+    ap.add_argument("--no-reference", action="store_true", help="skip the stream / row-gather bandwidth references")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for rocprofv3 counters)")
     args = ap.parse_args()
@@ -190,6 +192,72 @@ def main() -> int:
                      "queries_stopped_by_cap": ab["hit_cap"]},
         "sweep": sweep,
     }
+
+    # ---- the same search over narrower storage of the same rows (Sec. IV-C.1, last paragraph) ----
+    if not args.no_storage:
+        narrow = []
+        for name, code, width_b in (("f16", cagra.F16, 2), ("u8", cagra.U8, 1)):
+            if dim % (16 // width_b) != 0 or (code == cagra.U8 and w.name != "sift1m"):
+                continue            # uint8 only where the values are integers 0..255
+            conv = cagra.convert_dataset(base, code)
+            n_ids = torch.empty((B, w.k), dtype=torch.int32, device=dev)
+            n_d = torch.empty((B, w.k), dtype=torch.float32, device=dev)
+
+            def run_n(stats=False):
+                return cagra.search(graph, conv, queries, w.k, M, w.search_width, w.metric, opts,
+                                    return_stats=stats, out=(n_ids, n_d), workspace=ws)
+            _, _, st_n = run_n(True)
+            torch.cuda.synchronize()
+            rec_n = recall_at_k(n_ids.cpu().numpy().view(np.uint32), gt_np)
+            for _ in range(2):
+                run_n()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                run_n()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            nd = int(st_n.cpu().numpy().view(np.uint32)[:, 2].astype(np.int64).sum())
+            narrow.append({"storage": name, "itopk": M, "recall_at_k": round(rec_n, 5), "kernel_ms": round(ms, 4),
+                           "qps_kernel": round(B / (ms * 1e-3), 1),
+                           "gathered_vector_GBs": round(nd * dim * width_b / (ms * 1e-3) / 1e9, 1),
+                           "same_ids_as_fp32": bool(torch.equal(n_ids, ids))})
+            log(f"[bench] storage {name}: recall {rec_n:.4f}  {ms:.3f} ms  {narrow[-1]['qps_kernel']:.0f} QPS")
+            del conv
+        out["narrow_storage"] = narrow
+
+    # ---- what the device delivers for the access patterns alone (no method arithmetic) ---------
+    if not args.no_reference:
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+
+        def time_probe(reps, **kw):
+            cagra.probe_bandwidth(base, sink=sink, **kw)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for r in range(reps):
+                cagra.probe_bandwidth(base, sink=sink, seed=r, **kw)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        n_read = ab["n_dist"]
+        ms_stream = time_probe(10, pattern=0)
+        ref = {"stream_read_GBs": round(N * dim * 4 / (ms_stream * 1e-3) / 1e9, 1), "row_bytes": dim * 4,
+               "rows_gathered": n_read, "row_gather": []}
+        best = 0.0
+        for rif in (4, 8):
+            for wpc in (8, 16):
+                ms_g = time_probe(5, pattern=1, n_read=n_read, rows_in_flight=rif, waves_per_cu=wpc)
+                gbs = n_read * dim * 4 / (ms_g * 1e-3) / 1e9
+                best = max(best, gbs)
+                ref["row_gather"].append({"rows_in_flight": rif, "waves_per_cu": wpc, "GBs": round(gbs, 1)})
+        ref["best_row_gather_GBs"] = round(best, 1)
+        ref["search_vs_best_row_gather"] = round(out["roofline"]["gathered_vector_GBs"] / best, 4)
+        out["hbm_reference"] = ref
+        log(f"[bench] reference: stream read {ref['stream_read_GBs']} GB/s, random {dim * 4}-byte rows "
+            f"{ref['best_row_gather_GBs']} GB/s")
 
     # ---- small batches in multi-workgroup mode: host-side latency per call (Sec. IV-C.2) -------
     if not args.no_latency:

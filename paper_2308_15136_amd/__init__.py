@@ -86,6 +86,8 @@ def load_library():
     lib.cagra_optimize.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.cagra_optimize_workspace_bytes.restype = sz
     lib.cagra_optimize_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.cagra_probe_bandwidth.restype = C.c_int
+    lib.cagra_probe_bandwidth.argtypes = [vp, i64, i64, i64, i32, i64, i32, i32, i32, C.c_uint64, vp, vp]
     _lib = lib
     return lib
 
@@ -130,6 +132,22 @@ def convert_dataset(dataset, dtype: int):
                                                 dataset.stride(0), dtype, out.data_ptr(), out.stride(0),
                                                 _stream(dataset.device)), "cagra_convert_dataset")
     return out
+
+
+def probe_bandwidth(data, pattern: int, n_read: int = 0, team_size: int = 0, rows_in_flight: int = 0,
+                    waves_per_cu: int = 0, seed: int = 0, sink=None) -> None:
+    """Enqueue one bandwidth-reference read of the 2-D device tensor `data` (pattern 0: streaming
+    read of all of it, 1: n_read random whole rows).  The caller times it."""
+    torch = _torch()
+    if not (isinstance(data, torch.Tensor) and data.is_cuda and data.dim() == 2 and data.stride(1) == 1):
+        raise TypeError("data must be a 2-D device tensor with unit inner stride")
+    es = data.element_size()
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int32, device=data.device)
+    _check(load_library().cagra_probe_bandwidth(data.data_ptr(), data.shape[0], data.shape[1] * es,
+                                                data.stride(0) * es, pattern, n_read, team_size, rows_in_flight,
+                                                waves_per_cu, seed, sink.data_ptr(), _stream(data.device)),
+           "cagra_probe_bandwidth")
 
 
 def _dev_i32(t, name):
