@@ -59,7 +59,7 @@ typedef enum {
     CAGRA_ERR_BAD_TOPK = -4,       /* k, itopk, search_width out of range */
     CAGRA_ERR_BAD_OPTION = -5,     /* a cagra_search_opts field is not supported */
     CAGRA_ERR_WORKSPACE = -6,      /* workspace missing, misaligned or too small */
-    CAGRA_ERR_HASH_CAPACITY = -7,  /* visited table cannot hold itopk + interval * width * degree at load 7/8 */
+    CAGRA_ERR_HASH_CAPACITY = -7,  /* periodic-reset table cannot hold itopk + interval * width * degree at load 7/8 */
     CAGRA_ERR_LAUNCH = -8          /* the HIP runtime refused a launch */
 } cagra_status;
 
@@ -71,15 +71,23 @@ typedef struct {
     int32_t max_iterations;   /* I_max; 0 => 2 * ceil(itopk / search_width) + 32 */
     int32_t mode;             /* 0 automatic (Sec. IV-C.3), 1 single workgroup per query, 2 several */
     int32_t team_size;        /* lanes per distance computation: 0 automatic, else 4, 8, 16 or 32 (Sec. IV-B.1) */
-    int32_t hash_bits;        /* single mode: log2 of the LDS visited table, 8..13 (Sec. IV-B.3); 0 automatic
-                                 (the library picks a size, not necessarily a power of two) */
-    int32_t reset_interval;   /* single mode: passes between table resets, 0 automatic (the largest for which
-                                 itopk + interval * search_width * degree stays within 7/8 of the table) */
+    int32_t hash_bits;        /* single mode, periodic-reset table: log2 of the LDS visited table, 8..13
+                                 (Sec. IV-B.3); 0 automatic (the library picks a size, not necessarily a power
+                                 of two) */
+    int32_t reset_interval;   /* single mode, periodic-reset table: passes between resets, 0 automatic (the
+                                 largest for which itopk + interval * search_width * degree stays within 7/8 of
+                                 the table) */
     int32_t wg_per_query;     /* multi mode: workgroups per query, 0 => search_width */
     int32_t table_entries;    /* single mode: entries of the LDS visited table given directly (multiple of 64,
                                  256..8192); 0 => from hash_bits.  Not both. */
     int32_t dataset_type;     /* a cagra_dtype: storage type of the rows behind `dataset` (0 = fp32) */
-    int32_t reserved;
+    int32_t table_policy;     /* single mode: how the LDS visited table forgets (Sec. IV-B.3).  1: the paper's
+                                 periodic reset (open addressing, cleared every reset_interval passes, top-M
+                                 ids re-registered); 2: replacement (sets of four ids, a new id replaces the
+                                 oldest of its set; duplicates are rejected where candidates enter the top-M
+                                 list); 0: automatic = 1 if hash_bits or reset_interval is given, else 2.
+                                 Results are the same for both; only the number of distances computed twice
+                                 differs. */
     uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
                                  flags (bit 0: stopped by I_max, bit 1: visited table overflowed) */
 } cagra_search_opts;
@@ -125,6 +133,7 @@ typedef struct {
                                  max(k, 32, ceil(itopk / workers)) in multi mode */
     int32_t lds_bytes;        /* dynamic LDS per workgroup */
     int32_t workgroups;       /* launch size */
+    int32_t table_policy;     /* single mode: 1 periodic reset, 2 replacement; 0 in multi mode */
 } cagra_search_plan;
 
 int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,

@@ -18,7 +18,8 @@ from dataclasses import dataclass
 from typing import Optional, Tuple
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libcagra_hip.so")
+# CAGRA_HIP_LIB names another build of the same library (e.g. one with the phase timers compiled in)
+LIB_PATH = os.environ.get("CAGRA_HIP_LIB") or os.path.join(_PKG, "libcagra_hip.so")
 
 L2 = 0
 IP = 1
@@ -38,13 +39,13 @@ class _SearchOpts(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("max_iterations", C.c_int32), ("mode", C.c_int32),
                 ("team_size", C.c_int32), ("hash_bits", C.c_int32), ("reset_interval", C.c_int32),
                 ("wg_per_query", C.c_int32), ("table_entries", C.c_int32), ("dataset_type", C.c_int32),
-                ("reserved", C.c_int32), ("stats", C.c_void_p)]
+                ("table_policy", C.c_int32), ("stats", C.c_void_p)]
 
 
 class _SearchPlan(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("mode", "team_size", "table_entries", "reset_interval",
                                          "max_iterations", "wg_per_query", "itopk_local", "lds_bytes",
-                                         "workgroups")]
+                                         "workgroups", "table_policy")]
 
 
 def load_library():
@@ -186,11 +187,12 @@ class SearchOptions:
     wg_per_query: int = 0
     table_entries: int = 0
     dataset_type: int = 0      # F32 / F16 / U8; search() sets it from the dataset tensor's dtype
+    table_policy: int = 0      # 0 automatic, 1 periodic reset (the paper's), 2 replacement in sets of four
 
 
 def _copts(o: "SearchOptions", stats_ptr=None) -> _SearchOpts:
     return _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
-                       o.wg_per_query, o.table_entries, o.dataset_type, 0, stats_ptr)
+                       o.wg_per_query, o.table_entries, o.dataset_type, o.table_policy, stats_ptr)
 
 
 def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width: int = 1,

@@ -39,23 +39,32 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(_OBJ_DIR, os.path.basename(src) + ".o")
-    subprocess.run([_hipcc(), *HIPCC_FLAGS, "-c", src, "-o", obj], check=True)
-    return obj
-
-
-def build_library(verbose: bool = False) -> str:
-    """Compile every source (always: this is also the 'does it build' check) and link."""
-    os.makedirs(_OBJ_DIR, exist_ok=True)
+def build_library(verbose: bool = False, defines=(), out: str = LIB) -> str:
+    """Compile every source (always: this is also the 'does it build' check) and link.
+    `defines` are extra -D macros (e.g. CAGRA_PHASE_CLOCKS for the phase timers); a build with
+    defines should go to another `out` than the product library."""
+    obj_dir = _OBJ_DIR if out == LIB else out + ".obj"
+    os.makedirs(obj_dir, exist_ok=True)
     srcs = sources()
+    flags = HIPCC_FLAGS + ["-D" + d for d in defines]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(obj_dir, os.path.basename(src) + ".o")
+        subprocess.run([_hipcc(), *flags, "-c", src, "-o", obj], check=True)
+        return obj
+
     with cf.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(_compile, srcs))
-    subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+        objs = list(ex.map(compile_one, srcs))
+    subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs], check=True)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":
-    build_library(verbose=True)
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--define", action="append", default=[], help="extra -D macro, may repeat")
+    ap.add_argument("--out", default=LIB)
+    a = ap.parse_args()
+    build_library(verbose=True, defines=a.define, out=os.path.abspath(a.out))

@@ -53,8 +53,13 @@ static int elems_per_piece(int dataset_type)
     return dataset_type == CAGRA_F32 ? 4 : dataset_type == CAGRA_F16 ? 8 : dataset_type == CAGRA_U8 ? 16 : 0;
 }
 
+#ifndef CAGRA_AUTO_SET_TABLE
+#define CAGRA_AUTO_SET_TABLE 3072
+#endif
+constexpr int kAutoSetTableEntries = CAGRA_AUTO_SET_TABLE;
+
 struct SinglePlan {
-    int mr, cr, table_words, reset_interval, team_log2, max_iterations;
+    int mr, cr, table_words, table_policy, reset_interval, team_log2, max_iterations;
     size_t smem;
     int off_query, off_newid, off_newdist, off_parents;
 };
@@ -76,33 +81,44 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
     if (o.max_iterations < 0) return CAGRA_ERR_BAD_OPTION;
     pl.max_iterations = o.max_iterations == 0 ? auto_max_iterations(itopk, width) : o.max_iterations;
 
-    // Visited table in LDS (Sec. IV-B.3).  Between two resets it receives at most
-    // itopk + interval * n_cand ids; probing in LDS is cheap, so it may fill up to 7/8.
-    // Automatic size: 4096 entries.  Measured on the 1M x 128 workload, 3456..4096 entries are
-    // the flat optimum for itopk 64..256: 16 KB still leaves 9 wavefronts per CU, which with four
-    // rows per team in flight keep the gather bandwidth near its peak, and the longer history
-    // means fewer distances computed twice.  More if eight passes would not fit, at most 8192.
+    // Visited table in LDS (Sec. IV-B.3), in one of two managements.
+    //  - replacement (default): sets of four ids, a new id replaces the oldest of its set.  Any size
+    //    works; automatic size 3072 entries (12 KB + 768 bytes of per-set cursors), the measured optimum
+    //    on the 1M x 128 workload for itopk 64..256: smaller tables forget more, larger ones cost wavefronts per CU.
+    //  - periodic reset (the paper's; chosen by table_policy 1, or when hash_bits or reset_interval
+    //    are given): open addressing.  Between two resets the table receives at most
+    //    itopk + interval * n_cand ids; probing in LDS is cheap, so it may fill up to 7/8.
+    if (o.table_policy < 0 || o.table_policy > 2) return CAGRA_ERR_BAD_OPTION;
+    if (o.hash_bits < 0 || o.reset_interval < 0 || o.table_entries < 0) return CAGRA_ERR_BAD_OPTION;
+    const bool reset = o.table_policy == 1 || (o.table_policy == 0 && (o.hash_bits != 0 || o.reset_interval != 0));
+    if (!reset && (o.hash_bits != 0 || o.reset_interval != 0)) return CAGRA_ERR_BAD_OPTION;
     int words;
     if (o.table_entries != 0) {
         if (o.hash_bits != 0 || o.table_entries < 256 || o.table_entries > 8192 || (o.table_entries & 63))
             return CAGRA_ERR_BAD_OPTION;
         words = o.table_entries;
-    } else if (o.hash_bits == 0) {
+    } else if (o.hash_bits != 0) {
+        if (o.hash_bits < 8 || o.hash_bits > 13) return CAGRA_ERR_BAD_OPTION;
+        words = 1 << o.hash_bits;
+    } else if (reset) {
         const int want = ((itopk + 8 * n_cand) * 8 / 7 + 63) & ~63;
         words = std::min(8192, std::max(4096, want));
     } else {
-        if (o.hash_bits < 8 || o.hash_bits > 13) return CAGRA_ERR_BAD_OPTION;
-        words = 1 << o.hash_bits;
+        words = kAutoSetTableEntries;
     }
-    const int capacity = words / 8 * 7;
-    if (o.reset_interval < 0) return CAGRA_ERR_BAD_OPTION;
-    int interval = o.reset_interval;
-    if (interval == 0) interval = (capacity - itopk) / n_cand;
-    if (interval < 1 || itopk + (int64_t)interval * n_cand > capacity) return CAGRA_ERR_HASH_CAPACITY;
     pl.table_words = words;
-    pl.reset_interval = interval;
+    pl.table_policy = reset ? 1 : 2;
+    pl.reset_interval = 0;
+    if (reset) {
+        const int capacity = words / 8 * 7;
+        int interval = o.reset_interval;
+        if (interval == 0) interval = (capacity - itopk) / n_cand;
+        if (interval < 1 || itopk + (int64_t)interval * n_cand > capacity) return CAGRA_ERR_HASH_CAPACITY;
+        pl.reset_interval = interval;
+    }
 
     size_t off = (size_t)4 * words;
+    if (!reset) off += (size_t)(words / 4 + 15) & ~(size_t)15;   // one cursor byte per set of four
     pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
     pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
     pl.off_newdist = (int)off;    off += (size_t)4 * 64 * pl.cr;
@@ -233,6 +249,7 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
         int rc = plan_multi(degree, dim, std::max<int64_t>(B, 1), k, itopk, search_width, o, pl);
         if (rc != CAGRA_OK) return rc;
         out.team_size = 1 << pl.team_log2; out.table_entries = 1 << pl.hash_bits; out.reset_interval = 0;
+        out.table_policy = 0;
         out.max_iterations = pl.max_iterations; out.wg_per_query = pl.workers; out.itopk_local = pl.itopk_local;
         out.lds_bytes = (int32_t)pl.smem; out.workgroups = (int32_t)(B * pl.workers);
     } else {
@@ -240,6 +257,7 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
         int rc = plan_single(degree, dim, itopk, search_width, o, pl);
         if (rc != CAGRA_OK) return rc;
         out.team_size = 1 << pl.team_log2; out.table_entries = pl.table_words; out.reset_interval = pl.reset_interval;
+        out.table_policy = pl.table_policy;
         out.max_iterations = pl.max_iterations; out.wg_per_query = 1; out.itopk_local = itopk;
         out.lds_bytes = (int32_t)pl.smem;
         int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));

@@ -115,10 +115,18 @@ __device__ __forceinline__ void merge_into_topm(uint32_t (&thi)[MR], uint32_t (&
 // Ordered insertion of one key (wavefront-uniform) into the sorted list t: entries from its
 // position on move up by one element (one lane to the right, lane 63 into lane 0 of the next
 // register), the last element of the list falls off.
-template <int MR>
+// With DEDUP the key is dropped when the list already holds its node (ids are compared; the
+// parent flags may differ, the distance of a node is always the same bits).
+template <int MR, bool DEDUP>
 __device__ __forceinline__ void insert_into_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR],
                                                  uint32_t khi, uint32_t klo, int lane)
 {
+    if constexpr (DEDUP) {
+        bool same = false;
+#pragma unroll
+        for (int r = 0; r < MR; ++r) same |= (tlo[r] >> 1) == (klo >> 1);
+        if (__ballot(same) != 0ull) return;
+    }
     int pos = 0;   // entries smaller than the key form a prefix of the sorted list
 #pragma unroll
     for (int r = 0; r < MR; ++r) pos += __popcll(__ballot(key_less(thi[r], tlo[r], khi, klo)));
@@ -134,6 +142,46 @@ __device__ __forceinline__ void insert_into_topm(uint32_t (&thi)[MR], uint32_t (
         thi[r] = e > pos ? up_hi : (e == pos ? khi : thi[r]);
         tlo[r] = e > pos ? up_lo : (e == pos ? klo : tlo[r]);
     }
+}
+
+// Lane i takes the value of lane i - 1, lane 0 that of lane 63 (DPP wave_ror:1).
+__device__ __forceinline__ uint32_t wave_rotate1(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x13C, 0xF, 0xF, false);
+}
+
+// Turns into dummies (a) every candidate whose node is already in the list t and (b) all but the
+// first (lowest element index) of candidates that name the same node.  Every candidate travels
+// once around the wavefront and is compared with what each lane holds.  Needed only where the
+// visited table may have forgotten a node that is still in the list (see visited_insert_sets).
+template <int MR, int CR>
+__device__ __forceinline__ void drop_duplicates(const uint32_t (&tlo)[MR], uint32_t (&chi)[CR], uint32_t (&clo)[CR], int lane)
+{
+    uint32_t rid[CR];                 // travelling node ids (0x7FFFFFFF for a dummy: no node has it)
+    uint32_t dup = 0;                 // bit r: the travelling candidate of register r is a duplicate
+    uint32_t home = (uint32_t)lane;   // lane the travelling candidates belong to
+#pragma unroll
+    for (int r = 0; r < CR; ++r) rid[r] = clo[r] >> 1;
+    for (int step = 0; step < kWave; ++step) {
+#pragma unroll
+        for (int r = 0; r < CR; ++r) {
+            bool m = false;
+#pragma unroll
+            for (int t = 0; t < MR; ++t) m |= (tlo[t] >> 1) == rid[r];
+#pragma unroll
+            for (int r2 = 0; r2 < CR; ++r2)
+                m |= ((clo[r2] >> 1) == rid[r]) & ((uint32_t)(r2 * kWave + lane) < (uint32_t)r * kWave + home);
+            dup |= m ? (1u << r) : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < CR; ++r) rid[r] = wave_rotate1(rid[r]);
+        dup = wave_rotate1(dup);
+        home = wave_rotate1(home);
+    }
+    // after 64 rotations every candidate is back in its own lane
+#pragma unroll
+    for (int r = 0; r < CR; ++r)
+        if (dup & (1u << r)) { chi[r] = kDummyHi; clo[r] = kInvalidId; }
 }
 
 // ---- visited table (Sec. IV-B.3) -------------------------------------------------------------
@@ -161,6 +209,24 @@ __device__ __forceinline__ bool visited_insert(uint32_t *table, uint32_t words, 
         s = s + 1 == words ? 0u : s + 1;
     }
     overflow = true;
+    return true;
+}
+
+// LDS table organised as sets of four ids (one 16-byte read tests a node) in which a new id
+// replaces the oldest of its set: forgetting by replacement instead of the periodic reset of
+// Sec. IV-B.3.  `cursor` holds one byte per set, four sets per word, counting the set's
+// insertions; a byte that wraps carries into its neighbour, which only shifts that set's
+// replacement order.  The table never reports an unseen node as seen; it may forget any node,
+// also one that is still in the top-M list, so list entry has to reject duplicates.
+// true if id was not in the table (and is now).
+__device__ __forceinline__ bool visited_insert_sets(uint32_t *table, uint32_t *cursor, uint32_t sets, uint32_t id)
+{
+    const uint32_t s = hash_slot_words(id, sets);
+    const uint4 e = *reinterpret_cast<const uint4 *>(table + 4 * s);
+    if (e.x == id || e.y == id || e.z == id || e.w == id) return false;
+    const uint32_t sh = 8u * (s & 3u);
+    const uint32_t c = atomicAdd(&cursor[s >> 2], 1u << sh);
+    table[4 * s + ((c >> sh) & 3u)] = id;
     return true;
 }
 

@@ -12,9 +12,13 @@
 //   - distances are computed by teams of 4/8/16/32 lanes, one dataset row per team,
 //     16-byte loads, butterfly reduction (Sec. IV-B.1).
 // Single mode (Sec. IV-C.1): workgroups are persistent and pull query indices from a
-// device counter; the visited table is an open-addressing hash in LDS that is cleared
-// every `reset_interval` passes and re-filled with the current top-M ids (forgettable
-// management, Sec. IV-B.3).
+// device counter; the visited table lives in LDS and forgets (Sec. IV-B.3), in one of two
+// ways: kTableSets -- sets of four ids in which a new id replaces the oldest, with
+// duplicates rejected where candidates enter the top-M list -- or kTableReset -- the
+// paper's open-addressing table that is cleared every `reset_interval` passes and re-filled
+// with the current top-M ids.  Both give the same results (a forgotten node that is measured
+// again cannot enter the list a second time); they differ in how many distances are
+// computed twice.
 // Multi mode (Sec. IV-C.2): `workers` workgroups per query, each with one parent per pass,
 // its own seeds and its own list, sharing one visited table in device memory; the last
 // worker of a query to finish merges the lists and writes the result.
@@ -84,13 +88,33 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 #endif
 constexpr int kInsertLimit = CAGRA_INSERT_LIMIT;
 
+// Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
+// every wavefront spends in each part of the loop, summed over the launch into a device array
+// that cagra_debug_phase_clocks_<type>() reads back.  Off by default; the timers cost a scalar
+// memory-time read and a wait per phase.
+#ifdef CAGRA_PHASE_CLOCKS
+static __device__ unsigned long long g_phase_clocks[8];
+#define CAGRA_PHASE_BEGIN() unsigned long long ph_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long ph_t = __builtin_amdgcn_s_memtime();
+#define CAGRA_PHASE(i) { const unsigned long long ph_n = __builtin_amdgcn_s_memtime(); ph_acc[i] += ph_n - ph_t; ph_t = ph_n; }
+#define CAGRA_PHASE_END() if (lane == 0) { _Pragma("unroll") for (int ph_i = 0; ph_i < 8; ++ph_i) if (ph_acc[ph_i]) atomicAdd(&g_phase_clocks[ph_i], ph_acc[ph_i]); }
+#else
+#define CAGRA_PHASE_BEGIN()
+#define CAGRA_PHASE(i)
+#define CAGRA_PHASE_END()
+#endif
+
+// kinds of visited table
+constexpr int kTableSets = 0;     // LDS, 4-way sets, replacement of the oldest
+constexpr int kTableReset = 1;    // LDS, open addressing, periodic reset (Sec. IV-B.3)
+constexpr int kTableGlobal = 2;   // device memory, open addressing, never forgets (multi mode)
+
 struct QueryStats {
     uint32_t n_iter, n_parent, n_dist, flags;
 };
 
 // The search of one (query, worker): on return thi/tlo hold the sorted top-M list.
 // `table` is the LDS table (single) or this query's device-memory table (multi).
-template <int MR, int CR, bool MULTI, int RIF>
+template <int MR, int CR, int KIND, int RIF>
 __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, int worker,
                                             uint32_t *table, float *qlds, uint32_t *newid,
                                             float *newdist, uint32_t *parents,
@@ -105,12 +129,20 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     const int t = lane & (team - 1);       // lane within the team
     const int n_cand = P.search_width * P.degree;
     const int nchunk = P.dim / kElemsPerPiece;   // 16-byte pieces per row
+    constexpr bool MULTI = KIND == kTableGlobal;
     const int table_words = P.table_words;   // single mode: LDS table
+    uint32_t *cursor = table + table_words;  // kTableSets: one byte per set behind the table
+    const uint32_t sets = (uint32_t)table_words >> 2;
 
+    CAGRA_PHASE_BEGIN()
     const float *q = P.queries + (size_t)qi * P.ld_queries;
     for (int j = lane; j < P.dim; j += kWave) qlds[j] = q[j];
-    if (!MULTI)
-        for (int j = lane; j < table_words; j += kWave) table[j] = kInvalidId;
+    if (!MULTI) {
+        for (int j = 4 * lane; j < table_words; j += 4 * kWave)
+            *reinterpret_cast<uint4 *>(table + j) = make_uint4(kInvalidId, kInvalidId, kInvalidId, kInvalidId);
+        if (KIND == kTableSets)
+            for (int j = lane; j < (int)(sets + 3) / 4; j += kWave) cursor[j] = 0u;
+    }
 
     uint32_t chi[CR], clo[CR];
 #pragma unroll
@@ -133,15 +165,18 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 #pragma unroll
     for (int r = 0; r < CR; ++r) ahead[r] = kInvalidId;
 
+    CAGRA_PHASE(0)
     for (int it = 0;; ++it) {
         // ---- step 3: first-time test, compaction, team distances -------------------------
         int n_new = 0;
 #pragma unroll
         for (int r = 0; r < CR; ++r) {
             bool isnew = false;
-            if (raw[r] != kInvalidId)
-                isnew = MULTI ? visited_insert_global(table, P.hash_bits, raw[r], overflow)
-                              : visited_insert(table, (uint32_t)table_words, raw[r], overflow);
+            if (raw[r] != kInvalidId) {
+                if constexpr (KIND == kTableGlobal) isnew = visited_insert_global(table, P.hash_bits, raw[r], overflow);
+                else if constexpr (KIND == kTableReset) isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
+                else isnew = visited_insert_sets(table, cursor, sets, raw[r]);
+            }
             const uint64_t m = __ballot(isnew);
             const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
                                          __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
@@ -150,6 +185,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         }
         __syncthreads();
         n_dist_total += (uint32_t)n_new;
+        CAGRA_PHASE(1)
 
         for (int c0 = 0; c0 < n_new; c0 += RIF * n_teams) {
             // RIF dataset rows per team in flight: all loads of a round are issued before any is used
@@ -210,6 +246,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
             }
         }
         __syncthreads();
+        CAGRA_PHASE(2)
 #pragma unroll
         for (int r = 0; r < CR; ++r) {
             int c = r * 64 + lane;
@@ -246,11 +283,12 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                         while (m != 0ull) {
                             const int l = __builtin_ctzll(m);
                             m &= m - 1;
-                            insert_into_topm<MR>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
-                                                 __builtin_amdgcn_readlane(clo[r], l), lane);
+                            insert_into_topm<MR, KIND == kTableSets>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
+                                                                     __builtin_amdgcn_readlane(clo[r], l), lane);
                         }
                     }
                 } else {
+                    if constexpr (KIND == kTableSets) drop_duplicates<MR, CR>(tlo, chi, clo, lane);
                     bitonic_sort<CR>(chi, clo, lane);
                     merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
                 }
@@ -260,10 +298,11 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                     if (r * 64 + lane >= P.itopk) { thi[r] = kDummyHi; tlo[r] = kInvalidId; }
             }
         }
+        CAGRA_PHASE(3)
         if (it == P.max_iterations) { flags |= 1u; break; }
 
         // ---- forgettable management: periodic reset (Sec. IV-B.3), single mode only ------
-        if (!MULTI && P.reset_interval > 0 && it > 0 && (it % P.reset_interval) == 0) {
+        if (KIND == kTableReset && P.reset_interval > 0 && it > 0 && (it % P.reset_interval) == 0) {
             __syncthreads();
             for (int j = lane; j < table_words; j += kWave) table[j] = kInvalidId;
             __syncthreads();
@@ -272,6 +311,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                 if (tlo[r] != kInvalidId) (void)visited_insert(table, (uint32_t)table_words, tlo[r] >> 1, overflow);
         }
 
+        CAGRA_PHASE(4)
         // ---- step 2: parents = first search_width entries without the flag ----------------
         int n_par = 0;
 #pragma unroll
@@ -322,7 +362,9 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                 raw[r] = v ? P.graph[(size_t)parents[v ? slot_parent[r] : 0] * P.degree + slot_nbr[r]] : kInvalidId;
             }
         }
+        CAGRA_PHASE(5)
     }
+    CAGRA_PHASE_END()
     if (__ballot(overflow) != 0ull) flags |= 2u;
     qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
 }
@@ -358,7 +400,7 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
         slot_nbr[r] = c - slot_parent[r] * P.degree;                             \
     }
 
-template <int ELEM, int MR, int CR>
+template <int ELEM, int MR, int CR, int KIND>
 __global__ void __launch_bounds__(kWave)
 search_single_kernel(const SearchParams P)
 {
@@ -372,7 +414,7 @@ search_single_kernel(const SearchParams P)
         if ((int64_t)qi >= P.B) break;
         uint32_t thi[MR], tlo[MR];
         QueryStats qs;
-        search_body<MR, CR, false, kRowsInFlight>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+        search_body<MR, CR, KIND, kRowsInFlight>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                                    thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
         if (P.stats != nullptr && lane == 0) {
@@ -393,7 +435,7 @@ search_multi_kernel(const SearchParams P)
     uint32_t *table = P.tables + ((size_t)qi << P.hash_bits);
     uint32_t thi[MR], tlo[MR];
     QueryStats qs;
-    search_body<MR, CR, true, kRowsInFlightMulti>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+    search_body<MR, CR, kTableGlobal, kRowsInFlightMulti>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                               thi, tlo, qs);
     if (P.stats != nullptr && lane == 0) {
         uint32_t *s = P.stats + (size_t)qi * 4;
@@ -432,7 +474,10 @@ template <int MR, int CR>
 static hipError_t launch_single_one(const SearchParams &P, int grid, size_t smem, hipStream_t stream)
 {
     launch_zero_counter(P.counter, stream);
-    hipLaunchKernelGGL((search_single_kernel<kElem, MR, CR>), dim3(grid), dim3(kWave), smem, stream, P);
+    if (P.reset_interval > 0)
+        hipLaunchKernelGGL((search_single_kernel<kElem, MR, CR, kTableReset>), dim3(grid), dim3(kWave), smem, stream, P);
+    else
+        hipLaunchKernelGGL((search_single_kernel<kElem, MR, CR, kTableSets>), dim3(grid), dim3(kWave), smem, stream, P);
     return hipGetLastError();
 }
 
@@ -474,3 +519,17 @@ hipError_t CAGRA_CAT(launch_search_multi_, CAGRA_ELEM_NAME)(const SearchParams &
 }
 
 }  // namespace cagra
+
+#ifdef CAGRA_PHASE_CLOCKS
+// Reads (and optionally clears) the phase timers of this storage type's kernels; synchronises the device.
+extern "C" int CAGRA_CAT(cagra_debug_phase_clocks_, CAGRA_ELEM_NAME)(unsigned long long *out_host, int clear)
+{
+    if (hipDeviceSynchronize() != hipSuccess) return -1;
+    if (out_host && hipMemcpyFromSymbol(out_host, HIP_SYMBOL(cagra::g_phase_clocks), sizeof(unsigned long long) * 8) != hipSuccess) return -1;
+    if (clear) {
+        unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(cagra::g_phase_clocks), z, sizeof(z)) != hipSuccess) return -1;
+    }
+    return 0;
+}
+#endif

@@ -60,8 +60,10 @@ def test_describe_reports_the_automatic_parameters():
     import paper_2308_15136_amd as m
     p = m.describe(64, 128, 10_000, 10, 128, 1, m.SearchOptions(mode=1))
     assert p["mode"] == 1 and p["team_size"] == 8 and p["max_iterations"] == 2 * 128 + 32
-    assert p["table_entries"] % 64 == 0
-    assert 128 + p["reset_interval"] * 64 <= p["table_entries"] // 8 * 7
+    assert p["table_entries"] % 64 == 0 and p["table_policy"] == 2 and p["reset_interval"] == 0
+    r = m.describe(64, 128, 10_000, 10, 128, 1, m.SearchOptions(mode=1, table_policy=1))
+    assert r["table_policy"] == 1 and r["reset_interval"] >= 1
+    assert 128 + r["reset_interval"] * 64 <= r["table_entries"] // 8 * 7
     q = m.describe(32, 96, 1, 10, 64, 4, m.SearchOptions(mode=2))
     assert q["mode"] == 2 and q["wg_per_query"] == 4 and q["itopk_local"] == 32
     assert q["table_entries"] >= 2 * 4 * 32 * (q["max_iterations"] + 1)     # Sec. IV-B.3: at least twice

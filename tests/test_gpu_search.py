@@ -120,14 +120,15 @@ def test_search_matches_oracle(cagra, name, n, nq, degree, k, itopk, width, exac
 @pytest.mark.parametrize("hash_bits,interval", [(9, 1), (10, 2), (11, 0), (13, 0), (13, 40), (0, 0), (0, 3),
                                                 (8, 2)])
 def test_forgettable_table_does_not_change_results(cagra, hash_bits, interval):
-    # Sec. IV-B.3: table size and reset interval change the work, not the answer; with the same
-    # reset schedule the number of distance computations equals the oracle's simulated forgetting.
+    # Sec. IV-B.3 (periodic reset): table size and reset interval change the work, not the answer;
+    # with the same reset schedule the number of distance computations equals the oracle's
+    # simulated forgetting.
     w, g, gt = _setup("sift1m", 20_000, 300, 64)
     gd, bd, qd = _to_dev(w, g)
-    opts = cagra.SearchOptions(seed=7, mode=1, hash_bits=hash_bits, reset_interval=interval)
+    opts = cagra.SearchOptions(seed=7, mode=1, hash_bits=hash_bits, reset_interval=interval, table_policy=1)
     plan = cagra.describe(64, 128, 300, 10, 64, 1, opts)
     entries = (1 << hash_bits) if hash_bits else plan["table_entries"]
-    assert plan["mode"] == 1 and plan["table_entries"] == entries
+    assert plan["mode"] == 1 and plan["table_entries"] == entries and plan["table_policy"] == 1
     eff = plan["reset_interval"]
     assert eff == (interval if interval else (entries // 8 * 7 - 64) // 64)
     ids, dists, st = cagra.search(gd, bd, qd, 10, 64, 1, w.metric, opts, return_stats=True)
@@ -138,6 +139,53 @@ def test_forgettable_table_does_not_change_results(cagra, hash_bits, interval):
     np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), ref_ids)
     np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
     np.testing.assert_array_equal(st[:, :3], ref_st[:, :3])
+
+
+@pytest.mark.parametrize("entries,k,itopk,width", [(256, 10, 64, 1), (256, 40, 300, 2), (512, 10, 128, 4),
+                                                   (1024, 100, 512, 2), (2048, 10, 96, 1), (8192, 10, 256, 1),
+                                                   (0, 10, 128, 1)])
+def test_replacement_table_does_not_change_results(cagra, entries, k, itopk, width):
+    # The table that forgets by replacement (sets of four, oldest out) may forget any node, also one
+    # that is still in the top-M list; duplicates are rejected at list entry, so the answer is the
+    # oracle's whatever the table size.  A table far too small (256 entries for hundreds of list
+    # members) makes nearly every list member come back as a candidate.
+    w, g, gt = _setup("sift1m", 20_000, 300, 64)
+    print(f"case replacement table entries={entries} k={k} M={itopk} p={width}", flush=True)
+    gd, bd, qd = _to_dev(w, g)
+    opts = cagra.SearchOptions(seed=21, mode=1, table_entries=entries, table_policy=2)
+    plan = cagra.describe(64, 128, 300, k, itopk, width, opts)
+    assert plan["table_policy"] == 2 and plan["reset_interval"] == 0
+    assert entries == 0 or plan["table_entries"] == entries
+    ids, dists, st = cagra.search(gd, bd, qd, k, itopk, width, w.metric, opts, return_stats=True)
+    st = st.cpu().numpy().view(np.uint32)
+    ref_ids, ref_d, ref_st = oracle.search(g, w.base, w.queries, k, itopk, width, w.metric, seed=21,
+                                           return_stats=True)
+    np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), ref_ids)
+    np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
+    np.testing.assert_array_equal(st[:, :2], ref_st[:, :2])          # same passes, same parents
+    assert np.all(st[:, 2] >= ref_st[:, 2]) and np.all(st[:, 3] == ref_st[:, 3])
+    if entries == 8192:
+        # a table about twice the nodes this search ever visits forgets next to nothing
+        assert st[:, 2].sum() <= 1.05 * ref_st[:, 2].sum()
+    print(f"  distances computed: {st[:, 2].mean():.0f} per query, oracle (never forgets) {ref_st[:, 2].mean():.0f}",
+          flush=True)
+
+
+def test_repeated_ids_in_a_graph_row(cagra):
+    # a row that names the same neighbour several times: the first occurrence counts, as in the oracle
+    import torch
+    w, g, gt = _setup("sift1m", 20_000, 300, 64)
+    g2 = g.copy()
+    g2[:, 1::4] = g2[:, 0:1]          # every fourth slot repeats the row's first neighbour
+    g2[::3, 5] = g2[::3, 4]
+    gd = torch.from_numpy(g2.view(np.int32)).cuda()
+    _, bd, qd = _to_dev(w, g)
+    for policy, width, itopk in [(2, 1, 64), (2, 2, 200), (1, 1, 64), (1, 2, 200)]:
+        ids, dists = cagra.search(gd, bd, qd, 10, itopk, width, w.metric,
+                                  cagra.SearchOptions(seed=8, mode=1, table_policy=policy))
+        ref_ids, ref_d = oracle.search(g2, w.base, w.queries, 10, itopk, width, w.metric, seed=8)
+        np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), ref_ids)
+        np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
 
 
 @pytest.mark.parametrize("team", [4, 8, 16, 32])
@@ -188,6 +236,8 @@ def test_empty_batch_and_rejections(cagra):
         cagra.search(gd, bd, qd, 10, 64, 1, options=cagra.SearchOptions(mode=1, team_size=3))
     with pytest.raises(cagra.CagraError):
         cagra.search(gd, bd, qd, 10, 200, 1, options=cagra.SearchOptions(mode=1, hash_bits=8))  # too small
+    with pytest.raises(cagra.CagraError):                       # reset parameters with the replacement table
+        cagra.search(gd, bd, qd, 10, 64, 1, options=cagra.SearchOptions(mode=1, table_policy=2, reset_interval=2))
     with pytest.raises(cagra.CagraError):
         cagra.search(gd, bd, qd, 10, 1024, 1, options=cagra.SearchOptions(mode=1))  # single mode: M <= 512
     torch.cuda.synchronize()
