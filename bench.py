@@ -61,7 +61,10 @@ def main() -> int:
     ap.add_argument("--workload", default="sift1m")
     ap.add_argument("--n", type=int, default=0, help="shrink the base set (debugging only)")
     ap.add_argument("--queries", type=int, default=0)
-    ap.add_argument("--itopk", type=int, default=0, help="skip the sweep and time this itopk")
+    ap.add_argument("--itopk", type=int, default=0, help="skip the itopk sweep and time this itopk")
+    ap.add_argument("--width", type=int, default=0, help="skip the search_width sweep and use this width")
+    ap.add_argument("--full-sweep", action="store_true",
+                    help="per search_width go on beyond the first itopk that reaches the recall target")
     ap.add_argument("--cpu-sample", type=int, default=10000, help="queries given to the CPU oracle")
     ap.add_argument("--no-latency", action="store_true", help="skip the small-batch (multi mode) latency part")
     ap.add_argument("--latency-workers", type=int, default=8, help="workgroups per query in the latency part")
@@ -114,60 +117,71 @@ def main() -> int:
     ws = torch.empty(4096, dtype=torch.uint8, device=dev)
     ids = torch.empty((B, w.k), dtype=torch.int32, device=dev)
     dists = torch.empty((B, w.k), dtype=torch.float32, device=dev)
+    stats = torch.zeros((B, 4), dtype=torch.int32, device=dev)
 
-    def run(itopk, stats=False):
-        return cagra.search(graph, base, queries, w.k, itopk, w.search_width, w.metric, opts,
-                            return_stats=stats, out=(ids, dists), workspace=ws)
+    def run(itopk, width):
+        # every launch also writes its per-query counters (16 bytes per query), so the algorithmic
+        # bytes below are those of the timed launches themselves
+        return cagra.search(graph, base, queries, w.k, itopk, width, w.metric, opts,
+                            out=(ids, dists), workspace=ws, stats=stats)
 
-    def timed(itopk, steps, warmup):
+    def timed(itopk, width, steps, warmup):
         for _ in range(warmup):
-            run(itopk)
+            run(itopk, width)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t_start = time.perf_counter()
         e0.record()
         for _ in range(steps):
-            run(itopk)
+            run(itopk, width)
         e1.record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t_start) * 1e3 / steps
         return wall_ms, e0.elapsed_time(e1) / steps
 
-    # ---- sweep itopk: (recall, QPS) pairs ----------------------------------------------------
+    # ---- sweep (search_width, itopk): (recall, QPS) pairs; per width up to the first itopk that
+    #      reaches the target (QPS only falls beyond it) -------------------------------------------
     sweep = []
+    widths = (args.width,) if args.width else w.search_widths
     sweep_list = (args.itopk,) if args.itopk else w.itopk
-    for M in sweep_list:
-        _, _, st = run(M, stats=True)
-        torch.cuda.synchronize()
-        rec = recall_at_k(ids.cpu().numpy().view(np.uint32), gt_np)
-        wall_ms, dev_ms = timed(M, 5, 2)
-        ab = algorithmic_bytes(st.cpu().numpy().view(np.uint32), dim, w.degree, w.k)
-        sweep.append({"itopk": M, "recall": round(rec, 5), "qps": round(B / (wall_ms * 1e-3), 1),
-                      "kernel_ms": round(dev_ms, 4),
-                      "vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
-                      "iterations": round(ab["iterations_mean"], 2),
-                      "n_dist_per_query": round(ab["n_dist"] / B, 1)})
-        log(f"[bench] itopk {M}: recall@{w.k} {rec:.4f}  {sweep[-1]['qps']:.0f} QPS  "
-            f"{sweep[-1]['vector_GBs']:.0f} GB/s gathered")
-    ok = [s for s in sweep if s["recall"] >= TARGET_RECALL]
-    chosen = ok[0] if ok else sweep[-1]
-    M = chosen["itopk"]
-    qps_at_target = None
-    idx = sweep.index(chosen)
-    if ok and idx > 0 and sweep[idx - 1]["recall"] < TARGET_RECALL:
-        lo, hi = sweep[idx - 1], chosen
-        f = (TARGET_RECALL - lo["recall"]) / (hi["recall"] - lo["recall"])
-        qps_at_target = lo["qps"] + f * (hi["qps"] - lo["qps"])
+    best = None
+    interpolated = []
+    for p in widths:
+        prev = None
+        for M in sweep_list:
+            if M < w.k or p * w.degree > 256:
+                continue
+            wall_ms, dev_ms = timed(M, p, 5, 2)
+            rec = recall_at_k(ids.cpu().numpy().view(np.uint32), gt_np)
+            ab = algorithmic_bytes(stats.cpu().numpy().view(np.uint32), dim, w.degree, w.k)
+            pt = {"search_width": p, "itopk": M, "recall": round(rec, 5), "qps": round(B / (wall_ms * 1e-3), 1),
+                  "kernel_ms": round(dev_ms, 4),
+                  "vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
+                  "iterations": round(ab["iterations_mean"], 2),
+                  "n_dist_per_query": round(ab["n_dist"] / B, 1)}
+            sweep.append(pt)
+            log(f"[bench] width {p} itopk {M}: recall@{w.k} {rec:.4f}  {pt['qps']:.0f} QPS  "
+                f"{pt['vector_GBs']:.0f} GB/s gathered")
+            if rec >= TARGET_RECALL:
+                if best is None or pt["qps"] > best["qps"]:
+                    best = pt
+                if prev is not None and prev["recall"] < TARGET_RECALL:
+                    f = (TARGET_RECALL - prev["recall"]) / (rec - prev["recall"])
+                    interpolated.append(prev["qps"] + f * (pt["qps"] - prev["qps"]))
+                if not args.full_sweep:
+                    break
+            prev = pt
+    chosen = best if best is not None else sweep[-1]
+    M, P_WIDTH = chosen["itopk"], chosen["search_width"]
+    qps_at_target = max(interpolated) if interpolated else None
 
     # ---- the timed region ---------------------------------------------------------------------
-    _, _, st = run(M, stats=True)
-    torch.cuda.synchronize()
-    st_np = st.cpu().numpy().view(np.uint32)
+    wall_ms, dev_ms = timed(M, P_WIDTH, args.steps, args.warmup)
+    st_np = stats.cpu().numpy().view(np.uint32)
     ab = algorithmic_bytes(st_np, dim, w.degree, w.k)
     gpu_ids = ids.cpu().numpy().view(np.uint32).copy()
     gpu_d = dists.cpu().numpy().copy()
     rec = recall_at_k(gpu_ids, gt_np)
-    wall_ms, dev_ms = timed(M, args.steps, args.warmup)
     value = B / (wall_ms * 1e-3)
     achieved = ab["total_bytes"] / (dev_ms * 1e-3) / 1e9
 
@@ -178,8 +192,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{w.name}: N={N} dim={dim} fp32 integer-valued 0..255, B={B}, "
                                f"degree={w.degree} (init {w.init_degree}), k={w.k}, itopk={M}, "
-                               f"search_width={w.search_width}, single-workgroup mode",
-                   "itopk": M, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
+                               f"search_width={P_WIDTH}, single-workgroup mode",
+                   "itopk": M, "search_width": P_WIDTH, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
                    "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
                    "graph_build_s": round(build_s, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -203,10 +217,12 @@ def main() -> int:
             n_ids = torch.empty((B, w.k), dtype=torch.int32, device=dev)
             n_d = torch.empty((B, w.k), dtype=torch.float32, device=dev)
 
-            def run_n(stats=False):
-                return cagra.search(graph, conv, queries, w.k, M, w.search_width, w.metric, opts,
-                                    return_stats=stats, out=(n_ids, n_d), workspace=ws)
-            _, _, st_n = run_n(True)
+            st_n = torch.zeros((B, 4), dtype=torch.int32, device=dev)
+
+            def run_n():
+                return cagra.search(graph, conv, queries, w.k, M, P_WIDTH, w.metric, opts,
+                                    out=(n_ids, n_d), workspace=ws, stats=st_n)
+            run_n()
             torch.cuda.synchronize()
             rec_n = recall_at_k(n_ids.cpu().numpy().view(np.uint32), gt_np)
             for _ in range(2):
@@ -220,7 +236,7 @@ def main() -> int:
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / 10
             nd = int(st_n.cpu().numpy().view(np.uint32)[:, 2].astype(np.int64).sum())
-            narrow.append({"storage": name, "itopk": M, "recall_at_k": round(rec_n, 5), "kernel_ms": round(ms, 4),
+            narrow.append({"storage": name, "itopk": M, "search_width": P_WIDTH, "recall_at_k": round(rec_n, 5), "kernel_ms": round(ms, 4),
                            "qps_kernel": round(B / (ms * 1e-3), 1),
                            "gathered_vector_GBs": round(nd * dim * width_b / (ms * 1e-3) / 1e9, 1),
                            "same_ids_as_fp32": bool(torch.equal(n_ids, ids))})
@@ -299,9 +315,9 @@ def main() -> int:
         import oracle
         ns = min(args.cpu_sample, B)
         g_np = graph.cpu().numpy().view(np.uint32)
-        oracle.search(g_np, w.base, w.queries[:64], w.k, M, w.search_width, w.metric, seed=opts.seed)  # warm-up
+        oracle.search(g_np, w.base, w.queries[:64], w.k, M, P_WIDTH, w.metric, seed=opts.seed)  # warm-up
         t0 = time.perf_counter()
-        o_ids, o_d, o_st = oracle.search(g_np, w.base, w.queries[:ns], w.k, M, w.search_width, w.metric,
+        o_ids, o_d, o_st = oracle.search(g_np, w.base, w.queries[:ns], w.k, M, P_WIDTH, w.metric,
                                          seed=opts.seed, return_stats=True)
         cpu_s = time.perf_counter() - t0
         inter = sum(len(np.intersect1d(a, b)) for a, b in zip(gpu_ids[:ns], o_ids))
@@ -309,7 +325,7 @@ def main() -> int:
         rel = float(np.max(np.abs(gpu_d[:ns] - o_d)[same] / np.maximum(np.abs(o_d[same]), 1e-30))) if same.any() else 0.0
         out["cpu_baseline"] = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "sample": f"first {ns} of the {B} queries, same graph, "
-                               f"itopk={M}, OpenMP over queries, {cpu_s:.2f}s"}
+                               f"itopk={M}, search_width={P_WIDTH}, OpenMP over queries, {cpu_s:.2f}s"}
         out["parity_at_full_size"] = {"sample": ns, "id_agreement": round(inter / float(ns * w.k), 6),
                                       "positionwise_equal": round(float(same.mean()), 6),
                                       "max_rel_dist_err": rel,

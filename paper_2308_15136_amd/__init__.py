@@ -214,8 +214,9 @@ def search_workspace_bytes(n: int, degree: int, batch: int, k: int, itopk: int, 
 
 def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,
            options: Optional[SearchOptions] = None, return_stats: bool = False,
-           out: Optional[Tuple] = None, workspace=None):
-    """Batched greedy graph search: (ids[B, k] int32, dists[B, k] float32[, stats[B, 4] int32])."""
+           out: Optional[Tuple] = None, workspace=None, stats=None):
+    """Batched greedy graph search: (ids[B, k] int32, dists[B, k] float32[, stats[B, 4] int32]).
+    `out`, `workspace` and `stats` (int32 [B, 4], implies return_stats) may be preallocated."""
     torch = _torch()
     lib = load_library()
     graph = _dev_i32(graph, "graph")
@@ -224,7 +225,12 @@ def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, m
     dev = dataset.device
     B = queries.shape[0]
     o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype)
-    stats = torch.zeros((B, 4), dtype=torch.int32, device=dev) if return_stats else None
+    if stats is not None:
+        return_stats = True
+        if not (stats.is_cuda and stats.dtype == torch.int32 and stats.is_contiguous() and stats.numel() >= 4 * B):
+            raise TypeError("stats must be a contiguous int32 device tensor of at least B * 4 elements")
+    elif return_stats:
+        stats = torch.zeros((B, 4), dtype=torch.int32, device=dev)
     copts = _copts(o, stats.data_ptr() if stats is not None else None)
     if out is None:
         ids = torch.empty((B, k), dtype=torch.int32, device=dev)

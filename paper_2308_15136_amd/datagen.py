@@ -156,6 +156,7 @@ class Workload:
     k: int
     itopk: tuple              # sweep of M values
     search_width: int = 1
+    search_widths: tuple = (1, 2, 4)   # sweep of p values (Sec. IV-A: parents per pass)
     notes: str = ""
     extra: dict = field(default_factory=dict)
 
@@ -174,7 +175,7 @@ def workload(name: str, n: Optional[int] = None, n_queries: Optional[int] = None
         b = n_queries or 10_000
         base = sift_like(n, 128, 256, seed=1, stream=1)
         qs = sift_like(b, 128, 256, seed=1, stream=2)
-        return Workload(name, base, qs, L2, 64, 128, 10, (32, 64, 96, 128, 192, 256))
+        return Workload(name, base, qs, L2, 64, 128, 10, (32, 48, 64, 96, 128, 192, 256))
     if name == "deep1m":        # large batch, lower dim: 1M x 96 unit norm
         n = n or 1_000_000
         b = n_queries or 10_000
