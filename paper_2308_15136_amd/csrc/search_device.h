@@ -115,18 +115,10 @@ __device__ __forceinline__ void merge_into_topm(uint32_t (&thi)[MR], uint32_t (&
 // Ordered insertion of one key (wavefront-uniform) into the sorted list t: entries from its
 // position on move up by one element (one lane to the right, lane 63 into lane 0 of the next
 // register), the last element of the list falls off.
-// With DEDUP the key is dropped when the list already holds its node (ids are compared; the
-// parent flags may differ, the distance of a node is always the same bits).
-template <int MR, bool DEDUP>
+template <int MR>
 __device__ __forceinline__ void insert_into_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR],
                                                  uint32_t khi, uint32_t klo, int lane)
 {
-    if constexpr (DEDUP) {
-        bool same = false;
-#pragma unroll
-        for (int r = 0; r < MR; ++r) same |= (tlo[r] >> 1) == (klo >> 1);
-        if (__ballot(same) != 0ull) return;
-    }
     int pos = 0;   // entries smaller than the key form a prefix of the sorted list
 #pragma unroll
     for (int r = 0; r < MR; ++r) pos += __popcll(__ballot(key_less(thi[r], tlo[r], khi, klo)));
@@ -152,8 +144,9 @@ __device__ __forceinline__ uint32_t wave_rotate1(uint32_t v)
 
 // Turns into dummies (a) every candidate whose node is already in the list t and (b) all but the
 // first (lowest element index) of candidates that name the same node.  Every candidate travels
-// once around the wavefront and is compared with what each lane holds.  Needed only where the
-// visited table may have forgotten a node that is still in the list (see visited_insert_sets).
+// once around the wavefront and is compared with what each lane holds.  The slow, complete
+// check: used only in a pass in which the visited table lost an id it had just taken (see
+// visited_insert_sets).
 template <int MR, int CR>
 __device__ __forceinline__ void drop_duplicates(const uint32_t (&tlo)[MR], uint32_t (&chi)[CR], uint32_t (&clo)[CR], int lane)
 {
@@ -216,18 +209,55 @@ __device__ __forceinline__ bool visited_insert(uint32_t *table, uint32_t words, 
 // replaces the oldest of its set: forgetting by replacement instead of the periodic reset of
 // Sec. IV-B.3.  `cursor` holds one byte per set, four sets per word, counting the set's
 // insertions; a byte that wraps carries into its neighbour, which only shifts that set's
-// replacement order.  The table never reports an unseen node as seen; it may forget any node,
-// also one that is still in the top-M list, so list entry has to reject duplicates.
-// true if id was not in the table (and is now).
-__device__ __forceinline__ bool visited_insert_sets(uint32_t *table, uint32_t *cursor, uint32_t sets, uint32_t id)
+// replacement order.  The table never reports an unseen node as seen.  It may forget a node,
+// also one that is still in the top-M list; the two flags tell the caller when list entry has
+// to look for duplicates:
+//   forgot -- an id that the table held was overwritten (by this lane): from now on a candidate
+//             may be a node that is already in the list;
+//   lost   -- this lane's own id did not survive the insertions of the same pass (five or more
+//             of them hit one set): candidates of this pass may repeat each other unnoticed.
+// Keeps the compiler from moving or merging LDS accesses across this point (the hardware runs
+// one wavefront's LDS instructions in order).
+__device__ __forceinline__ void lds_order() { __asm__ volatile("" ::: "memory"); }
+
+// A pass tests all its candidates first, then inserts the missing ones, then reads the sets
+// again: lanes that inserted the same id all found it missing, and only the copy in the lowest
+// way counts as new.  All lanes call these together; `valid` lanes take part.
+__device__ __forceinline__ bool sets_lookup(const uint32_t *table, uint32_t sets, uint32_t id, bool valid, uint32_t &set)
 {
-    const uint32_t s = hash_slot_words(id, sets);
-    const uint4 e = *reinterpret_cast<const uint4 *>(table + 4 * s);
-    if (e.x == id || e.y == id || e.z == id || e.w == id) return false;
-    const uint32_t sh = 8u * (s & 3u);
-    const uint32_t c = atomicAdd(&cursor[s >> 2], 1u << sh);
-    table[4 * s + ((c >> sh) & 3u)] = id;
-    return true;
+    set = valid ? hash_slot_words(id, sets) : 0u;
+    const uint4 e = *reinterpret_cast<const uint4 *>(table + 4 * set);
+    return valid && !(e.x == id || e.y == id || e.z == id || e.w == id);   // true: not in the table
+}
+
+// returns the set's insertion count before this one; the id goes to way count & 3
+__device__ __forceinline__ uint32_t sets_insert(uint32_t *table, uint32_t *cursor, uint32_t set, uint32_t id, bool &forgot)
+{
+    const uint32_t sh = 8u * (set & 3u);
+    const uint32_t count = (atomicAdd(&cursor[set >> 2], 1u << sh) >> sh) & 0xFFu;
+    forgot |= count >= 4u;
+    table[4 * set + (count & 3u)] = id;
+    return count;
+}
+
+// true if this lane's insertion makes its id a new node
+__device__ __forceinline__ bool sets_confirm(const uint32_t *table, const uint32_t *cursor, uint32_t set, uint32_t count,
+                                             uint32_t id, bool &forgot, bool &lost)
+{
+    const uint4 f = *reinterpret_cast<const uint4 *>(table + 4 * set);
+    const uint32_t now = (cursor[set >> 2] >> (8u * (set & 3u))) & 0xFFu;
+    if (((now - count) & 0xFFu) > 4u) {
+        // four or more insertions into this set came after this lane's: its way was written again
+        lost = true;
+        forgot = true;
+        return true;
+    }
+    const uint32_t way = count & 3u;
+    const uint32_t fw[4] = {f.x, f.y, f.z, f.w};
+    bool lower = false;
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) lower |= (k < way) & (fw[k] == id);
+    return !lower;
 }
 
 }  // namespace cagra

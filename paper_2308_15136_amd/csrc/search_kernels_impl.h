@@ -160,6 +160,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 
     uint32_t n_iter = 0, n_parent_total = 0, n_dist_total = 0, flags = 0;
     bool overflow = false;
+    bool forgot = false;                 // kTableSets: the table has dropped an id it once held
     uint32_t ahead[CR];                  // graph row read ahead for the likely next parent
     uint32_t ahead_id = kInvalidId;
 #pragma unroll
@@ -169,13 +170,27 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     for (int it = 0;; ++it) {
         // ---- step 3: first-time test, compaction, team distances -------------------------
         int n_new = 0;
+        bool lost = false;               // kTableSets: an id of this pass did not survive its own insertion
+        bool fresh[CR];
+        if constexpr (KIND == kTableSets) {
+            uint32_t set[CR], way[CR];   // way: the set's insertion count before this lane's
+#pragma unroll
+            for (int r = 0; r < CR; ++r) fresh[r] = sets_lookup(table, sets, raw[r], raw[r] != kInvalidId, set[r]);
+            lds_order();   // the 16-byte reads and the 4-byte writes below touch the same words
+#pragma unroll
+            for (int r = 0; r < CR; ++r) way[r] = fresh[r] ? sets_insert(table, cursor, set[r], raw[r], forgot) : 0u;
+            lds_order();
+#pragma unroll
+            for (int r = 0; r < CR; ++r) fresh[r] = fresh[r] && sets_confirm(table, cursor, set[r], way[r], raw[r], forgot, lost);
+        }
 #pragma unroll
         for (int r = 0; r < CR; ++r) {
             bool isnew = false;
-            if (raw[r] != kInvalidId) {
+            if constexpr (KIND == kTableSets) {
+                isnew = fresh[r];
+            } else if (raw[r] != kInvalidId) {
                 if constexpr (KIND == kTableGlobal) isnew = visited_insert_global(table, P.hash_bits, raw[r], overflow);
-                else if constexpr (KIND == kTableReset) isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
-                else isnew = visited_insert_sets(table, cursor, sets, raw[r]);
+                else isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
             }
             const uint64_t m = __ballot(isnew);
             const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
@@ -273,6 +288,38 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                 better[r] = __ballot(key_less(chi[r], clo[r], whi, wlo));
                 n_better += __popcll(better[r]);
             }
+            if constexpr (KIND == kTableSets) {
+                // The table only filters: where it may have let a node through twice, winners are
+                // checked before they enter the list (a node that is measured again has the same key,
+                // so only a winner can be a copy of a list member).
+                if (n_better != 0 && __ballot(lost) != 0ull) {
+                    drop_duplicates<MR, CR>(tlo, chi, clo, lane);
+                    n_better = 0;
+#pragma unroll
+                    for (int r = 0; r < CR; ++r) {
+                        better[r] = __ballot(key_less(chi[r], clo[r], whi, wlo));
+                        n_better += __popcll(better[r]);
+                    }
+                } else if (n_better != 0 && __ballot(forgot) != 0ull) {
+#pragma unroll
+                    for (int r = 0; r < CR; ++r) {
+                        uint64_t m = better[r];
+                        while (m != 0ull) {
+                            const int l = __builtin_ctzll(m);
+                            m &= m - 1;
+                            const uint32_t id = __builtin_amdgcn_readlane(clo[r], l) >> 1;
+                            bool same = false;
+#pragma unroll
+                            for (int t2 = 0; t2 < MR; ++t2) same |= (tlo[t2] >> 1) == id;
+                            if (__ballot(same) != 0ull) {
+                                if (lane == l) { chi[r] = kDummyHi; clo[r] = kInvalidId; }
+                                better[r] &= ~(1ull << l);
+                                --n_better;
+                            }
+                        }
+                    }
+                }
+            }
             if (n_better != 0) {
                 if (n_better <= kInsertLimit) {
                     // few winners (the usual case once the list has settled): one ordered
@@ -283,12 +330,30 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                         while (m != 0ull) {
                             const int l = __builtin_ctzll(m);
                             m &= m - 1;
-                            insert_into_topm<MR, KIND == kTableSets>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
-                                                                     __builtin_amdgcn_readlane(clo[r], l), lane);
+                            insert_into_topm<MR>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
+                                                 __builtin_amdgcn_readlane(clo[r], l), lane);
                         }
                     }
+                } else if (CR > 1 && n_better <= kWave) {
+                    // the winners fit one register: gather them through LDS (the candidate arrays are
+                    // free until the next pass), sort 64 keys instead of 64 * CR
+                    int before = 0;
+#pragma unroll
+                    for (int r = 0; r < CR; ++r) {
+                        const uint64_t m = better[r];
+                        const int pos = before + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                        if ((m >> lane) & 1ull) { newid[pos] = clo[r]; newdist[pos] = __uint_as_float(chi[r]); }
+                        before += __popcll(m);
+                    }
+                    __syncthreads();
+                    uint32_t whi1[1], wlo1[1];
+                    whi1[0] = lane < n_better ? __float_as_uint(newdist[lane]) : kDummyHi;
+                    wlo1[0] = lane < n_better ? newid[lane] : kInvalidId;
+                    __syncthreads();
+                    bitonic_sort<1>(whi1, wlo1, lane);
+                    merge_into_topm<MR, 1>(thi, tlo, whi1, wlo1, lane);
                 } else {
-                    if constexpr (KIND == kTableSets) drop_duplicates<MR, CR>(tlo, chi, clo, lane);
                     bitonic_sort<CR>(chi, clo, lane);
                     merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
                 }
