@@ -102,8 +102,23 @@ def main() -> int:
     queries = torch.from_numpy(w.queries).to(dev)
 
     t0 = time.time()
-    graph = cagra.build(base, w.degree, w.init_degree, w.metric)
-    torch.cuda.synchronize()
+    if N <= 2_000_000:
+        graph = cagra.build(base, w.degree, w.init_degree, w.metric)
+        torch.cuda.synchronize()
+    else:
+        # the same two stages as cagra_build, the first in slices of rows so that a long build
+        # reports its progress
+        knn = torch.empty((N, w.init_degree), dtype=torch.int32, device=dev)
+        step = 250_000
+        for lo in range(0, N, step):
+            hi = min(N, lo + step)
+            knn[lo:hi] = cagra.exact_search(base, base[lo:hi], w.init_degree, w.metric, exclude_self=True,
+                                            self_offset=lo, return_dists=False)
+            torch.cuda.synchronize()
+            log(f"[bench] k-NN graph rows {hi}/{N} after {time.time() - t0:.0f}s")
+        graph = cagra.optimize(knn, w.degree)
+        torch.cuda.synchronize()
+        del knn
     build_s = time.time() - t0
     log(f"[bench] graph built on the GPU in {build_s:.1f}s")
 
@@ -276,39 +291,45 @@ def main() -> int:
             f"{ref['best_row_gather_GBs']} GB/s")
 
     # ---- small batches in multi-workgroup mode: host-side latency per call (Sec. IV-C.2) -------
+    # Workers per query W and the pass limit I_max are swept (itopk = 32 W, so every worker keeps
+    # the minimum list of 32); recall is measured on the first 1000 queries in one call (the seed of
+    # a query depends on its index in the call, so that is a separate, untimed launch).
     if not args.no_latency:
+        lat_configs = [(args.latency_workers, 0)] + [(W, i) for W in (8, 16, 32) for i in (6, 8, 12, 16)]
+        nq_rec = min(1000, B)
         small = []
-        for nb in (1, 10, 100):
-            mopts = cagra.SearchOptions(seed=20230815, mode=2, wg_per_query=args.latency_workers)
-            plan = cagra.describe(w.degree, dim, nb, w.k, args.latency_itopk, 1, mopts)
-            mws = torch.empty(cagra.search_workspace_bytes(N, w.degree, nb, w.k, args.latency_itopk, 1, mopts),
-                              dtype=torch.uint8, device=dev)
-            m_ids = torch.empty((nb, w.k), dtype=torch.int32, device=dev)
-            m_d = torch.empty((nb, w.k), dtype=torch.float32, device=dev)
-            n_calls = 300
-            lat = np.empty(n_calls)
-            for c in range(-10, n_calls):
-                lo = (max(c, 0) * nb) % (B - nb + 1)
-                qs = queries[lo:lo + nb]
-                t_c = time.perf_counter()
-                cagra.search(graph, base, qs, w.k, args.latency_itopk, 1, w.metric, mopts, out=(m_ids, m_d),
-                             workspace=mws)
-                torch.cuda.synchronize()
-                if c >= 0:
-                    lat[c] = (time.perf_counter() - t_c) * 1e6
-            # recall of this mode on the first 1000 queries, in one call (the seed of a query depends on
-            # its index in the call, so this is a separate, untimed measurement)
-            r_ids, _ = cagra.search(graph, base, queries[:1000], w.k, args.latency_itopk, 1, w.metric, mopts)
-            rec_m = recall_at_k(r_ids.cpu().numpy().view(np.uint32), gt_np[:1000])
-            small.append({"batch": nb, "p50_us": round(float(np.percentile(lat, 50)), 1),
-                          "p99_us": round(float(np.percentile(lat, 99)), 1),
-                          "qps": round(nb / (float(np.mean(lat)) * 1e-6), 1),
-                          "workers": plan["wg_per_query"], "itopk": args.latency_itopk,
-                          "itopk_local": plan["itopk_local"], "recall_at_k_b1000": round(rec_m, 5)})
-            log(f"[bench] multi mode batch {nb}: p50 {small[-1]['p50_us']} us  p99 {small[-1]['p99_us']} us")
+        for W, imax in lat_configs:
+            mopts = cagra.SearchOptions(seed=20230815, mode=2, wg_per_query=W, max_iterations=imax)
+            m_itopk = 32 * W
+            r_ids, _ = cagra.search(graph, base, queries[:nq_rec], w.k, m_itopk, 1, w.metric, mopts)
+            rec_m = recall_at_k(r_ids.cpu().numpy().view(np.uint32), gt_np[:nq_rec])
+            entry = {"workers": W, "itopk": m_itopk, "max_iterations": imax or "auto",
+                     f"recall_at_k_b{nq_rec}": round(rec_m, 5)}
+            for nb in (1, 10, 100):
+                mws = torch.empty(cagra.search_workspace_bytes(N, w.degree, nb, w.k, m_itopk, 1, mopts),
+                                  dtype=torch.uint8, device=dev)
+                m_ids = torch.empty((nb, w.k), dtype=torch.int32, device=dev)
+                m_d = torch.empty((nb, w.k), dtype=torch.float32, device=dev)
+                n_calls = 200
+                lat = np.empty(n_calls)
+                for c in range(-10, n_calls):
+                    lo = (max(c, 0) * nb) % (B - nb + 1)
+                    qs = queries[lo:lo + nb]
+                    t_c = time.perf_counter()
+                    cagra.search(graph, base, qs, w.k, m_itopk, 1, w.metric, mopts, out=(m_ids, m_d), workspace=mws)
+                    torch.cuda.synchronize()
+                    if c >= 0:
+                        lat[c] = (time.perf_counter() - t_c) * 1e6
+                entry[f"b{nb}"] = {"p50_us": round(float(np.percentile(lat, 50)), 1),
+                                   "p99_us": round(float(np.percentile(lat, 99)), 1),
+                                   "qps": round(nb / (float(np.mean(lat)) * 1e-6), 1)}
+            small.append(entry)
+            log(f"[bench] multi mode W={W} I_max={imax or 'auto'}: recall {rec_m:.4f}  batch 1 p50 "
+                f"{entry['b1']['p50_us']} us  batch 10 {entry['b10']['p50_us']} us  batch 100 {entry['b100']['p50_us']} us")
+        good = [e for e in small if e[f"recall_at_k_b{nq_rec}"] >= TARGET_RECALL]
+        best_lat = min(good, key=lambda e: e["b1"]["p50_us"]) if good else None
         out["small_batch"] = {"mode": "multi-workgroup, host wall-clock per call incl. launch and stream sync",
-                              "dataset": f"{w.name} (the 10M x 96 configuration is not built in this run)",
-                              "results": small}
+                              "dataset": w.name, "best_batch1_at_target_recall": best_lat, "results": small}
 
     # ---- CPU oracle on a sample of the same queries (rank 0, N = 1 only) -----------------------
     if not args.no_cpu:
@@ -316,16 +337,20 @@ def main() -> int:
         ns = min(args.cpu_sample, B)
         g_np = graph.cpu().numpy().view(np.uint32)
         oracle.search(g_np, w.base, w.queries[:64], w.k, M, P_WIDTH, w.metric, seed=opts.seed)  # warm-up
+        reps = 0
         t0 = time.perf_counter()
-        o_ids, o_d, o_st = oracle.search(g_np, w.base, w.queries[:ns], w.k, M, P_WIDTH, w.metric,
-                                         seed=opts.seed, return_stats=True)
-        cpu_s = time.perf_counter() - t0
+        while reps == 0 or (time.perf_counter() - t0 < 1.5 and reps < 20):     # >= 1.5 s of wall clock on all cores
+            o_ids, o_d, o_st = oracle.search(g_np, w.base, w.queries[:ns], w.k, M, P_WIDTH, w.metric,
+                                             seed=opts.seed, return_stats=True)
+            reps += 1
+        cpu_s = (time.perf_counter() - t0) / reps
         inter = sum(len(np.intersect1d(a, b)) for a, b in zip(gpu_ids[:ns], o_ids))
         same = gpu_ids[:ns] == o_ids
         rel = float(np.max(np.abs(gpu_d[:ns] - o_d)[same] / np.maximum(np.abs(o_d[same]), 1e-30))) if same.any() else 0.0
         out["cpu_baseline"] = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "sample": f"first {ns} of the {B} queries, same graph, "
-                               f"itopk={M}, search_width={P_WIDTH}, OpenMP over queries, {cpu_s:.2f}s"}
+                               f"itopk={M}, search_width={P_WIDTH}, OpenMP over queries, "
+                               f"{cpu_s:.2f}s per pass over the sample, {reps} passes"}
         out["parity_at_full_size"] = {"sample": ns, "id_agreement": round(inter / float(ns * w.k), 6),
                                       "positionwise_equal": round(float(same.mean()), 6),
                                       "max_rel_dist_err": rel,
