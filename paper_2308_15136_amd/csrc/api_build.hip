@@ -77,9 +77,9 @@ extern "C" {
 
 size_t cagra_exact_search_workspace_bytes(int64_t N, int64_t B, int32_t k)
 {
-    (void)k;
-    if (N < 1 || B < 0) return 256;
-    return up256((size_t)exact_block_rows(N, B) * (size_t)exact_search_pitch(N) * sizeof(float));
+    if (N < 1 || B < 0 || k < 1) return 256;
+    // the distance block, and the running distances of a block of rows
+    return up256((size_t)exact_block_rows(N, B) * ((size_t)exact_search_pitch(N) + (size_t)k) * sizeof(float));
 }
 
 int cagra_exact_search(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,

@@ -1,9 +1,11 @@
 // Exhaustive k-nearest-neighbour search (Eq. 1) for gfx950: also the exact initial
 // k-NN graph of Sec. III-B.1 (with the node itself left out).
 //
-// Two kernels per block of query rows:
-//   dist_tile_kernel   all distances of a block of rows to every dataset row, written to
-//                      a row-major scratch block.  Each output is accumulated one
+// Two kernels per block of query rows and slice of dataset rows (at most kMaxCols of them, so
+// that a block of thousands of query rows fits the scratch space also for very large N; the k
+// best of a row are carried from slice to slice):
+//   dist_tile_kernel   all distances of a block of rows to every dataset row of the slice,
+//                      written to a row-major scratch block.  Each output is accumulated one
 //                      dimension after the other with one fused multiply-add per
 //                      dimension, so its bits do not depend on the tiling and equal
 //                      those of a plain sequential loop.
@@ -125,9 +127,13 @@ __device__ void pool_sort(uint64_t *pool, int tid)
     __syncthreads();
 }
 
+// D holds the distances to dataset rows col0 .. col0 + pitch (beyond the dataset: +inf).  With
+// `carry` the k best found in earlier slices (ids_out, best_d) compete as well.  best_d[rows_total, k]
+// receives the distances of the result; it is dists_out itself where the caller wants distances.
 __global__ void __launch_bounds__(256)
 row_select_kernel(const float *__restrict__ D, int64_t pitch, int64_t rows, int k,
-                  uint32_t *__restrict__ ids_out, float *__restrict__ dists_out, int64_t out_row0)
+                  uint32_t *__restrict__ ids_out, float *__restrict__ best_d, int64_t out_row0,
+                  int64_t best_row0, int64_t col0, int carry)
 {
     __shared__ uint64_t pool[kPool];
     __shared__ int count;
@@ -135,8 +141,21 @@ row_select_kernel(const float *__restrict__ D, int64_t pitch, int64_t rows, int 
     const int64_t row = blockIdx.x;
     if (row >= rows) return;
     const float *src = D + row * pitch;
-    if (tid == 0) count = 0;
+    uint32_t *ids_row = ids_out + (out_row0 + row) * k;
+    float *d_row = best_d + (best_row0 + row) * k;
     uint64_t tau = kKeyInf;
+    if (carry) {
+        // the earlier result is sorted and its valid entries come first
+        for (int i = tid; i < k; i += 256)
+            pool[i] = ((uint64_t)f32_to_ordered(d_row[i]) << 32) | ids_row[i];
+        __syncthreads();
+        int n = 0;
+        for (int i = 0; i < k; ++i) n += (uint32_t)pool[i] != kInvalidId;   // k <= 512, once per slice
+        if (tid == 0) count = n;
+        if (n >= k) tau = pool[k - 1];
+    } else if (tid == 0) {
+        count = 0;
+    }
     __syncthreads();
     for (int64_t base = 0; base < pitch; base += 1024) {
         const int64_t c = base + tid * 4;
@@ -145,7 +164,7 @@ row_select_kernel(const float *__restrict__ D, int64_t pitch, int64_t rows, int 
             const float vals[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                uint64_t key = ((uint64_t)f32_to_ordered(vals[u]) << 32) | (uint32_t)(c + u);
+                uint64_t key = ((uint64_t)f32_to_ordered(vals[u]) << 32) | (uint32_t)(col0 + c + u);
                 if (key < tau) pool[atomicAdd(&count, 1)] = key;
             }
         }
@@ -166,30 +185,44 @@ row_select_kernel(const float *__restrict__ D, int64_t pitch, int64_t rows, int 
     for (int i = tid; i < k; i += 256) {
         const bool ok = i < n;
         const uint64_t key = pool[i];
-        ids_out[(out_row0 + row) * k + i] = ok ? (uint32_t)key : kInvalidId;
-        if (dists_out) dists_out[(out_row0 + row) * k + i] = ok ? ordered_to_f32((uint32_t)(key >> 32)) : __uint_as_float(kFltMaxBits);
+        ids_row[i] = ok ? (uint32_t)key : kInvalidId;
+        d_row[i] = ok ? ordered_to_f32((uint32_t)(key >> 32)) : __uint_as_float(kFltMaxBits);
     }
 }
 
+constexpr int64_t kMaxCols = 1 << 20;   // dataset rows per slice (a multiple of kTile)
+
+int64_t exact_search_pitch(int64_t N)
+{
+    const int64_t cols = N < kMaxCols ? N : kMaxCols;
+    return (cols + kTile - 1) / kTile * kTile;
+}
+
+// scratch: block_rows x exact_search_pitch(N) floats, then block_rows x k floats (the running
+// distances of a block when the caller does not ask for distances)
 hipError_t launch_exact_search(const float *X, int64_t N, int dim, int64_t ldX, int metric,
                                const float *Q, int64_t B, int64_t ldQ, int k, int exclude_self,
                                int64_t self_offset, uint32_t *ids, float *dists, float *scratch,
                                int64_t block_rows, hipStream_t stream)
 {
-    const int64_t pitch = (N + kTile - 1) / kTile * kTile;
+    const int64_t pitch = exact_search_pitch(N);
+    float *running = scratch + block_rows * pitch;
     for (int64_t r0 = 0; r0 < B; r0 += block_rows) {
         const int64_t rows = B - r0 < block_rows ? B - r0 : block_rows;
-        dim3 grid((unsigned)(pitch / kTile), (unsigned)((rows + kTile - 1) / kTile));
-        hipLaunchKernelGGL(dist_tile_kernel, grid, dim3(256), 0, stream, Q, r0 + rows, ldQ, r0, X, N, ldX,
-                           dim, metric, exclude_self, self_offset, scratch, pitch);
-        hipLaunchKernelGGL(row_select_kernel, dim3((unsigned)rows), dim3(256), 0, stream, scratch, pitch,
-                           rows, k, ids, dists, r0);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        for (int64_t c0 = 0; c0 < N; c0 += kMaxCols) {
+            const int64_t cols = N - c0 < kMaxCols ? N - c0 : kMaxCols;
+            dim3 grid((unsigned)(pitch / kTile), (unsigned)((rows + kTile - 1) / kTile));
+            // rows of X from c0 on; the row to leave out is given relative to that slice
+            hipLaunchKernelGGL(dist_tile_kernel, grid, dim3(256), 0, stream, Q, r0 + rows, ldQ, r0, X + c0 * ldX,
+                               cols, ldX, dim, metric, exclude_self, self_offset - c0, scratch, pitch);
+            hipLaunchKernelGGL(row_select_kernel, dim3((unsigned)rows), dim3(256), 0, stream, scratch, pitch,
+                               rows, k, ids, dists ? dists : running, r0, dists ? r0 : (int64_t)0, c0,
+                               c0 > 0 ? 1 : 0);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
     }
     return hipSuccess;
 }
-
-int64_t exact_search_pitch(int64_t N) { return (N + kTile - 1) / kTile * kTile; }
 
 }  // namespace cagra

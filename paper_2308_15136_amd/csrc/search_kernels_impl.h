@@ -60,13 +60,17 @@ __device__ __forceinline__ float4 widen4(const uint4 &p, int i)
     }
 }
 
-// true if id was not in the device-memory table (and is now)
-__device__ __forceinline__ bool visited_insert_global(uint32_t *table, int bits, uint32_t id, bool &overflow)
+// Multi mode issues the first probe of every candidate before the dataset rows are fetched and
+// looks at its answer afterwards (the row loads do not wait for the table).  `old` is what the
+// first probe at the home slot returned; further probes only after a collision.
+__device__ __forceinline__ bool visited_resolve_global(uint32_t *table, int bits, uint32_t id, uint32_t old, bool &overflow)
 {
+    if (old == kInvalidId) return true;
+    if (old == id) return false;
     const uint32_t mask = (1u << bits) - 1u;
-    uint32_t s = hash_slot(id, bits);
-    for (uint32_t probe = 0; probe <= mask; ++probe) {
-        uint32_t old = atomicCAS(&table[s], kInvalidId, id);
+    uint32_t s = (hash_slot(id, bits) + 1) & mask;
+    for (uint32_t probe = 1; probe <= mask; ++probe) {
+        old = atomicCAS(&table[s], kInvalidId, id);
         if (old == kInvalidId) return true;
         if (old == id) return false;
         s = (s + 1) & mask;
@@ -183,23 +187,34 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 #pragma unroll
             for (int r = 0; r < CR; ++r) fresh[r] = fresh[r] && sets_confirm(table, cursor, set[r], way[r], raw[r], forgot, lost);
         }
+        uint32_t first_probe[CR];        // kTableGlobal: answer of the first probe, read after the distances
+        if constexpr (KIND == kTableGlobal) {
+            // Small batches are bound by latency, not by bandwidth: every candidate's row is fetched
+            // while its table probe is still under way, and the distance of a node that turns out to
+            // have been seen is thrown away.
 #pragma unroll
-        for (int r = 0; r < CR; ++r) {
-            bool isnew = false;
-            if constexpr (KIND == kTableSets) {
-                isnew = fresh[r];
-            } else if (raw[r] != kInvalidId) {
-                if constexpr (KIND == kTableGlobal) isnew = visited_insert_global(table, P.hash_bits, raw[r], overflow);
-                else isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
+            for (int r = 0; r < CR; ++r) {
+                first_probe[r] = kInvalidId;
+                if (raw[r] != kInvalidId)
+                    first_probe[r] = atomicCAS(&table[hash_slot(raw[r], P.hash_bits)], kInvalidId, raw[r]);
+                newid[r * kWave + lane] = raw[r];
             }
-            const uint64_t m = __ballot(isnew);
-            const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                         __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            if (isnew) newid[pos] = raw[r];
-            n_new += __popcll(m);
+            n_new = n_cand;
+        } else {
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                bool isnew = false;
+                if constexpr (KIND == kTableSets) isnew = fresh[r];
+                else if (raw[r] != kInvalidId) isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
+                const uint64_t m = __ballot(isnew);
+                const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                if (isnew) newid[pos] = raw[r];
+                n_new += __popcll(m);
+            }
+            n_dist_total += (uint32_t)n_new;
         }
         __syncthreads();
-        n_dist_total += (uint32_t)n_new;
         CAGRA_PHASE(1)
 
         for (int c0 = 0; c0 < n_new; c0 += RIF * n_teams) {
@@ -210,8 +225,9 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 #pragma unroll
             for (int u = 0; u < RIF; ++u) {
                 const int c = c0 + u * n_teams + g;
-                ok[u] = c < n_new;
-                row[u] = static_cast<const unsigned char *>(P.dataset) + (size_t)(ok[u] ? newid[c] : 0u) * P.ld * kElemBytes;
+                const uint32_t node = c < n_new ? newid[c] : kInvalidId;
+                ok[u] = node != kInvalidId;
+                row[u] = static_cast<const unsigned char *>(P.dataset) + (size_t)(ok[u] ? node : 0u) * P.ld * kElemBytes;
                 acc[u] = 0.f;
             }
             for (int base = 0; base < nchunk; base += 4 * team) {
@@ -266,6 +282,10 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         for (int r = 0; r < CR; ++r) {
             int c = r * 64 + lane;
             bool v = c < n_new;
+            if constexpr (KIND == kTableGlobal) {
+                v = raw[r] != kInvalidId && visited_resolve_global(table, P.hash_bits, raw[r], first_probe[r], overflow);
+                n_dist_total += (uint32_t)__popcll(__ballot(v));
+            }
             chi[r] = v ? f32_to_ordered(newdist[c]) : kDummyHi;
             clo[r] = v ? (newid[c] << 1) : kInvalidId;
         }

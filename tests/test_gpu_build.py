@@ -113,3 +113,28 @@ def test_build_rejections(cagra):
         cagra.exact_search(b, b, 513)
     with pytest.raises(cagra.CagraError):
         cagra.build(b[:, :30], 8, 16)          # dim not a multiple of 4
+
+
+def test_exact_search_beyond_one_slice_of_dataset_rows(cagra):
+    # More than 2^20 dataset rows: the exhaustive search walks the dataset in slices and carries the
+    # k best of a row from slice to slice.  Checked on runs of rows at the start, across the slice
+    # boundary and at the end, against the oracle's brute force (integer data: bit-exact).
+    import torch
+    n, dim, k = 1_100_000, 16, 48
+    base = datagen.sift_like(n, dim, 64, seed=5, stream=1)
+    bd = torch.from_numpy(base).cuda()
+    for lo, hi in [(0, 40), (2**20 - 20, 2**20 + 20), (n - 40, n)]:
+        print(f"case sliced exact search rows {lo}..{hi}", flush=True)
+        rows = np.arange(lo, hi, dtype=np.int64)
+        ids = cagra.exact_search(bd, bd[lo:hi], k, cagra.L2, exclude_self=True, self_offset=lo, return_dists=False)
+        ref, ref_d = oracle.knn_graph(base, k, oracle.L2, rows=rows, return_dists=True)
+        np.testing.assert_array_equal(_u32(ids), ref)
+        ids2, d2 = cagra.exact_search(bd, bd[lo:hi], k, cagra.L2, exclude_self=True, self_offset=lo)
+        np.testing.assert_array_equal(_u32(ids2), ref)
+        np.testing.assert_array_equal(d2.cpu().numpy(), ref_d)
+    # plain queries (nothing left out), fewer valid neighbours than k cannot happen here; k = 1 edge
+    q = datagen.sift_like(16, dim, 64, seed=5, stream=2)
+    ids, d = cagra.exact_search(bd, torch.from_numpy(q).cuda(), 1, cagra.L2)
+    r_ids, r_d = oracle.exact_search(base, q, 1, oracle.L2)
+    np.testing.assert_array_equal(_u32(ids), r_ids)
+    np.testing.assert_array_equal(d.cpu().numpy(), r_d)
