@@ -71,6 +71,8 @@ def main() -> int:
     ap.add_argument("--latency-itopk", type=int, default=128)
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from rocprofv3 counters, copied into roofline.traffic")
+    ap.add_argument("--reorder", choices=("rank", "distance"), default="rank",
+                    help="edge reordering of the graph optimisation (Sec. III-B.2); rank is CAGRA's")
     ap.add_argument("--no-graph", action="store_true", help="skip the captured-graph replay of the batch-1 call")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-storage", action="store_true", help="skip the fp16 / uint8 storage part")
@@ -104,22 +106,28 @@ def main() -> int:
 
     t0 = time.time()
     if N <= 2_000_000:
-        graph = cagra.build(base, w.degree, w.init_degree, w.metric)
+        graph = cagra.build(base, w.degree, w.init_degree, w.metric,
+                            reorder=cagra.REORDER_DISTANCE if args.reorder == "distance" else cagra.REORDER_RANK)
         torch.cuda.synchronize()
     else:
         # the same two stages as cagra_build, the first in slices of rows so that a long build
         # reports its progress
         knn = torch.empty((N, w.init_degree), dtype=torch.int32, device=dev)
+        knn_d = torch.empty((N, w.init_degree), dtype=torch.float32, device=dev) if args.reorder == "distance" else None
         step = 250_000
         for lo in range(0, N, step):
             hi = min(N, lo + step)
-            knn[lo:hi] = cagra.exact_search(base, base[lo:hi], w.init_degree, w.metric, exclude_self=True,
-                                            self_offset=lo, return_dists=False)
+            part = cagra.exact_search(base, base[lo:hi], w.init_degree, w.metric, exclude_self=True,
+                                      self_offset=lo, return_dists=knn_d is not None)
+            if knn_d is not None:
+                knn[lo:hi], knn_d[lo:hi] = part
+            else:
+                knn[lo:hi] = part
             torch.cuda.synchronize()
             log(f"[bench] k-NN graph rows {hi}/{N} after {time.time() - t0:.0f}s")
-        graph = cagra.optimize(knn, w.degree)
+        graph = cagra.optimize(knn, w.degree, knn_dists=knn_d)
         torch.cuda.synchronize()
-        del knn
+        del knn, knn_d
     build_s = time.time() - t0
     log(f"[bench] graph built on the GPU in {build_s:.1f}s")
 
@@ -211,7 +219,7 @@ def main() -> int:
                                f"search_width={P_WIDTH}, single-workgroup mode",
                    "itopk": M, "search_width": P_WIDTH, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
                    "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
-                   "graph_build_s": round(build_s, 2)},
+                   "graph_build_s": round(build_s, 2), "reorder": args.reorder},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": args.traffic_bytes,
                      "kernel": "search_single_kernel", "kernel_ms": round(dev_ms, 4),

@@ -194,6 +194,37 @@ int cagra_optimize(const uint32_t *knn, int64_t N, int32_t init_degree, int32_t 
 
 size_t cagra_optimize_workspace_bytes(int64_t N, int32_t init_degree, int32_t degree);
 
+/*
+ * How the edges of a node are reordered before pruning (Sec. III-B.2).  Both count, for every
+ * edge X -> Y of the initial graph, the detourable routes X -> Z -> Y of Eq. 3 and sort the list
+ * by (count, initial rank); they differ in the edge weight w of Eq. 3:
+ *   CAGRA_REORDER_RANK      w = position of the edge in the source's sorted initial list (what
+ *                           CAGRA adopts; integer work only, no distance table);
+ *   CAGRA_REORDER_DISTANCE  w = the distance (needs the distances of the initial graph's edges,
+ *                           knn_dists[N, init_degree], which the exhaustive search returns).
+ */
+typedef enum {
+    CAGRA_REORDER_RANK = 0,
+    CAGRA_REORDER_DISTANCE = 1
+} cagra_reorder;
+
+/* cagra_optimize with the reordering chosen; knn_dists may be NULL for CAGRA_REORDER_RANK.
+ * Same workspace as cagra_optimize. */
+int cagra_optimize_ex(const uint32_t *knn, const float *knn_dists, int64_t N, int32_t init_degree,
+                      int32_t degree, cagra_reorder reorder, uint32_t *graph_out,
+                      uint32_t *pruned_out /* may be NULL */, uint32_t *reversed_out /* may be NULL */,
+                      uint32_t *reversed_len_out /* may be NULL */,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* cagra_build with the reordering chosen (the distance table lives in the workspace). */
+int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                   int32_t degree, int32_t init_degree, cagra_reorder reorder,
+                   uint32_t *graph_out /* [N, degree] */,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t cagra_build_ex_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree,
+                                      cagra_reorder reorder);
+
 /* ---- dataset storage ------------------------------------------------------------------------- */
 
 /* fp32 rows -> fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255).

@@ -50,6 +50,14 @@ def _load():
         lib.oracle_exact_search.argtypes = [f32p, i64, i32, i32, f32p, i64, i32, u32p, f32p]
         lib.oracle_knn_graph.argtypes = [f32p, i64, i32, i32, i64p, i64, i32, u32p, f32p]
         lib.oracle_detour_count.argtypes = [u32p, i64, i32, i64p, i64, u32p]
+        lib.oracle_detour_count_distance.argtypes = [u32p, f32p, i64, i32, i64p, i64, u32p]
+        lib.oracle_optimize_ex.argtypes = [u32p, f32p, i64, i32, i32, u32p]
+        lib.oracle_build_ex.argtypes = [f32p, i64, i32, i32, i32, i32, i32, u32p]
+        lib.oracle_two_hop_counts.argtypes = [u32p, i64, i32, u32p]
+        lib.oracle_strong_components.restype = i64
+        lib.oracle_strong_components.argtypes = [u32p, i64, i32]
+        lib.oracle_weak_components.restype = i64
+        lib.oracle_weak_components.argtypes = [u32p, i64, i32]
         lib.oracle_prune.argtypes = [u32p, u32p, i64, i32, i32, u32p]
         lib.oracle_reverse.argtypes = [u32p, i64, i32, u32p, u32p]
         lib.oracle_merge.argtypes = [u32p, u32p, u32p, i64, i32, u32p]
@@ -140,6 +148,18 @@ def detour_count(g0, rows=None):
     return cnt
 
 
+def detour_count_distance(g0, g0_dist, rows=None):
+    """Eq. 3 with the stored distances as weights (distance-based reordering)."""
+    g0, g0_dist = _u32(g0), _f32(g0_dist)
+    rows_a = None if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    n = g0.shape[0] if rows_a is None else rows_a.shape[0]
+    cnt = np.empty((n, g0.shape[1]), np.uint32)
+    _check(_load().oracle_detour_count_distance(_p(g0, C.c_uint32), _p(g0_dist, C.c_float), g0.shape[0],
+                                                g0.shape[1], _p(rows_a, C.c_int64), n,
+                                                _p(cnt, C.c_uint32)), "detour_count_distance")
+    return cnt
+
+
 def prune(g0, count, d: int):
     g0, count = _u32(g0), _u32(count)
     out = np.empty((g0.shape[0], d), np.uint32)
@@ -167,20 +187,51 @@ def merge(pruned, rev, rev_len):
     return out
 
 
-def optimize(g0, d: int):
+RANK = 0       # reordering by ranks (what CAGRA adopts)
+DISTANCE = 1   # reordering by the stored distances
+
+
+def optimize(g0, d: int, g0_dist=None):
+    """g0_dist given: distance-based reordering, else rank-based."""
     g0 = _u32(g0)
+    gd = None if g0_dist is None else _f32(g0_dist)
     out = np.empty((g0.shape[0], d), np.uint32)
-    _check(_load().oracle_optimize(_p(g0, C.c_uint32), g0.shape[0], g0.shape[1], d,
-                                   _p(out, C.c_uint32)), "optimize")
+    _check(_load().oracle_optimize_ex(_p(g0, C.c_uint32), _p(gd, C.c_float), g0.shape[0], g0.shape[1], d,
+                                      _p(out, C.c_uint32)), "optimize")
     return out
 
 
-def build(base, degree: int, init_degree: int = 0, metric: int = L2):
+def build(base, degree: int, init_degree: int = 0, metric: int = L2, reorder: int = RANK):
     base = _f32(base)
     out = np.empty((base.shape[0], degree), np.uint32)
-    _check(_load().oracle_build(_p(base, C.c_float), base.shape[0], base.shape[1], metric, degree,
-                                init_degree, _p(out, C.c_uint32)), "build")
+    _check(_load().oracle_build_ex(_p(base, C.c_float), base.shape[0], base.shape[1], metric, degree,
+                                   init_degree, reorder, _p(out, C.c_uint32)), "build")
     return out
+
+
+def two_hop_counts(graph) -> np.ndarray:
+    """Sec. III-A: per node, the number of other nodes reachable in one or two steps."""
+    graph = _u32(graph)
+    out = np.empty(graph.shape[0], np.uint32)
+    _check(_load().oracle_two_hop_counts(_p(graph, C.c_uint32), graph.shape[0], graph.shape[1],
+                                         _p(out, C.c_uint32)), "two_hop_counts")
+    return out
+
+
+def strong_components(graph) -> int:
+    graph = _u32(graph)
+    n = int(_load().oracle_strong_components(_p(graph, C.c_uint32), graph.shape[0], graph.shape[1]))
+    if n < 0:
+        raise ValueError("oracle strong_components failed")
+    return n
+
+
+def weak_components(graph) -> int:
+    graph = _u32(graph)
+    n = int(_load().oracle_weak_components(_p(graph, C.c_uint32), graph.shape[0], graph.shape[1]))
+    if n < 0:
+        raise ValueError("oracle weak_components failed")
+    return n
 
 
 def splitmix_fin(z: int) -> int:

@@ -7,8 +7,11 @@
  *
  * Everything follows the paper's own order of steps:
  *   - k-NNS definition and recall:                Sec. II-A, Eq. 1, Eq. 2
+ *   - reachability measures (2-hop count, CC):     Sec. III-A
  *   - initial k-NN graph, rows sorted by distance: Sec. III-B.1
  *   - rank-based detour count, reorder, prune:     Sec. III-B.2, Eq. 3
+ *   - distance-based detour count (the variant the paper compares with):
+ *                                                  Sec. III-B.2, Eq. 3 with distances
  *   - reversed graph and interleaved merge:        Sec. III-B.2
  *   - search steps 0..3, termination, output:      Sec. IV-A
  *   - forgettable visited-set management:          Sec. IV-B.3
@@ -192,6 +195,42 @@ int oracle_detour_count(const uint32_t *g0, int64_t N, int32_t d_init, const int
     return 0;
 }
 
+/* ---- Sec. III-B.2, Eq. 3 with distances as weights --------------------------- */
+/* The distance-based variant: count[X][j] = number of two-hop routes
+ * X -> Z -> Y (Y = G0[X][j], Z in X's list, Y in Z's list) with
+ * max(dist(X, Z), dist(Z, Y)) < dist(X, Y), the distances being those stored
+ * with the initial graph (g0_dist[N][d_init], the table the paper speaks of). */
+int oracle_detour_count_distance(const uint32_t *g0, const float *g0_dist, int64_t N,
+                                 int32_t d_init, const int64_t *rows, int64_t n_rows,
+                                 uint32_t *count)
+{
+    if (!g0 || !g0_dist || !count || N < 1 || d_init < 1) return -1;
+    if (!rows) n_rows = N;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const int64_t x = rows ? rows[t] : t;
+        const uint32_t *lx = g0 + (size_t)x * d_init;
+        const float *dx = g0_dist + (size_t)x * d_init;
+        for (int j = 0; j < d_init; ++j) {
+            const uint32_t y = lx[j];
+            const float wxy = dx[j];
+            uint32_t c = 0;
+            for (int i = 0; i < d_init; ++i) {
+                if (!(dx[i] < wxy)) continue;                     /* w(X->Z) < w(X->Y) */
+                const uint32_t *lz = g0 + (size_t)lx[i] * d_init;
+                const float *dz = g0_dist + (size_t)lx[i] * d_init;
+                for (int l = 0; l < d_init; ++l)
+                    if (lz[l] == y) {                             /* the edge Z -> Y exists */
+                        if (dz[l] < wxy) ++c;                     /* w(Z->Y) < w(X->Y) */
+                        break;
+                    }
+            }
+            count[(size_t)t * d_init + j] = c;
+        }
+    }
+    return 0;
+}
+
 /* Reorder each list by (count, initial rank) ascending and keep the first d. */
 int oracle_prune(const uint32_t *g0, const uint32_t *count, int64_t N, int32_t d_init,
                  int32_t d, uint32_t *pruned)
@@ -261,8 +300,18 @@ int oracle_merge(const uint32_t *pruned, const uint32_t *rev, const uint32_t *re
     return 0;
 }
 
-/* Whole optimisation: initial sorted k-NN graph -> CAGRA graph of degree d. */
+/* Whole optimisation: initial sorted k-NN graph -> CAGRA graph of degree d.
+ * g0_dist == NULL: rank-based reordering (what CAGRA adopts); else distance-based. */
+int oracle_optimize_ex(const uint32_t *g0, const float *g0_dist, int64_t N, int32_t d_init,
+                       int32_t d, uint32_t *graph);
+
 int oracle_optimize(const uint32_t *g0, int64_t N, int32_t d_init, int32_t d, uint32_t *graph)
+{
+    return oracle_optimize_ex(g0, NULL, N, d_init, d, graph);
+}
+
+int oracle_optimize_ex(const uint32_t *g0, const float *g0_dist, int64_t N, int32_t d_init,
+                       int32_t d, uint32_t *graph)
 {
     if (!g0 || !graph || N < 1 || d < 2 || (d & 1) || d > d_init) return -1;
     uint32_t *count = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * d_init);
@@ -271,7 +320,8 @@ int oracle_optimize(const uint32_t *g0, int64_t N, int32_t d_init, int32_t d, ui
     uint32_t *rev_len = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);
     int rc = -2;
     if (count && pruned && rev && rev_len) {
-        rc = oracle_detour_count(g0, N, d_init, NULL, N, count);
+        rc = g0_dist ? oracle_detour_count_distance(g0, g0_dist, N, d_init, NULL, N, count)
+                     : oracle_detour_count(g0, N, d_init, NULL, N, count);
         if (!rc) rc = oracle_prune(g0, count, N, d_init, d, pruned);
         if (!rc) rc = oracle_reverse(pruned, N, d, rev, rev_len);
         if (!rc) rc = oracle_merge(pruned, rev, rev_len, N, d, graph);
@@ -280,17 +330,131 @@ int oracle_optimize(const uint32_t *g0, int64_t N, int32_t d_init, int32_t d, ui
     return rc;
 }
 
+/* reorder: 0 rank-based, 1 distance-based */
+int oracle_build_ex(const float *X, int64_t N, int32_t dim, int32_t metric, int32_t d,
+                    int32_t d_init, int32_t reorder, uint32_t *graph)
+{
+    if (d_init == 0) d_init = 2 * d;
+    if (!X || !graph || N < 2 || d_init >= N || reorder < 0 || reorder > 1) return -1;
+    uint32_t *g0 = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * d_init);
+    float *gd = reorder ? (float *)malloc(sizeof(float) * (size_t)N * d_init) : NULL;
+    int rc = -2;
+    if (g0 && (gd || !reorder)) {
+        rc = oracle_knn_graph(X, N, dim, metric, NULL, N, d_init, g0, gd);
+        if (!rc) rc = oracle_optimize_ex(g0, gd, N, d_init, d, graph);
+    }
+    free(g0);
+    free(gd);
+    return rc;
+}
+
 int oracle_build(const float *X, int64_t N, int32_t dim, int32_t metric, int32_t d,
                  int32_t d_init, uint32_t *graph)
 {
-    if (d_init == 0) d_init = 2 * d;
-    if (!X || !graph || N < 2 || d_init >= N) return -1;
-    uint32_t *g0 = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * d_init);
-    if (!g0) return -2;
-    int rc = oracle_knn_graph(X, N, dim, metric, NULL, N, d_init, g0, NULL);
-    if (!rc) rc = oracle_optimize(g0, N, d_init, d, graph);
-    free(g0);
-    return rc;
+    return oracle_build_ex(X, N, dim, metric, d, d_init, 0, graph);
+}
+
+/* ---- Sec. III-A: how reachability of a graph is measured ---------------------- */
+/* 2-hop node count of X: the number of nodes other than X that can be reached
+ * from X in one or two steps (at most d + d^2). */
+int oracle_two_hop_counts(const uint32_t *graph, int64_t N, int32_t d, uint32_t *counts)
+{
+    if (!graph || !counts || N < 1 || d < 1) return -1;
+#pragma omp parallel
+    {
+        uint8_t *seen = (uint8_t *)calloc((size_t)N, 1);
+        uint32_t *list = (uint32_t *)malloc(sizeof(uint32_t) * ((size_t)d + (size_t)d * d));
+#pragma omp for schedule(dynamic, 256)
+        for (int64_t x = 0; x < N; ++x) {
+            size_t n = 0;
+            if (!seen || !list) { counts[x] = 0; continue; }
+            seen[x] = 1;
+            for (int i = 0; i < d; ++i) {
+                uint32_t y = graph[(size_t)x * d + i];
+                if (!seen[y]) { seen[y] = 1; list[n++] = y; }
+                for (int j = 0; j < d; ++j) {
+                    uint32_t z = graph[(size_t)y * d + j];
+                    if (!seen[z]) { seen[z] = 1; list[n++] = z; }
+                }
+            }
+            counts[x] = (uint32_t)n;
+            seen[x] = 0;
+            for (size_t t = 0; t < n; ++t) seen[list[t]] = 0;
+        }
+        free(seen);
+        free(list);
+    }
+    return 0;
+}
+
+/* Number of strongly connected components (every node of a component reaches
+ * every other one along directed edges): Tarjan's algorithm with an explicit
+ * stack.  Returns -1 on bad arguments, -2 when out of memory. */
+int64_t oracle_strong_components(const uint32_t *graph, int64_t N, int32_t d)
+{
+    if (!graph || N < 1 || d < 1) return -1;
+    int64_t *index = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);   /* discovery order, -1 = new */
+    int64_t *low = (int64_t *)malloc(sizeof(int64_t) * (size_t)N);
+    uint8_t *on_stack = (uint8_t *)calloc((size_t)N, 1);
+    uint32_t *stack = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);       /* Tarjan's node stack */
+    uint32_t *call_node = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);   /* recursion, unrolled */
+    int32_t *call_edge = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    int64_t n_comp = -2;
+    if (index && low && on_stack && stack && call_node && call_edge) {
+        int64_t next = 0, sp = 0;
+        n_comp = 0;
+        for (int64_t v = 0; v < N; ++v) index[v] = -1;
+        for (int64_t root = 0; root < N; ++root) {
+            if (index[root] >= 0) continue;
+            int64_t cp = 0;
+            call_node[0] = (uint32_t)root; call_edge[0] = 0;
+            index[root] = low[root] = next++;
+            stack[sp++] = (uint32_t)root; on_stack[root] = 1;
+            while (cp >= 0) {
+                const uint32_t v = call_node[cp];
+                if (call_edge[cp] < d) {
+                    const uint32_t w = graph[(size_t)v * d + call_edge[cp]++];
+                    if (index[w] < 0) {
+                        index[w] = low[w] = next++;
+                        stack[sp++] = w; on_stack[w] = 1;
+                        ++cp; call_node[cp] = w; call_edge[cp] = 0;
+                    } else if (on_stack[w] && index[w] < low[v]) {
+                        low[v] = index[w];
+                    }
+                } else {
+                    if (low[v] == index[v]) {            /* v is the root of a component */
+                        uint32_t w;
+                        do { w = stack[--sp]; on_stack[w] = 0; } while (w != v);
+                        ++n_comp;
+                    }
+                    --cp;
+                    if (cp >= 0 && low[v] < low[call_node[cp]]) low[call_node[cp]] = low[v];
+                }
+            }
+        }
+    }
+    free(index); free(low); free(on_stack); free(stack); free(call_node); free(call_edge);
+    return n_comp;
+}
+
+/* Number of weakly connected components (edge directions ignored): union-find. */
+int64_t oracle_weak_components(const uint32_t *graph, int64_t N, int32_t d)
+{
+    if (!graph || N < 1 || d < 1) return -1;
+    uint32_t *parent = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);
+    if (!parent) return -2;
+    for (int64_t v = 0; v < N; ++v) parent[v] = (uint32_t)v;
+    for (int64_t v = 0; v < N; ++v)
+        for (int i = 0; i < d; ++i) {
+            uint32_t a = (uint32_t)v, b = graph[(size_t)v * d + i];
+            while (parent[a] != a) { parent[a] = parent[parent[a]]; a = parent[a]; }
+            while (parent[b] != b) { parent[b] = parent[parent[b]]; b = parent[b]; }
+            if (a != b) parent[a > b ? a : b] = a > b ? b : a;
+        }
+    int64_t n_comp = 0;
+    for (int64_t v = 0; v < N; ++v) n_comp += parent[v] == (uint32_t)v;
+    free(parent);
+    return n_comp;
 }
 
 /* ---- step 0 seed generator --------------------------------------------------- */

@@ -26,6 +26,8 @@ IP = 1
 F32 = 0
 F16 = 1
 U8 = 2
+REORDER_RANK = 0
+REORDER_DISTANCE = 1
 INVALID_ID = -1  # 0xFFFFFFFF seen through int32
 
 _lib = None
@@ -87,6 +89,12 @@ def load_library():
     lib.cagra_optimize.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.cagra_optimize_workspace_bytes.restype = sz
     lib.cagra_optimize_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.cagra_optimize_ex.restype = C.c_int
+    lib.cagra_optimize_ex.argtypes = [vp, vp, i64, i32, i32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
+    lib.cagra_build_ex.restype = C.c_int
+    lib.cagra_build_ex.argtypes = [vp, i64, i32, i64, C.c_int, i32, i32, C.c_int, vp, vp, sz, vp]
+    lib.cagra_build_ex_workspace_bytes.restype = sz
+    lib.cagra_build_ex_workspace_bytes.argtypes = [i64, i32, i32, i32, C.c_int]
     lib.cagra_probe_bandwidth.restype = C.c_int
     lib.cagra_probe_bandwidth.argtypes = [vp, i64, i64, i64, i32, i64, i32, i32, i32, C.c_uint64, vp, vp]
     _lib = lib
@@ -270,7 +278,7 @@ def exact_search(dataset, queries, k: int, metric: int = L2, exclude_self: bool 
     return (ids, dists) if return_dists else ids
 
 
-def build(dataset, degree: int, init_degree: int = 0, metric: int = L2):
+def build(dataset, degree: int, init_degree: int = 0, metric: int = L2, reorder: int = REORDER_RANK):
     """dataset[N, dim] -> CAGRA graph[N, degree] (int32 tensor)."""
     torch = _torch()
     lib = load_library()
@@ -278,19 +286,24 @@ def build(dataset, degree: int, init_degree: int = 0, metric: int = L2):
     dev = dataset.device
     N, dim = dataset.shape
     graph = torch.empty((N, degree), dtype=torch.int32, device=dev)
-    ws = _workspace(lib.cagra_build_workspace_bytes(N, dim, degree, init_degree), dev)
-    rc = lib.cagra_build(dataset.data_ptr(), N, dim, dataset.stride(0), metric, degree, init_degree,
-                         graph.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev))
-    _check(rc, "cagra_build")
+    ws = _workspace(lib.cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, reorder), dev)
+    rc = lib.cagra_build_ex(dataset.data_ptr(), N, dim, dataset.stride(0), metric, degree, init_degree, reorder,
+                            graph.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev))
+    _check(rc, "cagra_build_ex")
     return graph
 
 
-def optimize(knn, degree: int, return_stages: bool = False):
+def optimize(knn, degree: int, return_stages: bool = False, knn_dists=None):
     """Sorted k-NN graph[N, init_degree] -> CAGRA graph[N, degree]; optionally also the
-    pruned graph, the reversed graph and its list lengths."""
+    pruned graph, the reversed graph and its list lengths.  With knn_dists[N, init_degree]
+    the reordering is distance-based, else rank-based."""
     torch = _torch()
     lib = load_library()
     knn = _dev_i32(knn, "knn")
+    if knn_dists is not None:
+        knn_dists = _dev_f32(knn_dists, "knn_dists")
+        if knn_dists.shape != knn.shape or not knn_dists.is_contiguous():
+            raise TypeError("knn_dists must be contiguous and shaped like knn")
     dev = knn.device
     N, init_degree = knn.shape
     graph = torch.empty((N, degree), dtype=torch.int32, device=dev)
@@ -300,10 +313,12 @@ def optimize(knn, degree: int, return_stages: bool = False):
         rev = torch.empty((N, degree), dtype=torch.int32, device=dev)
         rlen = torch.empty((N,), dtype=torch.int32, device=dev)
     ws = _workspace(lib.cagra_optimize_workspace_bytes(N, init_degree, degree), dev)
-    rc = lib.cagra_optimize(knn.data_ptr(), N, init_degree, degree, graph.data_ptr(),
-                            pruned.data_ptr() if pruned is not None else None,
-                            rev.data_ptr() if rev is not None else None,
-                            rlen.data_ptr() if rlen is not None else None,
-                            ws.data_ptr(), ws.numel(), _stream(dev))
-    _check(rc, "cagra_optimize")
+    rc = lib.cagra_optimize_ex(knn.data_ptr(), knn_dists.data_ptr() if knn_dists is not None else None,
+                               N, init_degree, degree,
+                               REORDER_DISTANCE if knn_dists is not None else REORDER_RANK, graph.data_ptr(),
+                               pruned.data_ptr() if pruned is not None else None,
+                               rev.data_ptr() if rev is not None else None,
+                               rlen.data_ptr() if rlen is not None else None,
+                               ws.data_ptr(), ws.numel(), _stream(dev))
+    _check(rc, "cagra_optimize_ex")
     return (graph, pruned, rev, rlen) if return_stages else graph

@@ -118,7 +118,17 @@ int cagra_optimize(const uint32_t *knn, int64_t N, int32_t init_degree, int32_t 
                    uint32_t *graph_out, uint32_t *pruned_out, uint32_t *reversed_out,
                    uint32_t *reversed_len_out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
+    return cagra_optimize_ex(knn, nullptr, N, init_degree, degree, CAGRA_REORDER_RANK, graph_out, pruned_out,
+                             reversed_out, reversed_len_out, workspace, workspace_bytes, hip_stream);
+}
+
+int cagra_optimize_ex(const uint32_t *knn, const float *knn_dists, int64_t N, int32_t init_degree, int32_t degree,
+                      cagra_reorder reorder, uint32_t *graph_out, uint32_t *pruned_out, uint32_t *reversed_out,
+                      uint32_t *reversed_len_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
     if (!knn || !graph_out) return CAGRA_ERR_NULL_POINTER;
+    if (reorder != CAGRA_REORDER_RANK && reorder != CAGRA_REORDER_DISTANCE) return CAGRA_ERR_BAD_OPTION;
+    if (reorder == CAGRA_REORDER_DISTANCE && !knn_dists) return CAGRA_ERR_NULL_POINTER;
     if (N < 2 || N > 0x7FFFFFFFll) return CAGRA_ERR_BAD_SHAPE;
     int rc = check_degrees(N, degree, init_degree);
     if (rc != CAGRA_OK) return rc;
@@ -126,8 +136,8 @@ int cagra_optimize(const uint32_t *knn, int64_t N, int32_t init_degree, int32_t 
         workspace_bytes < cagra_optimize_workspace_bytes(N, init_degree, degree))
         return CAGRA_ERR_WORKSPACE;
     OptimizeCarve c = carve_optimize(workspace, N, degree);
-    hipError_t e = launch_optimize(knn, N, init_degree, degree, graph_out,
-                                   pruned_out ? pruned_out : c.pruned,
+    hipError_t e = launch_optimize(knn, reorder == CAGRA_REORDER_DISTANCE ? knn_dists : nullptr, N, init_degree,
+                                   degree, graph_out, pruned_out ? pruned_out : c.pruned,
                                    reversed_out ? reversed_out : c.rev,
                                    reversed_len_out ? reversed_len_out : c.rev_len, c.s,
                                    static_cast<hipStream_t>(hip_stream));
@@ -136,10 +146,18 @@ int cagra_optimize(const uint32_t *knn, int64_t N, int32_t init_degree, int32_t 
 
 size_t cagra_build_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree)
 {
+    return cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, CAGRA_REORDER_RANK);
+}
+
+size_t cagra_build_ex_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree,
+                                      cagra_reorder reorder)
+{
     (void)dim;
     if (init_degree == 0) init_degree = 2 * degree;
     if (N < 1 || degree < 1) return 256;
-    const size_t knn = up256((size_t)N * init_degree * sizeof(uint32_t));
+    // the k-NN graph, for the distance-based reordering also its distances
+    const size_t knn = up256((size_t)N * init_degree * sizeof(uint32_t)) *
+                       (reorder == CAGRA_REORDER_DISTANCE ? 2 : 1);
     // the distance block is dead once the k-NN graph exists, so the optimisation reuses its space
     return knn + std::max(cagra_exact_search_workspace_bytes(N, N, init_degree),
                           cagra_optimize_workspace_bytes(N, init_degree, degree));
@@ -149,7 +167,16 @@ int cagra_build(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_
                 int32_t degree, int32_t init_degree, uint32_t *graph_out, void *workspace,
                 size_t workspace_bytes, void *hip_stream)
 {
+    return cagra_build_ex(dataset, N, dim, ld, metric, degree, init_degree, CAGRA_REORDER_RANK, graph_out,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                   int32_t degree, int32_t init_degree, cagra_reorder reorder, uint32_t *graph_out,
+                   void *workspace, size_t workspace_bytes, void *hip_stream)
+{
     if (init_degree == 0) init_degree = 2 * degree;
+    if (reorder != CAGRA_REORDER_RANK && reorder != CAGRA_REORDER_DISTANCE) return CAGRA_ERR_BAD_OPTION;
     if (!dataset || !graph_out) return CAGRA_ERR_NULL_POINTER;
     if (N < 2) return CAGRA_ERR_BAD_SHAPE;
     int rc = check_matrix(dataset, N, dim, ld);
@@ -158,17 +185,23 @@ int cagra_build(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_
     rc = check_degrees(N, degree, init_degree);
     if (rc != CAGRA_OK) return rc;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
-        workspace_bytes < cagra_build_workspace_bytes(N, dim, degree, init_degree))
+        workspace_bytes < cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, reorder))
         return CAGRA_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const size_t knn_bytes = up256((size_t)N * init_degree * sizeof(uint32_t));
     uint32_t *knn = static_cast<uint32_t *>(workspace);
-    unsigned char *rest = static_cast<unsigned char *>(workspace) + up256((size_t)N * init_degree * sizeof(uint32_t));
+    unsigned char *rest = static_cast<unsigned char *>(workspace) + knn_bytes;
+    float *knn_dists = nullptr;
+    if (reorder == CAGRA_REORDER_DISTANCE) {
+        knn_dists = reinterpret_cast<float *>(rest);
+        rest += knn_bytes;
+    }
     hipError_t e = launch_exact_search(dataset, N, dim, ld, (int)metric, dataset, N, ld, init_degree, 1, 0,
-                                       knn, nullptr, reinterpret_cast<float *>(rest),
+                                       knn, knn_dists, reinterpret_cast<float *>(rest),
                                        exact_block_rows(N, N), stream);
     if (e != hipSuccess) return CAGRA_ERR_LAUNCH;
     OptimizeCarve c = carve_optimize(rest, N, degree);
-    e = launch_optimize(knn, N, init_degree, degree, graph_out, c.pruned, c.rev, c.rev_len, c.s, stream);
+    e = launch_optimize(knn, knn_dists, N, init_degree, degree, graph_out, c.pruned, c.rev, c.rev_len, c.s, stream);
     return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
 }
 

@@ -20,7 +20,8 @@ struct OptimizeScratch {
     uint64_t *bucket;     // [N * degree]
 };
 
-hipError_t launch_optimize(const uint32_t *knn, int64_t N, int d_init, int d, uint32_t *graph,
+// knn_dist == nullptr: rank-based reordering; else the distances of the knn entries are the weights
+hipError_t launch_optimize(const uint32_t *knn, const float *knn_dist, int64_t N, int d_init, int d, uint32_t *graph,
                            uint32_t *pruned, uint32_t *rev, uint32_t *rev_len,
                            const OptimizeScratch &s, hipStream_t stream);
 

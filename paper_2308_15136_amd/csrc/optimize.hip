@@ -1,5 +1,7 @@
-// CAGRA graph optimisation for gfx950 (Sec. III-B.2): rank-based detour count (Eq. 3),
-// reorder and prune, reversed graph, interleaved merge.  Integer work only.
+// CAGRA graph optimisation for gfx950 (Sec. III-B.2): detour count (Eq. 3) with ranks as edge
+// weights (what CAGRA adopts; integer work only) or with the stored distances of the initial
+// graph (the distance-based variant the paper compares with), reorder and prune, reversed
+// graph, interleaved merge.
 #include "device_util.h"
 #include "build_kernels.h"
 
@@ -9,16 +11,18 @@ namespace cagra {
 // One workgroup (256 threads) per node X.  The initial list of X sits in LDS together with a
 // small open-addressing map id -> rank in that list.  For every Z = list[i] the list of Z is
 // streamed once; an entry W at rank l of Z that is also entry j of X is a detourable route for
-// the edge X -> W iff max(i, l) < j.
+// the edge X -> W iff max(i, l) < j (rank-based), or iff both hops are shorter than the edge,
+// max(dist(X, Z), dist(Z, W)) < dist(X, W), when the distance table knn_dist is given.
 
 constexpr int kMaxInit = 512;
 constexpr int kMapSize = 2048;   // >= 4 * kMaxInit
 
 __global__ void __launch_bounds__(256)
-prune_kernel(const uint32_t *__restrict__ knn, int64_t N, int d_init, int d,
+prune_kernel(const uint32_t *__restrict__ knn, const float *__restrict__ knn_dist, int64_t N, int d_init, int d,
              uint32_t *__restrict__ pruned)
 {
     __shared__ uint32_t xlist[kMaxInit];
+    __shared__ float xdist[kMaxInit];
     __shared__ uint32_t cnt[kMaxInit];
     __shared__ uint32_t map_key[kMapSize];
     __shared__ uint16_t map_val[kMapSize];
@@ -27,7 +31,11 @@ prune_kernel(const uint32_t *__restrict__ knn, int64_t N, int d_init, int d,
     const uint32_t *lx = knn + x * d_init;
 
     for (int i = tid; i < kMapSize; i += 256) map_key[i] = kInvalidId;
-    for (int i = tid; i < d_init; i += 256) { xlist[i] = lx[i]; cnt[i] = 0; }
+    for (int i = tid; i < d_init; i += 256) {
+        xlist[i] = lx[i];
+        cnt[i] = 0;
+        xdist[i] = knn_dist ? knn_dist[x * d_init + i] : 0.f;
+    }
     __syncthreads();
     for (int j = tid; j < d_init; j += 256) {
         uint32_t id = xlist[j];
@@ -43,6 +51,7 @@ prune_kernel(const uint32_t *__restrict__ knn, int64_t N, int d_init, int d,
     const int wave = tid >> 6, lane = tid & 63;
     for (int i = wave; i < d_init; i += 4) {
         const uint32_t *lz = knn + (int64_t)xlist[i] * d_init;
+        const float *dz = knn_dist ? knn_dist + (int64_t)xlist[i] * d_init : nullptr;
         for (int l = lane; l < d_init; l += 64) {
             const uint32_t w = lz[l];
             uint32_t s = (w * 2654435761u) >> 21;
@@ -51,7 +60,8 @@ prune_kernel(const uint32_t *__restrict__ knn, int64_t N, int d_init, int d,
                 if (key == kInvalidId) break;
                 if (key == w) {
                     const int j = map_val[s];
-                    if (j > i && j > l) atomicAdd(&cnt[j], 1u);
+                    const bool detour = dz ? (xdist[i] < xdist[j] && dz[l] < xdist[j]) : (j > i && j > l);
+                    if (detour) atomicAdd(&cnt[j], 1u);
                     break;
                 }
                 s = (s + 1) & (kMapSize - 1);
@@ -254,13 +264,13 @@ __global__ void merge_kernel(const uint32_t *__restrict__ pruned, const uint32_t
 
 static unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
-hipError_t launch_optimize(const uint32_t *knn, int64_t N, int d_init, int d, uint32_t *graph,
+hipError_t launch_optimize(const uint32_t *knn, const float *knn_dist, int64_t N, int d_init, int d, uint32_t *graph,
                            uint32_t *pruned, uint32_t *rev, uint32_t *rev_len,
                            const OptimizeScratch &s, hipStream_t stream)
 {
     const int64_t n_edges = N * d;
     const int64_t n_blocks = (N + 1023) / 1024;
-    hipLaunchKernelGGL(prune_kernel, dim3((unsigned)N), dim3(256), 0, stream, knn, N, d_init, d, pruned);
+    hipLaunchKernelGGL(prune_kernel, dim3((unsigned)N), dim3(256), 0, stream, knn, knn_dist, N, d_init, d, pruned);
     hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.indeg, N, 0u);
     hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.cursor, N, 0u);
     hipLaunchKernelGGL(indegree_kernel, dim3(blocks_for(n_edges, 256)), dim3(256), 0, stream, pruned, n_edges, s.indeg);

@@ -138,3 +138,25 @@ def test_exact_search_beyond_one_slice_of_dataset_rows(cagra):
     r_ids, r_d = oracle.exact_search(base, q, 1, oracle.L2)
     np.testing.assert_array_equal(_u32(ids), r_ids)
     np.testing.assert_array_equal(d.cpu().numpy(), r_d)
+
+
+@pytest.mark.parametrize("name,n,d", [("tiny", 10_000, 32), ("sift1m", 6_000, 64), ("deep1m", 3_000, 2),
+                                      ("glove200", 1_500, 128)])
+def test_distance_based_reordering_bit_exact(cagra, name, n, d):
+    # Sec. III-B.2, the variant with distances as the weights of Eq. 3: the distance table is the
+    # exhaustive search's own output (bit-exact against the oracle's), the counts are integers.
+    print(f"case distance-based reordering {name} n={n} d={d}", flush=True)
+    w = datagen.workload(name, n=n, n_queries=1)
+    b = _dev(w.base)
+    g0, gd = oracle.knn_graph(w.base, 2 * d, w.metric, return_dists=True)
+    ids, dists = cagra.exact_search(b, b, 2 * d, w.metric, exclude_self=True)
+    np.testing.assert_array_equal(_u32(ids), g0)
+    np.testing.assert_array_equal(dists.cpu().numpy(), gd)
+    graph, pruned, rev, rlen = cagra.optimize(ids, d, return_stages=True, knn_dists=dists)
+    o_pr = oracle.prune(g0, oracle.detour_count_distance(g0, gd), d)
+    np.testing.assert_array_equal(_u32(pruned), o_pr)
+    np.testing.assert_array_equal(_u32(graph), oracle.optimize(g0, d, g0_dist=gd))
+    np.testing.assert_array_equal(_u32(cagra.build(b, d, 0, w.metric, reorder=cagra.REORDER_DISTANCE)),
+                                  oracle.build(w.base, d, 0, w.metric, reorder=oracle.DISTANCE))
+    # integer data has many equal distances (strict comparisons matter); the two reorderings differ
+    assert not np.array_equal(_u32(graph), oracle.optimize(g0, d))

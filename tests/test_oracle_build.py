@@ -219,3 +219,123 @@ def test_detour_count_rows_subset_equals_full():
     full = oracle.detour_count(g0)
     rows = np.array([399, 0, 17, 200], np.int64)
     np.testing.assert_array_equal(oracle.detour_count(g0, rows=rows), full[rows])
+
+
+# ---- distance-based reordering (Sec. III-B.2, the variant the paper compares with) ------------
+
+def test_distance_based_count_on_a_line_by_hand():
+    # Five points on a line at 0, 1, 3, 7, 15 (squared distances are integers), d_init = 4: every
+    # node lists every other node.  A route X -> Z -> Y counts iff both hops are shorter than the
+    # direct edge.  From the end point 0 every nearer point is a detour to every farther one:
+    # counts 0, 1, 2, 3 along its list (1, 3, 7, 15).  From the point at 3 (list 1, 0, 7, 15 at
+    # squared distances 4, 9, 16, 144): to 0 via 1 (4 < 9, 1 < 9): 1 route; to 7 none (1 -> 7 is
+    # 36, 0 -> 7 is 49, both >= 16); to 15 only via 7 (16 < 144, 64 < 144): 1 route.
+    pts = np.array([[0.0], [1.0], [3.0], [7.0], [15.0]], np.float32)
+    g0, gd = oracle.knn_graph(pts, 4, return_dists=True)
+    assert g0[0].tolist() == [1, 2, 3, 4] and g0[2].tolist() == [1, 0, 3, 4] and g0[4].tolist() == [3, 2, 1, 0]
+    assert gd[2].tolist() == [4.0, 9.0, 16.0, 144.0]
+    cnt = oracle.detour_count_distance(g0, gd)
+    assert cnt[0].tolist() == [0, 1, 2, 3]
+    assert cnt[2].tolist() == [0, 1, 0, 1]
+    assert cnt[4].tolist() == [0, 1, 2, 3]
+
+
+def test_distance_based_count_is_the_lune_count_on_complete_lists():
+    # d_init = N-1: every edge exists, so the count for X -> Y is the number of points Z that are
+    # closer than |XY| to both X and Y (the lune of the relative neighbourhood graph) -- a property
+    # of the metric alone, computed here from float64 distances (exact on integer data).
+    n = 40
+    base = datagen.sift_like(n, 8, 3, seed=11, stream=1)
+    g0, gd = oracle.knn_graph(base, n - 1, return_dists=True)
+    b = base.astype(np.float64)
+    D = ((b[:, None, :] - b[None, :, :]) ** 2).sum(-1)
+    cnt = oracle.detour_count_distance(g0, gd)
+    for x in range(n):
+        for j in range(n - 1):
+            y = int(g0[x, j])
+            want = sum(1 for z in range(n) if z != x and z != y and D[x, z] < D[x, y] and D[z, y] < D[x, y])
+            assert cnt[x, j] == want
+
+
+def test_distance_based_count_bounds_and_subset():
+    w = datagen.workload("deep1m", n=1500, n_queries=1)
+    g0, gd = oracle.knn_graph(w.base, 24, return_dists=True)
+    cnt = oracle.detour_count_distance(g0, gd)
+    assert np.all(cnt[:, 0] == 0)
+    # a detour's first hop is strictly shorter than the edge, so it sits earlier in the sorted list
+    assert np.all(cnt <= np.arange(24)[None, :])
+    rows = np.array([0, 7, 700, 1499], np.int64)
+    np.testing.assert_array_equal(oracle.detour_count_distance(g0, gd, rows=rows), cnt[rows])
+    # literal set form: routes through Z need Y in Z's list
+    member = [set(r.tolist()) for r in g0]
+    for x in (3, 999):
+        for j in range(24):
+            y = int(g0[x, j])
+            want = 0
+            for i in range(24):
+                z = int(g0[x, i])
+                if y in member[z] and gd[x, i] < gd[x, j] and gd[z, g0[z].tolist().index(y)] < gd[x, j]:
+                    want += 1
+            assert cnt[x, j] == want
+
+
+def test_distance_based_build_keeps_the_graph_invariants():
+    w = datagen.workload("tiny", n=1200, n_queries=1)
+    g = oracle.build(w.base, 16, 32, w.metric, reorder=oracle.DISTANCE)
+    n = g.shape[0]
+    assert g.shape == (n, 16) and g.max() < n
+    assert not np.any(g == np.arange(n, dtype=np.uint32)[:, None])
+    assert all(len(set(r.tolist())) == 16 for r in g)
+    g0, gd = oracle.knn_graph(w.base, 32, w.metric, return_dists=True)
+    np.testing.assert_array_equal(g, oracle.optimize(g0, 16, g0_dist=gd))
+    assert np.all(g[:, 0] == g0[:, 0])      # the nearest neighbour has no detour and stays first
+
+
+# ---- reachability measures of Sec. III-A ------------------------------------------------------
+
+def _adjacency(g):
+    n = g.shape[0]
+    a = np.zeros((n, n), bool)
+    a[np.repeat(np.arange(n), g.shape[1]), g.reshape(-1)] = True
+    return a
+
+
+def test_two_hop_counts_against_the_adjacency_matrix():
+    rng = np.random.default_rng(5)
+    n, d = 300, 5
+    g = np.stack([rng.choice(np.setdiff1d(np.arange(n), [x]), size=d, replace=False) for x in range(n)]).astype(np.uint32)
+    a = _adjacency(g)
+    reach = a | ((a.astype(np.int32) @ a.astype(np.int32)) > 0)     # one or two steps
+    reach[np.arange(n), np.arange(n)] = False                         # the node itself does not count
+    np.testing.assert_array_equal(oracle.two_hop_counts(g), reach.sum(1).astype(np.uint32))
+    # closed forms: a ring with one edge per node reaches 2 nodes, a complete graph all others,
+    # and nothing exceeds d + d^2
+    ring = ((np.arange(10) + 1) % 10).astype(np.uint32)[:, None]
+    assert oracle.two_hop_counts(ring).tolist() == [2] * 10
+    full = np.stack([np.setdiff1d(np.arange(7), [x]) for x in range(7)]).astype(np.uint32)
+    assert oracle.two_hop_counts(full).tolist() == [6] * 7
+    assert oracle.two_hop_counts(g).max() <= d + d * d
+
+
+def test_component_counts_against_scipy_and_by_hand():
+    from scipy.sparse import csr_matrix
+    from scipy.sparse.csgraph import connected_components
+    rng = np.random.default_rng(8)
+    for n, d in [(400, 1), (400, 2), (2000, 3), (50, 6)]:
+        g = np.stack([rng.choice(np.setdiff1d(np.arange(n), [x]), size=d, replace=False) for x in range(n)]).astype(np.uint32)
+        adj = csr_matrix(_adjacency(g))
+        assert oracle.strong_components(g) == connected_components(adj, directed=True, connection="strong")[0]
+        assert oracle.weak_components(g) == connected_components(adj, directed=True, connection="weak")[0]
+    # a directed ring is one strong component; a chain that ends in a 2-cycle has one component per
+    # chain node plus the cycle; two separate rings are two of each
+    ring = ((np.arange(9) + 1) % 9).astype(np.uint32)[:, None]
+    assert oracle.strong_components(ring) == 1 and oracle.weak_components(ring) == 1
+    chain = np.array([1, 2, 3, 4, 3], np.uint32)[:, None]           # 0->1->2->3<->4
+    assert oracle.strong_components(chain) == 4 and oracle.weak_components(chain) == 1
+    two = np.array([1, 2, 0, 4, 5, 3], np.uint32)[:, None]
+    assert oracle.strong_components(two) == 2 and oracle.weak_components(two) == 2
+    # a long path does not overflow anything (the recursion is unrolled)
+    n = 200_000
+    path = np.minimum(np.arange(n) + 1, n - 1).astype(np.uint32)[:, None]
+    path[-1, 0] = n - 2
+    assert oracle.strong_components(path) == n - 1
