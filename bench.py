@@ -53,6 +53,21 @@ def algorithmic_bytes(stats: np.ndarray, dim: int, degree: int, k: int) -> dict:
             "iterations_mean": float(stats[:, 0].mean()), "hit_cap": int((stats[:, 3] & 1).sum())}
 
 
+def measured_traffic(workload: str, width: int, itopk: int):
+    """HBM bytes per launch of the search kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE and WRITE_SIZE runs of this same script), if it covers this configuration."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"search_single_{workload}_pmc.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*(\d+)\s*\(search_width (\d+), itopk (\d+)", text)
+    if m and int(m.group(2)) == width and int(m.group(3)) == itopk:
+        return float(m.group(1))
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,7 +85,8 @@ def main() -> int:
     ap.add_argument("--latency-workers", type=int, default=8, help="workgroups per query in the latency part")
     ap.add_argument("--latency-itopk", type=int, default=128)
     ap.add_argument("--traffic-bytes", type=float, default=None,
-                    help="HBM bytes per launch from rocprofv3 counters, copied into roofline.traffic")
+                    help="HBM bytes per launch from rocprofv3 counters for roofline.traffic (default: the value "
+                         "in profiles/search_single_<workload>_pmc.md if it is for the timed configuration)")
     ap.add_argument("--reorder", choices=("rank", "distance"), default="rank",
                     help="edge reordering of the graph optimisation (Sec. III-B.2); rank is CAGRA's")
     ap.add_argument("--no-graph", action="store_true", help="skip the captured-graph replay of the batch-1 call")
@@ -214,14 +230,16 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: N={N} dim={dim} fp32 integer-valued 0..255, B={B}, "
+        "config": {"workload": f"{w.name}: N={N} dim={dim} fp32{' integer-valued 0..255' if w.name == 'sift1m' else ''}, B={B}, "
                                f"degree={w.degree} (init {w.init_degree}), k={w.k}, itopk={M}, "
                                f"search_width={P_WIDTH}, single-workgroup mode",
                    "itopk": M, "search_width": P_WIDTH, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
                    "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
                    "graph_build_s": round(build_s, 2), "reorder": args.reorder},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": args.traffic_bytes,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": args.traffic_bytes if args.traffic_bytes is not None
+                     else measured_traffic(w.name, P_WIDTH, M),
                      "kernel": "search_single_kernel", "kernel_ms": round(dev_ms, 4),
                      "algorithmic_bytes_per_launch": ab["total_bytes"],
                      "gathered_vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
