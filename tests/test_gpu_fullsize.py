@@ -53,16 +53,18 @@ def test_large_batch_workload_at_full_size():
 
     # search: whole batch on the GPU, a sample of it on the oracle (integer data: bit-exact)
     print("  search", flush=True)
-    for itopk in (64, 128):
+    # (search_width, itopk): the point bench.py times (4, 48), and the one-parent search at the same recall
+    for width, itopk in ((4, 48), (1, 128)):
+        print(f"    search_width {width} itopk {itopk}", flush=True)
         opts = cagra.SearchOptions(seed=20230815, mode=1)
-        ids, dists, st = cagra.search(graph, base, queries, w.k, itopk, 1, w.metric, opts, return_stats=True)
+        ids, dists, st = cagra.search(graph, base, queries, w.k, itopk, width, w.metric, opts, return_stats=True)
         ids_np, d_np, st_np = _u32(ids), dists.cpu().numpy(), _u32(st)
         assert not np.any(st_np[:, 3] & 2)
         sample = np.sort(rng.choice(w.queries.shape[0], size=1500, replace=False))
         # the seed generator is keyed by the query's index in the batch, so the oracle gets the
         # batch prefix up to the last sampled query
         upto = int(sample.max()) + 1
-        o_ids, o_d, o_st = oracle.search(graph_np, w.base, w.queries[:upto], w.k, itopk, 1, w.metric,
+        o_ids, o_d, o_st = oracle.search(graph_np, w.base, w.queries[:upto], w.k, itopk, width, w.metric,
                                          seed=20230815, return_stats=True)
         np.testing.assert_array_equal(ids_np[sample], o_ids[sample])
         np.testing.assert_array_equal(d_np[sample], o_d[sample])
@@ -72,3 +74,8 @@ def test_large_batch_workload_at_full_size():
         assert np.all(np.diff(d_np, axis=1) >= 0)
         srt = np.sort(ids_np, axis=1)
         assert np.all(srt[:, 1:] != srt[:, :-1])
+        # the same rows stored as uint8 / fp16 hold the same integers: same answer, bit for bit
+        for code in (cagra.U8, cagra.F16):
+            n_ids, n_d = cagra.search(graph, cagra.convert_dataset(base, code), queries, w.k, itopk, width,
+                                      w.metric, opts)
+            assert torch.equal(n_ids, ids) and torch.equal(n_d, dists)
