@@ -91,6 +91,7 @@ def main() -> int:
                     help="edge reordering of the graph optimisation (Sec. III-B.2); rank is CAGRA's")
     ap.add_argument("--no-graph", action="store_true", help="skip the captured-graph replay of the batch-1 call")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-scaling", action="store_true", help="skip the larger-batch runs")
     ap.add_argument("--no-storage", action="store_true", help="skip the fp16 / uint8 storage part")
     ap.add_argument("--no-reference", action="store_true", help="skip the stream / row-gather bandwidth references")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -248,6 +249,40 @@ def main() -> int:
                      "queries_stopped_by_cap": ab["hit_cap"]},
         "sweep": sweep,
     }
+
+    # ---- the same search on larger batches (the queries repeated; a query's seeds depend on its index
+    #      in the batch, so the copies walk different paths): how much of the 10,000-query time is the
+    #      start and the drain of the batch, during which the device is not full ----------------------
+    if not args.no_scaling:
+        scaling = []
+        for rep in (2, 4, 8):
+            qq = queries.repeat(rep, 1).contiguous()
+            Bq = qq.shape[0]
+            s_ids = torch.empty((Bq, w.k), dtype=torch.int32, device=dev)
+            s_d = torch.empty((Bq, w.k), dtype=torch.float32, device=dev)
+            s_st = torch.zeros((Bq, 4), dtype=torch.int32, device=dev)
+
+            def run_s():
+                return cagra.search(graph, base, qq, w.k, M, P_WIDTH, w.metric, opts, out=(s_ids, s_d),
+                                    workspace=ws, stats=s_st)
+            for _ in range(2):
+                run_s()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                run_s()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            ab_s = algorithmic_bytes(s_st.cpu().numpy().view(np.uint32), dim, w.degree, w.k)
+            scaling.append({"batch": Bq, "kernel_ms": round(ms, 4), "qps_kernel": round(Bq / (ms * 1e-3), 1),
+                            "achieved_GBs": round(ab_s["total_bytes"] / (ms * 1e-3) / 1e9, 1),
+                            "frac_of_hbm_peak": round(ab_s["total_bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+            log(f"[bench] batch {Bq}: {ms:.3f} ms  {scaling[-1]['qps_kernel']:.0f} QPS  {scaling[-1]['achieved_GBs']:.0f} GB/s")
+            del qq, s_ids, s_d, s_st
+        out["batch_scaling"] = {"note": "same index and parameters, the query set repeated 2, 4 and 8 times",
+                                "results": scaling}
 
     # ---- the same search over narrower storage of the same rows (Sec. IV-C.1, last paragraph) ----
     if not args.no_storage:

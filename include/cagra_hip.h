@@ -88,6 +88,11 @@ typedef struct {
                                  list); 0: automatic = 1 if hash_bits or reset_interval is given, else 2.
                                  Results are the same for both; only the number of distances computed twice
                                  differs. */
+    int32_t workgroups_per_cu; /* single mode: persistent single-wavefront workgroups per compute unit; 0 automatic,
+                                 else 1..16 (clipped to what the LDS allows).  More workgroups hide more latency,
+                                 fewer make each query finish sooner, which shortens the start and the end of a
+                                 batch during which the device is not full. */
+    int32_t reserved;
     uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
                                  flags (bit 0: stopped by I_max, bit 1: visited table overflowed) */
 } cagra_search_opts;

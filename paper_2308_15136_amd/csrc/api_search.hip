@@ -89,6 +89,7 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
     //    are given): open addressing.  Between two resets the table receives at most
     //    itopk + interval * n_cand ids; probing in LDS is cheap, so it may fill up to 7/8.
     if (o.table_policy < 0 || o.table_policy > 2) return CAGRA_ERR_BAD_OPTION;
+    if (o.workgroups_per_cu < 0 || o.workgroups_per_cu > 16) return CAGRA_ERR_BAD_OPTION;
     if (o.hash_bits < 0 || o.reset_interval < 0 || o.table_entries < 0) return CAGRA_ERR_BAD_OPTION;
     const bool reset = o.table_policy == 1 || (o.table_policy == 0 && (o.hash_bits != 0 || o.reset_interval != 0));
     if (!reset && (o.hash_bits != 0 || o.reset_interval != 0)) return CAGRA_ERR_BAD_OPTION;
@@ -129,6 +130,14 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
 }
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Persistent single-wavefront workgroups per compute unit: what the LDS allows (at most 16), or fewer on request.
+static int single_per_cu(const cagra_search_opts &o, const SinglePlan &pl, const DeviceInfo &di)
+{
+    int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
+    if (o.workgroups_per_cu > 0) per_cu = std::min(per_cu, (int)o.workgroups_per_cu);
+    return std::max(per_cu, 1);
+}
 
 struct MultiPlan {
     int mr, cr, workers, itopk_local, hash_bits, team_log2, max_iterations;
@@ -260,8 +269,7 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
         out.table_policy = pl.table_policy;
         out.max_iterations = pl.max_iterations; out.wg_per_query = 1; out.itopk_local = itopk;
         out.lds_bytes = (int32_t)pl.smem;
-        int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
-        out.workgroups = (int32_t)std::min<int64_t>(B, (int64_t)std::max(per_cu, 1) * di.cus);
+        out.workgroups = (int32_t)std::min<int64_t>(B, (int64_t)single_per_cu(o, pl, di) * di.cus);
     }
     *plan = out;
     return CAGRA_OK;
@@ -332,9 +340,7 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const void *d
 
     const DeviceInfo &di = device_info();
     // persistent grid: as many single-wavefront workgroups as fit (LDS-bound, at most 16 per CU)
-    int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
-    if (per_cu < 1) per_cu = 1;
-    int grid = (int)std::min<int64_t>(B, (int64_t)per_cu * di.cus);
+    int grid = (int)std::min<int64_t>(B, (int64_t)single_per_cu(o, pl, di) * di.cus);
     hipError_t e = o.dataset_type == CAGRA_F32   ? launch_search_single_f32(P, pl.mr, pl.cr, grid, pl.smem, stream)
                    : o.dataset_type == CAGRA_F16 ? launch_search_single_f16(P, pl.mr, pl.cr, grid, pl.smem, stream)
                                                  : launch_search_single_u8(P, pl.mr, pl.cr, grid, pl.smem, stream);
