@@ -89,6 +89,7 @@ def main() -> int:
                          "in profiles/search_single_<workload>_pmc.md if it is for the timed configuration)")
     ap.add_argument("--reorder", choices=("rank", "distance"), default="rank",
                     help="edge reordering of the graph optimisation (Sec. III-B.2); rank is CAGRA's")
+    ap.add_argument("--no-graph-report", action="store_true", help="skip the 2-hop / connected-component report")
     ap.add_argument("--no-graph", action="store_true", help="skip the captured-graph replay of the batch-1 call")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-scaling", action="store_true", help="skip the larger-batch runs")
@@ -147,6 +148,18 @@ def main() -> int:
         del knn, knn_d
     build_s = time.time() - t0
     log(f"[bench] graph built on the GPU in {build_s:.1f}s")
+
+    # reachability of the graph as the paper measures it (Sec. III-A)
+    graph_quality = None
+    if not args.no_graph_report and w.degree <= 64:
+        t0 = time.time()
+        two_hop = cagra.two_hop_counts(graph).to(torch.float64)
+        strong, weak = cagra.count_components(graph)
+        graph_quality = {"mean_two_hop_count": round(float(two_hop.mean().item()), 1),
+                         "max_possible": w.degree + w.degree * w.degree,
+                         "strong_components": strong, "weak_components": weak}
+        log(f"[bench] graph: mean 2-hop count {graph_quality['mean_two_hop_count']} of {graph_quality['max_possible']}, "
+            f"{strong} strong / {weak} weak components ({time.time() - t0:.1f}s)")
 
     t0 = time.time()
     gt = cagra.exact_search(base, queries, w.k, w.metric, return_dists=False)
@@ -236,7 +249,7 @@ def main() -> int:
                                f"search_width={P_WIDTH}, single-workgroup mode",
                    "itopk": M, "search_width": P_WIDTH, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
                    "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
-                   "graph_build_s": round(build_s, 2), "reorder": args.reorder},
+                   "graph_build_s": round(build_s, 2), "reorder": args.reorder, "graph_quality": graph_quality},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None

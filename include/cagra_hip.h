@@ -230,6 +230,18 @@ int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cag
 size_t cagra_build_ex_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree,
                                       cagra_reorder reorder);
 
+/* ---- reachability measures of a graph (Sec. III-A) ------------------------------------------ */
+
+/* 2-hop node count of every node: counts_out[N] (device) = number of nodes other than X that X reaches
+ * in one or two steps (at most degree + degree^2).  degree <= 64. */
+int cagra_two_hop_counts(const uint32_t *graph, int64_t N, int32_t degree, uint32_t *counts_out, void *hip_stream);
+
+/* Numbers of strongly / weakly connected components of the graph.  HOST function on a HOST copy of the
+ * graph (graph_host[N, degree], ids < N): a sequential traversal, nothing is launched.  Either output may
+ * be NULL.  CAGRA_ERR_WORKSPACE if host memory runs out, CAGRA_ERR_BAD_SHAPE for an id >= N. */
+int cagra_count_components(const uint32_t *graph_host, int64_t N, int32_t degree,
+                           int64_t *strong_out /* host */, int64_t *weak_out /* host */);
+
 /* ---- dataset storage ------------------------------------------------------------------------- */
 
 /* fp32 rows -> fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255).

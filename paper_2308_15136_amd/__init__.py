@@ -96,6 +96,10 @@ def load_library():
     lib.cagra_build_ex.argtypes = [vp, i64, i32, i64, C.c_int, i32, i32, C.c_int, vp, vp, sz, vp]
     lib.cagra_build_ex_workspace_bytes.restype = sz
     lib.cagra_build_ex_workspace_bytes.argtypes = [i64, i32, i32, i32, C.c_int]
+    lib.cagra_two_hop_counts.restype = C.c_int
+    lib.cagra_two_hop_counts.argtypes = [vp, i64, i32, vp, vp]
+    lib.cagra_count_components.restype = C.c_int
+    lib.cagra_count_components.argtypes = [vp, i64, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.cagra_probe_bandwidth.restype = C.c_int
     lib.cagra_probe_bandwidth.argtypes = [vp, i64, i64, i64, i32, i64, i32, i32, i32, C.c_uint64, vp, vp]
     _lib = lib
@@ -142,6 +146,28 @@ def convert_dataset(dataset, dtype: int):
                                                 dataset.stride(0), dtype, out.data_ptr(), out.stride(0),
                                                 _stream(dataset.device)), "cagra_convert_dataset")
     return out
+
+
+def two_hop_counts(graph):
+    """Sec. III-A: per node, the number of other nodes reachable in one or two steps (int32 device tensor)."""
+    torch = _torch()
+    graph = _dev_i32(graph, "graph")
+    out = torch.empty((graph.shape[0],), dtype=torch.int32, device=graph.device)
+    _check(load_library().cagra_two_hop_counts(graph.data_ptr(), graph.shape[0], graph.shape[1], out.data_ptr(),
+                                               _stream(graph.device)), "cagra_two_hop_counts")
+    return out
+
+
+def count_components(graph) -> Tuple[int, int]:
+    """(strong, weak) connected component counts of the graph; runs on the host on a copy of the graph."""
+    torch = _torch()
+    g = graph.detach().to("cpu").contiguous() if isinstance(graph, torch.Tensor) else torch.as_tensor(graph)
+    if g.dtype != torch.int32 or g.dim() != 2:
+        raise TypeError("graph must be a 2-D int32 tensor")
+    strong, weak = C.c_int64(0), C.c_int64(0)
+    _check(load_library().cagra_count_components(g.data_ptr(), g.shape[0], g.shape[1], C.byref(strong),
+                                                 C.byref(weak)), "cagra_count_components")
+    return int(strong.value), int(weak.value)
 
 
 def probe_bandwidth(data, pattern: int, n_read: int = 0, team_size: int = 0, rows_in_flight: int = 0,
