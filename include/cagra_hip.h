@@ -221,14 +221,42 @@ int cagra_optimize_ex(const uint32_t *knn, const float *knn_dists, int64_t N, in
                       uint32_t *reversed_len_out /* may be NULL */,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* cagra_build with the reordering chosen (the distance table lives in the workspace). */
+/*
+ * Initial graph by NN-descent (Sec. III-B.1 names it; the details are this library's): synchronous
+ * rounds in which every node pulls candidates, so the result does not depend on the order of
+ * processing.  Round 0: the k best of k pseudo-random nodes (the generator of the search's step 0
+ * on (seed, node, slot)).  Round t: F(x) = the first `sample` entries of x's list, R(x) = up to
+ * `sample` nodes y with x in F(y), ordered by (rank of x in F(y), y); the new list of x is the k best
+ * of its old list and all entries of the lists of F(x) and R(x), x left out.
+ * knn_out[N, k], dists_out[N, k]: rows ascending by (distance, id); unused slots
+ * (CAGRA_INVALID_ID, FLT_MAX).  rounds: number of rounds after round 0, < 0 automatic
+ * (about log2(N) / 2 + 5); sample: 1..min(64, k), 0 automatic (32).  1 <= k <= 512, k < N.
+ */
+int cagra_nn_descent(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                     int32_t k, int32_t rounds, int32_t sample, uint64_t seed,
+                     uint32_t *knn_out, float *dists_out,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t cagra_nn_descent_workspace_bytes(int64_t N, int32_t k, int32_t sample);
+
+/* Choices of the whole build.  A zero-initialised struct is cagra_build. */
+typedef struct {
+    int32_t reorder;        /* a cagra_reorder */
+    int32_t initial_graph;  /* 0: exact k-NN graph (exhaustive search); 1: NN-descent */
+    int32_t nnd_rounds;     /* NN-descent: rounds, 0 or < 0 automatic */
+    int32_t nnd_sample;     /* NN-descent: sample, 0 automatic */
+    uint64_t seed;          /* NN-descent: seed of round 0 */
+} cagra_build_opts;
+
+/* cagra_build with choices (opts may be NULL).  The initial graph, and for the distance-based
+ * reordering its distances, live in the workspace. */
 int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
-                   int32_t degree, int32_t init_degree, cagra_reorder reorder,
+                   int32_t degree, int32_t init_degree, const cagra_build_opts *opts /* host */,
                    uint32_t *graph_out /* [N, degree] */,
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 size_t cagra_build_ex_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree,
-                                      cagra_reorder reorder);
+                                      const cagra_build_opts *opts /* host */);
 
 /* ---- reachability measures of a graph (Sec. III-A) ------------------------------------------ */
 

@@ -53,6 +53,7 @@ def _load():
         lib.oracle_detour_count_distance.argtypes = [u32p, f32p, i64, i32, i64p, i64, u32p]
         lib.oracle_optimize_ex.argtypes = [u32p, f32p, i64, i32, i32, u32p]
         lib.oracle_build_ex.argtypes = [f32p, i64, i32, i32, i32, i32, i32, u32p]
+        lib.oracle_nn_descent.argtypes = [f32p, i64, i32, i32, i32, i32, i32, u64, u32p, f32p]
         lib.oracle_two_hop_counts.argtypes = [u32p, i64, i32, u32p]
         lib.oracle_strong_components.restype = i64
         lib.oracle_strong_components.argtypes = [u32p, i64, i32]
@@ -135,6 +136,17 @@ def knn_graph(base, d_init: int, metric: int = L2, rows=None, return_dists: bool
     _check(_load().oracle_knn_graph(_p(base, C.c_float), N, dim, metric, _p(rows_a, C.c_int64), n,
                                     d_init, _p(g0, C.c_uint32), _p(gd, C.c_float)), "knn_graph")
     return (g0, gd) if return_dists else g0
+
+
+def nn_descent(base, k: int, rounds: int, sample: int, metric: int = L2, seed: int = 0):
+    """Approximate k-NN graph by NN-descent in synchronous rounds: (ids[N, k], dists[N, k]), rows sorted."""
+    base = _f32(base)
+    N = base.shape[0]
+    ids = np.empty((N, k), np.uint32)
+    dists = np.empty((N, k), np.float32)
+    _check(_load().oracle_nn_descent(_p(base, C.c_float), N, base.shape[1], metric, k, rounds, sample, seed,
+                                     _p(ids, C.c_uint32), _p(dists, C.c_float)), "nn_descent")
+    return ids, dists
 
 
 def detour_count(g0, rows=None):

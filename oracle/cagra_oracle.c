@@ -8,7 +8,8 @@
  * Everything follows the paper's own order of steps:
  *   - k-NNS definition and recall:                Sec. II-A, Eq. 1, Eq. 2
  *   - reachability measures (2-hop count, CC):     Sec. III-A
- *   - initial k-NN graph, rows sorted by distance: Sec. III-B.1
+ *   - initial k-NN graph, rows sorted by distance: Sec. III-B.1 (exact, or NN-descent in
+ *                                                  synchronous rounds)
  *   - rank-based detour count, reorder, prune:     Sec. III-B.2, Eq. 3
  *   - distance-based detour count (the variant the paper compares with):
  *                                                  Sec. III-B.2, Eq. 3 with distances
@@ -165,6 +166,121 @@ int oracle_knn_graph(const float *X, int64_t N, int32_t dim, int32_t metric,
 {
     if (d_init >= N) return -1;
     return exact_topk(X, N, dim, metric, X, rows, rows ? n_rows : N, d_init, 1, g0, g0_dist);
+}
+
+/* ---- Sec. III-B.1 with NN-descent instead of exact neighbours ------------------ */
+/* The paper builds the initial graph with NN-descent (Dong et al., 2011) and
+ * gives no details.  Reading taken here (listed in the design notes): the
+ * algorithm's principle -- a neighbour of a neighbour is likely a neighbour --
+ * in synchronous rounds, every node pulling candidates, so that the result
+ * does not depend on the order in which nodes are processed:
+ *   round 0   L_0(x) = the k best of k pseudo-random nodes (slot j of node x is
+ *             the step-0 generator of the search applied to (seed, x, j));
+ *   round t   F(x) = the first s entries of L_{t-1}(x) (its s closest),
+ *             R(x) = up to s nodes y with x in F(y), ordered by (rank of x in
+ *                    F(y), y)  (reverse neighbours matter: a node nobody
+ *                    lists would never be proposed to anyone),
+ *             L_t(x) = the k best under T of L_{t-1}(x) and every entry of
+ *                    L_{t-1}(v), v in F(x) then R(x), each node once, x left out.
+ * Distances are the canonical fp32 ones; those of kept entries are carried. */
+int oracle_nn_descent(const float *X, int64_t N, int32_t dim, int32_t metric, int32_t k,
+                      int32_t rounds, int32_t s, uint64_t seed, uint32_t *ids, float *dists);
+
+uint32_t oracle_seed_id(uint64_t seed, uint64_t query, uint64_t slot, uint64_t N);
+
+/* k best under T of the entries in e[0..n) with repeated ids and the node `self` dropped;
+ * unused slots become dummies */
+static void keep_k_best(entry_t *e, int n, int k, uint32_t self, uint32_t *out_id, float *out_d)
+{
+    qsort(e, (size_t)n, sizeof(entry_t), entry_cmp);
+    int m = 0;
+    for (int i = 0; i < n && m < k; ++i) {
+        if (e[i].id == ORACLE_INVALID_ID || e[i].id == self) continue;
+        int dup = 0;
+        for (int j = 0; j < m; ++j) dup |= (out_id[j] == e[i].id);   /* same node, same distance: adjacent anyway */
+        if (dup) continue;
+        out_id[m] = e[i].id;
+        out_d[m] = e[i].dist;
+        ++m;
+    }
+    for (; m < k; ++m) { out_id[m] = ORACLE_INVALID_ID; out_d[m] = FLT_MAX; }
+}
+
+int oracle_nn_descent(const float *X, int64_t N, int32_t dim, int32_t metric, int32_t k,
+                      int32_t rounds, int32_t s, uint64_t seed, uint32_t *ids, float *dists)
+{
+    if (!X || !ids || !dists || N < 2 || k < 1 || k >= N || rounds < 0 || s < 1 || s > k) return -1;
+    uint32_t *prev_id = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * k);
+    float *prev_d = (float *)malloc(sizeof(float) * (size_t)N * k);
+    uint32_t *rev = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * s);
+    uint32_t *rev_len = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);
+    if (!prev_id || !prev_d || !rev || !rev_len) { free(prev_id); free(prev_d); free(rev); free(rev_len); return -2; }
+    /* round 0 */
+#pragma omp parallel
+    {
+        entry_t *e = (entry_t *)malloc(sizeof(entry_t) * (size_t)k);
+#pragma omp for schedule(static)
+        for (int64_t x = 0; x < N; ++x) {
+            for (int j = 0; j < k; ++j) {
+                uint32_t c = oracle_seed_id(seed, (uint64_t)x, (uint64_t)j, (uint64_t)N);
+                e[j].id = c; e[j].parent = 0;
+                e[j].dist = c == (uint32_t)x ? FLT_MAX : oracle_dist(X + (size_t)x * dim, X + (size_t)c * dim, dim, metric);
+            }
+            keep_k_best(e, k, k, (uint32_t)x, ids + (size_t)x * k, dists + (size_t)x * k);
+        }
+        free(e);
+    }
+    for (int t = 1; t <= rounds; ++t) {
+        memcpy(prev_id, ids, sizeof(uint32_t) * (size_t)N * k);
+        memcpy(prev_d, dists, sizeof(float) * (size_t)N * k);
+        /* reverse sample: sources in order of (rank, source id), at most s per node */
+        memset(rev_len, 0, sizeof(uint32_t) * (size_t)N);
+        for (int r = 0; r < s; ++r)
+            for (int64_t y = 0; y < N; ++y) {
+                uint32_t x = prev_id[(size_t)y * k + r];
+                if (x != ORACLE_INVALID_ID && rev_len[x] < (uint32_t)s) rev[(size_t)x * s + rev_len[x]++] = (uint32_t)y;
+            }
+#pragma omp parallel
+        {
+            const int cap = k + 2 * s * k;
+            entry_t *e = (entry_t *)malloc(sizeof(entry_t) * (size_t)cap);
+            uint8_t *seen = (uint8_t *)calloc((size_t)N, 1);
+#pragma omp for schedule(dynamic, 64)
+            for (int64_t x = 0; x < N; ++x) {
+                int n = 0;
+                seen[x] = 1;
+                for (int j = 0; j < k; ++j) {
+                    uint32_t c = prev_id[(size_t)x * k + j];
+                    e[n].id = c; e[n].dist = prev_d[(size_t)x * k + j]; e[n].parent = 0; ++n;
+                    if (c != ORACLE_INVALID_ID) seen[c] = 1;
+                }
+                const int n_own = n;
+                for (int pass = 0; pass < 2; ++pass) {
+                    const int np = pass == 0 ? s : (int)rev_len[x];
+                    for (int i = 0; i < np; ++i) {
+                        uint32_t v = pass == 0 ? prev_id[(size_t)x * k + i] : rev[(size_t)x * s + i];
+                        if (v == ORACLE_INVALID_ID) continue;
+                        for (int j = 0; j < k; ++j) {
+                            uint32_t c = prev_id[(size_t)v * k + j];
+                            if (c == ORACLE_INVALID_ID || seen[c]) continue;
+                            seen[c] = 1;
+                            e[n].id = c; e[n].parent = 0;
+                            e[n].dist = oracle_dist(X + (size_t)x * dim, X + (size_t)c * dim, dim, metric);
+                            ++n;
+                        }
+                    }
+                }
+                seen[x] = 0;
+                for (int i = 0; i < n; ++i) if (e[i].id != ORACLE_INVALID_ID) seen[e[i].id] = 0;
+                (void)n_own;
+                keep_k_best(e, n, k, (uint32_t)x, ids + (size_t)x * k, dists + (size_t)x * k);
+            }
+            free(e);
+            free(seen);
+        }
+    }
+    free(prev_id); free(prev_d); free(rev); free(rev_len);
+    return 0;
 }
 
 /* ---- Sec. III-B.2, Eq. 3 with ranks as weights ------------------------------ */

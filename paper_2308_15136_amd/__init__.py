@@ -45,6 +45,11 @@ class _SearchOpts(C.Structure):
                 ("stats", C.c_void_p)]
 
 
+class _BuildOpts(C.Structure):
+    _fields_ = [("reorder", C.c_int32), ("initial_graph", C.c_int32), ("nnd_rounds", C.c_int32),
+                ("nnd_sample", C.c_int32), ("seed", C.c_uint64)]
+
+
 class _SearchPlan(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("mode", "team_size", "table_entries", "reset_interval",
                                          "max_iterations", "wg_per_query", "itopk_local", "lds_bytes",
@@ -92,10 +97,15 @@ def load_library():
     lib.cagra_optimize_workspace_bytes.argtypes = [i64, i32, i32]
     lib.cagra_optimize_ex.restype = C.c_int
     lib.cagra_optimize_ex.argtypes = [vp, vp, i64, i32, i32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
+    bopts_p = C.POINTER(_BuildOpts)
     lib.cagra_build_ex.restype = C.c_int
-    lib.cagra_build_ex.argtypes = [vp, i64, i32, i64, C.c_int, i32, i32, C.c_int, vp, vp, sz, vp]
+    lib.cagra_build_ex.argtypes = [vp, i64, i32, i64, C.c_int, i32, i32, bopts_p, vp, vp, sz, vp]
     lib.cagra_build_ex_workspace_bytes.restype = sz
-    lib.cagra_build_ex_workspace_bytes.argtypes = [i64, i32, i32, i32, C.c_int]
+    lib.cagra_build_ex_workspace_bytes.argtypes = [i64, i32, i32, i32, bopts_p]
+    lib.cagra_nn_descent.restype = C.c_int
+    lib.cagra_nn_descent.argtypes = [vp, i64, i32, i64, C.c_int, i32, i32, i32, C.c_uint64, vp, vp, vp, sz, vp]
+    lib.cagra_nn_descent_workspace_bytes.restype = sz
+    lib.cagra_nn_descent_workspace_bytes.argtypes = [i64, i32, i32]
     lib.cagra_two_hop_counts.restype = C.c_int
     lib.cagra_two_hop_counts.argtypes = [vp, i64, i32, vp, vp]
     lib.cagra_count_components.restype = C.c_int
@@ -306,19 +316,39 @@ def exact_search(dataset, queries, k: int, metric: int = L2, exclude_self: bool 
     return (ids, dists) if return_dists else ids
 
 
-def build(dataset, degree: int, init_degree: int = 0, metric: int = L2, reorder: int = REORDER_RANK):
-    """dataset[N, dim] -> CAGRA graph[N, degree] (int32 tensor)."""
+def build(dataset, degree: int, init_degree: int = 0, metric: int = L2, reorder: int = REORDER_RANK,
+          nn_descent: bool = False, nnd_rounds: int = 0, nnd_sample: int = 0, seed: int = 0):
+    """dataset[N, dim] -> CAGRA graph[N, degree] (int32 tensor).  nn_descent: initial graph by
+    NN-descent instead of the exhaustive search."""
     torch = _torch()
     lib = load_library()
     dataset = _dev_f32(dataset, "dataset")
     dev = dataset.device
     N, dim = dataset.shape
     graph = torch.empty((N, degree), dtype=torch.int32, device=dev)
-    ws = _workspace(lib.cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, reorder), dev)
-    rc = lib.cagra_build_ex(dataset.data_ptr(), N, dim, dataset.stride(0), metric, degree, init_degree, reorder,
+    bo = _BuildOpts(reorder, 1 if nn_descent else 0, nnd_rounds, nnd_sample, seed)
+    ws = _workspace(lib.cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, C.byref(bo)), dev)
+    rc = lib.cagra_build_ex(dataset.data_ptr(), N, dim, dataset.stride(0), metric, degree, init_degree, C.byref(bo),
                             graph.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev))
     _check(rc, "cagra_build_ex")
     return graph
+
+
+def nn_descent(dataset, k: int, rounds: int = -1, sample: int = 0, metric: int = L2, seed: int = 0):
+    """Approximate k-NN graph by NN-descent in synchronous rounds: (ids[N, k] int32, dists[N, k]),
+    rows sorted by (distance, id).  rounds < 0: automatic; rounds = 0: only the random initial lists."""
+    torch = _torch()
+    lib = load_library()
+    dataset = _dev_f32(dataset, "dataset")
+    dev = dataset.device
+    N, dim = dataset.shape
+    ids = torch.empty((N, k), dtype=torch.int32, device=dev)
+    dists = torch.empty((N, k), dtype=torch.float32, device=dev)
+    ws = _workspace(lib.cagra_nn_descent_workspace_bytes(N, k, sample), dev)
+    rc = lib.cagra_nn_descent(dataset.data_ptr(), N, dim, dataset.stride(0), metric, k, rounds, sample, seed,
+                              ids.data_ptr(), dists.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev))
+    _check(rc, "cagra_nn_descent")
+    return ids, dists
 
 
 def optimize(knn, degree: int, return_stages: bool = False, knn_dists=None):

@@ -146,37 +146,49 @@ int cagra_optimize_ex(const uint32_t *knn, const float *knn_dists, int64_t N, in
 
 size_t cagra_build_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree)
 {
-    return cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, CAGRA_REORDER_RANK);
+    return cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, nullptr);
+}
+
+static int nnd_sample_of(const cagra_build_opts &o, int init_degree)
+{
+    return o.nnd_sample == 0 ? std::min(32, init_degree) : o.nnd_sample;
 }
 
 size_t cagra_build_ex_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree,
-                                      cagra_reorder reorder)
+                                      const cagra_build_opts *opts)
 {
     (void)dim;
+    cagra_build_opts o = {};
+    if (opts) o = *opts;
     if (init_degree == 0) init_degree = 2 * degree;
-    if (N < 1 || degree < 1) return 256;
-    // the k-NN graph, for the distance-based reordering also its distances
-    const size_t knn = up256((size_t)N * init_degree * sizeof(uint32_t)) *
-                       (reorder == CAGRA_REORDER_DISTANCE ? 2 : 1);
-    // the distance block is dead once the k-NN graph exists, so the optimisation reuses its space
-    return knn + std::max(cagra_exact_search_workspace_bytes(N, N, init_degree),
-                          cagra_optimize_workspace_bytes(N, init_degree, degree));
+    if (N < 2 || degree < 1) return 256;
+    // the k-NN graph; its distances for NN-descent (which produces them) or the distance-based reordering
+    const bool dists = o.initial_graph == 1 || o.reorder == CAGRA_REORDER_DISTANCE;
+    const size_t knn = up256((size_t)N * init_degree * sizeof(uint32_t)) * (dists ? 2 : 1);
+    // the scratch of the first stage is dead once the k-NN graph exists, so the optimisation reuses its space
+    const size_t first = o.initial_graph == 1
+                             ? nn_descent_workspace_bytes(N, init_degree, nnd_sample_of(o, init_degree))
+                             : cagra_exact_search_workspace_bytes(N, N, init_degree);
+    return knn + std::max(first, cagra_optimize_workspace_bytes(N, init_degree, degree));
 }
 
 int cagra_build(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
                 int32_t degree, int32_t init_degree, uint32_t *graph_out, void *workspace,
                 size_t workspace_bytes, void *hip_stream)
 {
-    return cagra_build_ex(dataset, N, dim, ld, metric, degree, init_degree, CAGRA_REORDER_RANK, graph_out,
-                          workspace, workspace_bytes, hip_stream);
+    return cagra_build_ex(dataset, N, dim, ld, metric, degree, init_degree, nullptr, graph_out, workspace,
+                          workspace_bytes, hip_stream);
 }
 
 int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
-                   int32_t degree, int32_t init_degree, cagra_reorder reorder, uint32_t *graph_out,
+                   int32_t degree, int32_t init_degree, const cagra_build_opts *opts, uint32_t *graph_out,
                    void *workspace, size_t workspace_bytes, void *hip_stream)
 {
+    cagra_build_opts o = {};
+    if (opts) o = *opts;
     if (init_degree == 0) init_degree = 2 * degree;
-    if (reorder != CAGRA_REORDER_RANK && reorder != CAGRA_REORDER_DISTANCE) return CAGRA_ERR_BAD_OPTION;
+    if (o.reorder != CAGRA_REORDER_RANK && o.reorder != CAGRA_REORDER_DISTANCE) return CAGRA_ERR_BAD_OPTION;
+    if (o.initial_graph != 0 && o.initial_graph != 1) return CAGRA_ERR_BAD_OPTION;
     if (!dataset || !graph_out) return CAGRA_ERR_NULL_POINTER;
     if (N < 2) return CAGRA_ERR_BAD_SHAPE;
     int rc = check_matrix(dataset, N, dim, ld);
@@ -184,24 +196,34 @@ int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cag
     if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
     rc = check_degrees(N, degree, init_degree);
     if (rc != CAGRA_OK) return rc;
+    const int sample = nnd_sample_of(o, init_degree);
+    if (o.initial_graph == 1 && (sample < 1 || sample > 64 || sample > init_degree || o.nnd_rounds > 1000))
+        return CAGRA_ERR_BAD_OPTION;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
-        workspace_bytes < cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, reorder))
+        workspace_bytes < cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, &o))
         return CAGRA_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const size_t knn_bytes = up256((size_t)N * init_degree * sizeof(uint32_t));
     uint32_t *knn = static_cast<uint32_t *>(workspace);
     unsigned char *rest = static_cast<unsigned char *>(workspace) + knn_bytes;
     float *knn_dists = nullptr;
-    if (reorder == CAGRA_REORDER_DISTANCE) {
+    if (o.initial_graph == 1 || o.reorder == CAGRA_REORDER_DISTANCE) {
         knn_dists = reinterpret_cast<float *>(rest);
         rest += knn_bytes;
     }
-    hipError_t e = launch_exact_search(dataset, N, dim, ld, (int)metric, dataset, N, ld, init_degree, 1, 0,
-                                       knn, knn_dists, reinterpret_cast<float *>(rest),
-                                       exact_block_rows(N, N), stream);
+    hipError_t e;
+    if (o.initial_graph == 1) {
+        const int rounds = o.nnd_rounds <= 0 ? nn_descent_auto_rounds(N) : o.nnd_rounds;
+        e = launch_nn_descent(dataset, N, dim, ld, (int)metric, init_degree, rounds, sample, o.seed, knn, knn_dists,
+                              rest, stream);
+    } else {
+        e = launch_exact_search(dataset, N, dim, ld, (int)metric, dataset, N, ld, init_degree, 1, 0,
+                                knn, knn_dists, reinterpret_cast<float *>(rest), exact_block_rows(N, N), stream);
+    }
     if (e != hipSuccess) return CAGRA_ERR_LAUNCH;
     OptimizeCarve c = carve_optimize(rest, N, degree);
-    e = launch_optimize(knn, knn_dists, N, init_degree, degree, graph_out, c.pruned, c.rev, c.rev_len, c.s, stream);
+    e = launch_optimize(knn, o.reorder == CAGRA_REORDER_DISTANCE ? knn_dists : nullptr, N, init_degree, degree,
+                        graph_out, c.pruned, c.rev, c.rev_len, c.s, stream);
     return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
 }
 

@@ -92,10 +92,15 @@ __global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t v)
     if (i < n) p[i] = v;
 }
 
-__global__ void indegree_kernel(const uint32_t *__restrict__ pruned, int64_t n_edges, uint32_t *indeg)
+// The graph whose edges are reversed is the first d entries of rows that are ld entries apart;
+// entries that are not node ids (unused slots) are skipped.
+__global__ void indegree_kernel(const uint32_t *__restrict__ g, int64_t N, int d, int64_t ld, uint32_t *indeg)
 {
     int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < n_edges) atomicAdd(&indeg[pruned[e]], 1u);
+    if (e >= N * d) return;
+    const int64_t x = e / d;
+    const uint32_t y = g[x * ld + (e - x * d)];
+    if ((int64_t)y < N) atomicAdd(&indeg[y], 1u);
 }
 
 // Exclusive scan of uint32 counts into uint64 offsets, three passes over blocks of 1024.
@@ -154,14 +159,15 @@ __global__ void scan_add_kernel(uint64_t *out, int64_t n, const uint64_t *__rest
     if (i < n) out[i] += block_sum[i >> 10];
 }
 
-__global__ void bucket_fill_kernel(const uint32_t *__restrict__ pruned, int64_t N, int d,
+__global__ void bucket_fill_kernel(const uint32_t *__restrict__ g, int64_t N, int d, int64_t ld,
                                    const uint64_t *__restrict__ offset, uint32_t *cursor,
                                    uint64_t *__restrict__ bucket)
 {
     int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= N * d) return;
     const uint32_t x = (uint32_t)(e / d), r = (uint32_t)(e - (int64_t)x * d);
-    const uint32_t y = pruned[e];
+    const uint32_t y = g[(int64_t)x * ld + r];
+    if ((int64_t)y >= N) return;
     const uint32_t pos = atomicAdd(&cursor[y], 1u);
     bucket[offset[y] + pos] = ((uint64_t)r << 32) | x;
 }
@@ -264,21 +270,30 @@ __global__ void merge_kernel(const uint32_t *__restrict__ pruned, const uint32_t
 
 static unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
+// Reversed graph of the first d entries of every row of g (rows ld apart): rev[N, d], rev_len[N].
+hipError_t launch_reverse(const uint32_t *g, int64_t N, int d, int64_t ld, uint32_t *rev, uint32_t *rev_len,
+                          const OptimizeScratch &s, hipStream_t stream)
+{
+    const int64_t n_edges = N * d;
+    const int64_t n_blocks = (N + 1023) / 1024;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.indeg, N, 0u);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.cursor, N, 0u);
+    hipLaunchKernelGGL(indegree_kernel, dim3(blocks_for(n_edges, 256)), dim3(256), 0, stream, g, N, d, ld, s.indeg);
+    hipLaunchKernelGGL(scan_block_kernel, dim3((unsigned)n_blocks), dim3(256), 0, stream, s.indeg, N, s.offset, s.block_sum);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, stream, s.block_sum, n_blocks);
+    hipLaunchKernelGGL(scan_add_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.offset, N, s.block_sum);
+    hipLaunchKernelGGL(bucket_fill_kernel, dim3(blocks_for(n_edges, 256)), dim3(256), 0, stream, g, N, d, ld, s.offset, s.cursor, s.bucket);
+    hipLaunchKernelGGL(reverse_select_kernel, dim3((unsigned)N), dim3(64), 0, stream, s.bucket, s.offset, s.indeg, N, d, rev, rev_len);
+    return hipGetLastError();
+}
+
 hipError_t launch_optimize(const uint32_t *knn, const float *knn_dist, int64_t N, int d_init, int d, uint32_t *graph,
                            uint32_t *pruned, uint32_t *rev, uint32_t *rev_len,
                            const OptimizeScratch &s, hipStream_t stream)
 {
-    const int64_t n_edges = N * d;
-    const int64_t n_blocks = (N + 1023) / 1024;
     hipLaunchKernelGGL(prune_kernel, dim3((unsigned)N), dim3(256), 0, stream, knn, knn_dist, N, d_init, d, pruned);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.indeg, N, 0u);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.cursor, N, 0u);
-    hipLaunchKernelGGL(indegree_kernel, dim3(blocks_for(n_edges, 256)), dim3(256), 0, stream, pruned, n_edges, s.indeg);
-    hipLaunchKernelGGL(scan_block_kernel, dim3((unsigned)n_blocks), dim3(256), 0, stream, s.indeg, N, s.offset, s.block_sum);
-    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, stream, s.block_sum, n_blocks);
-    hipLaunchKernelGGL(scan_add_kernel, dim3(blocks_for(N, 256)), dim3(256), 0, stream, s.offset, N, s.block_sum);
-    hipLaunchKernelGGL(bucket_fill_kernel, dim3(blocks_for(n_edges, 256)), dim3(256), 0, stream, pruned, N, d, s.offset, s.cursor, s.bucket);
-    hipLaunchKernelGGL(reverse_select_kernel, dim3((unsigned)N), dim3(64), 0, stream, s.bucket, s.offset, s.indeg, N, d, rev, rev_len);
+    hipError_t e = launch_reverse(pruned, N, d, d, rev, rev_len, s, stream);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(merge_kernel, dim3(blocks_for(N, 128)), dim3(128), 0, stream, pruned, rev, rev_len, N, d, graph);
     return hipGetLastError();
 }

@@ -177,6 +177,112 @@ __device__ __forceinline__ void drop_duplicates(const uint32_t (&tlo)[MR], uint3
         if (dup & (1u << r)) { chi[r] = kDummyHi; clo[r] = kInvalidId; }
 }
 
+// at most this many winning candidates are inserted one by one; more go through sort + merge
+#ifndef CAGRA_INSERT_LIMIT
+#define CAGRA_INSERT_LIMIT 8
+#endif
+constexpr int kInsertLimit = CAGRA_INSERT_LIMIT;
+
+// Step 1 (Sec. IV-A): the sorted list t of logical length `length` (its registers are padded to a
+// power of two with dummies) takes in the candidates c.  Skipped when no candidate beats the last
+// entry.  With DEDUP (a visited table that may forget) candidates that repeat a list member or each
+// other are dropped first; `lost` / `forgot` are the table's flags (see sets_insert, sets_confirm).
+// scratch_id / scratch_key: 64 * CR words of LDS each, free at this point.
+template <int MR, int CR, bool DEDUP>
+__device__ __forceinline__ void update_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR], uint32_t (&chi)[CR],
+                                            uint32_t (&clo)[CR], int length, bool lost, bool forgot,
+                                            uint32_t *scratch_id, float *scratch_key, int lane)
+{
+    const int last = length - 1;
+    // key of the last logical entry
+    uint32_t whi = kDummyHi, wlo = kInvalidId;
+#pragma unroll
+    for (int r = 0; r < MR; ++r)
+        if (r == (last >> 6)) {
+            whi = __builtin_amdgcn_readlane(thi[r], last & 63);
+            wlo = __builtin_amdgcn_readlane(tlo[r], last & 63);
+        }
+    uint64_t better[CR];
+    int n_better = 0;
+#pragma unroll
+    for (int r = 0; r < CR; ++r) {
+        better[r] = __ballot(key_less(chi[r], clo[r], whi, wlo));
+        n_better += __popcll(better[r]);
+    }
+    if constexpr (DEDUP) {
+        // The table only filters: where it may have let a node through twice, winners are checked
+        // before they enter the list (a node that is measured again has the same key, so only a
+        // winner can be a copy of a list member).
+        if (n_better != 0 && __ballot(lost) != 0ull) {
+            drop_duplicates<MR, CR>(tlo, chi, clo, lane);
+            n_better = 0;
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                better[r] = __ballot(key_less(chi[r], clo[r], whi, wlo));
+                n_better += __popcll(better[r]);
+            }
+        } else if (n_better != 0 && __ballot(forgot) != 0ull) {
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                uint64_t m = better[r];
+                while (m != 0ull) {
+                    const int l = __builtin_ctzll(m);
+                    m &= m - 1;
+                    const uint32_t id = __builtin_amdgcn_readlane(clo[r], l) >> 1;
+                    bool same = false;
+#pragma unroll
+                    for (int t2 = 0; t2 < MR; ++t2) same |= (tlo[t2] >> 1) == id;
+                    if (__ballot(same) != 0ull) {
+                        if (lane == l) { chi[r] = kDummyHi; clo[r] = kInvalidId; }
+                        better[r] &= ~(1ull << l);
+                        --n_better;
+                    }
+                }
+            }
+        }
+    }
+    if (n_better == 0) return;
+    if (n_better <= kInsertLimit) {
+        // few winners (the usual case once the list has settled): one ordered insertion each
+        // instead of the sorting network
+#pragma unroll
+        for (int r = 0; r < CR; ++r) {
+            uint64_t m = better[r];
+            while (m != 0ull) {
+                const int l = __builtin_ctzll(m);
+                m &= m - 1;
+                insert_into_topm<MR>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
+                                     __builtin_amdgcn_readlane(clo[r], l), lane);
+            }
+        }
+    } else if (CR > 1 && n_better <= kWave) {
+        // the winners fit one register: gather them through LDS, sort 64 keys instead of 64 * CR
+        int before = 0;
+#pragma unroll
+        for (int r = 0; r < CR; ++r) {
+            const uint64_t m = better[r];
+            const int pos = before + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                         __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if ((m >> lane) & 1ull) { scratch_id[pos] = clo[r]; scratch_key[pos] = __uint_as_float(chi[r]); }
+            before += __popcll(m);
+        }
+        __syncthreads();
+        uint32_t whi1[1], wlo1[1];
+        whi1[0] = lane < n_better ? __float_as_uint(scratch_key[lane]) : kDummyHi;
+        wlo1[0] = lane < n_better ? scratch_id[lane] : kInvalidId;
+        __syncthreads();
+        bitonic_sort<1>(whi1, wlo1, lane);
+        merge_into_topm<MR, 1>(thi, tlo, whi1, wlo1, lane);
+    } else {
+        bitonic_sort<CR>(chi, clo, lane);
+        merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
+    }
+    // logical length: whatever lies beyond it is padding and stays dummy
+#pragma unroll
+    for (int r = 0; r < MR; ++r)
+        if (r * 64 + lane >= length) { thi[r] = kDummyHi; tlo[r] = kInvalidId; }
+}
+
 // ---- visited table (Sec. IV-B.3) -------------------------------------------------------------
 
 __device__ __forceinline__ uint32_t hash_slot(uint32_t id, int bits)

@@ -30,6 +30,7 @@
 // precision storage relieves the memory-bandwidth limit).
 #include "device_util.h"
 #include "search_device.h"
+#include "team_distance.h"
 #include "search_params.h"
 
 #ifndef CAGRA_ELEM
@@ -39,26 +40,8 @@
 namespace cagra {
 
 constexpr int kElem = CAGRA_ELEM;
-constexpr int kElemsPerPiece = kElem == 0 ? 4 : kElem == 1 ? 8 : 16;   // elements in 16 bytes
+constexpr int kElemsPerPiece = elems_per_piece<kElem>();   // elements in 16 bytes
 constexpr int kElemBytes = 16 / kElemsPerPiece;
-
-// The i-th group of four consecutive elements of a 16-byte piece, widened to fp32.
-__device__ __forceinline__ float4 widen4(const uint4 &p, int i)
-{
-    const uint32_t w[4] = {p.x, p.y, p.z, p.w};
-    if constexpr (kElem == 0) {
-        return make_float4(__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3]));
-    } else if constexpr (kElem == 1) {
-        const uint32_t a = w[2 * i], b = w[2 * i + 1];
-        return make_float4(__half2float(__ushort_as_half((unsigned short)(a & 0xFFFFu))),
-                           __half2float(__ushort_as_half((unsigned short)(a >> 16))),
-                           __half2float(__ushort_as_half((unsigned short)(b & 0xFFFFu))),
-                           __half2float(__ushort_as_half((unsigned short)(b >> 16))));
-    } else {
-        const uint32_t a = w[i];
-        return make_float4((float)(a & 0xFFu), (float)((a >> 8) & 0xFFu), (float)((a >> 16) & 0xFFu), (float)(a >> 24));
-    }
-}
 
 // Multi mode issues the first probe of every candidate before the dataset rows are fetched and
 // looks at its answer afterwards (the row loads do not wait for the table).  `old` is what the
@@ -85,12 +68,6 @@ __device__ __forceinline__ bool visited_resolve_global(uint32_t *table, int bits
 #endif
 constexpr int kRowsInFlight = CAGRA_ROWS_IN_FLIGHT;
 constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, registers do not
-
-// at most this many winning candidates are inserted one by one; more go through sort + merge
-#ifndef CAGRA_INSERT_LIMIT
-#define CAGRA_INSERT_LIMIT 8
-#endif
-constexpr int kInsertLimit = CAGRA_INSERT_LIMIT;
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
@@ -127,12 +104,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 {
     const int lane = lane_id();
     const int team_log2 = P.team_log2;
-    const int team = 1 << team_log2;
-    const int n_teams = kWave >> team_log2;
-    const int g = lane >> team_log2;       // team of this lane
-    const int t = lane & (team - 1);       // lane within the team
     const int n_cand = P.search_width * P.degree;
-    const int nchunk = P.dim / kElemsPerPiece;   // 16-byte pieces per row
     constexpr bool MULTI = KIND == kTableGlobal;
     const int table_words = P.table_words;   // single mode: LDS table
     uint32_t *cursor = table + table_words;  // kTableSets: one byte per set behind the table
@@ -217,65 +189,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         __syncthreads();
         CAGRA_PHASE(1)
 
-        for (int c0 = 0; c0 < n_new; c0 += RIF * n_teams) {
-            // RIF dataset rows per team in flight: all loads of a round are issued before any is used
-            const unsigned char *row[RIF];
-            bool ok[RIF];
-            float acc[RIF];
-#pragma unroll
-            for (int u = 0; u < RIF; ++u) {
-                const int c = c0 + u * n_teams + g;
-                const uint32_t node = c < n_new ? newid[c] : kInvalidId;
-                ok[u] = node != kInvalidId;
-                row[u] = static_cast<const unsigned char *>(P.dataset) + (size_t)(ok[u] ? node : 0u) * P.ld * kElemBytes;
-                acc[u] = 0.f;
-            }
-            for (int base = 0; base < nchunk; base += 4 * team) {
-                uint4 x[RIF][4];
-#pragma unroll
-                for (int u = 0; u < RIF; ++u)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int ch = base + i * team + t;
-                        x[u][i] = (ok[u] && ch < nchunk) ? *reinterpret_cast<const uint4 *>(row[u] + 16 * ch)
-                                                         : make_uint4(0, 0, 0, 0);
-                    }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int ch = base + i * team + t;
-                    if (ch < nchunk) {
-#pragma unroll
-                        for (int h = 0; h < kElemsPerPiece / 4; ++h) {
-                            const float4 qv = *reinterpret_cast<const float4 *>(qlds + kElemsPerPiece * ch + 4 * h);
-                            if (P.metric == 0) {
-#pragma unroll
-                                for (int u = 0; u < RIF; ++u) {
-                                    const float4 xv = widen4(x[u][i], h);
-                                    const float d0 = xv.x - qv.x, d1 = xv.y - qv.y, d2 = xv.z - qv.z, d3 = xv.w - qv.w;
-                                    acc[u] = fmaf(d0, d0, acc[u]); acc[u] = fmaf(d1, d1, acc[u]);
-                                    acc[u] = fmaf(d2, d2, acc[u]); acc[u] = fmaf(d3, d3, acc[u]);
-                                }
-                            } else {
-#pragma unroll
-                                for (int u = 0; u < RIF; ++u) {
-                                    const float4 xv = widen4(x[u][i], h);
-                                    acc[u] = fmaf(xv.x, qv.x, acc[u]); acc[u] = fmaf(xv.y, qv.y, acc[u]);
-                                    acc[u] = fmaf(xv.z, qv.z, acc[u]); acc[u] = fmaf(xv.w, qv.w, acc[u]);
-                                }
-                            }
-                        }
-                    }
-                }
-            }
-            // butterfly over the team's lanes; every lane ends with the same bits
-#pragma unroll
-            for (int u = 0; u < RIF; ++u) acc[u] = team_sum(acc[u], team_log2);
-#pragma unroll
-            for (int u = 0; u < RIF; ++u) {
-                if (P.metric != 0) acc[u] = 0.0f - acc[u];
-                if (t == 0 && ok[u]) newdist[c0 + u * n_teams + g] = acc[u];
-            }
-        }
+        team_distances<kElem, RIF>(P.dataset, P.ld, P.dim, P.metric, team_log2, newid, n_new, qlds, newdist);
         __syncthreads();
         CAGRA_PHASE(2)
 #pragma unroll
@@ -291,98 +205,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         }
 
         // ---- step 1: top-M update (skipped when no candidate can enter) -------------------
-        {
-            const int last = P.itopk - 1;
-            // key of the last logical entry (the list's registers are padded to a power of two)
-            uint32_t whi = kDummyHi, wlo = kInvalidId;
-#pragma unroll
-            for (int r = 0; r < MR; ++r)
-                if (r == (last >> 6)) {
-                    whi = __builtin_amdgcn_readlane(thi[r], last & 63);
-                    wlo = __builtin_amdgcn_readlane(tlo[r], last & 63);
-                }
-            uint64_t better[CR];
-            int n_better = 0;
-#pragma unroll
-            for (int r = 0; r < CR; ++r) {
-                better[r] = __ballot(key_less(chi[r], clo[r], whi, wlo));
-                n_better += __popcll(better[r]);
-            }
-            if constexpr (KIND == kTableSets) {
-                // The table only filters: where it may have let a node through twice, winners are
-                // checked before they enter the list (a node that is measured again has the same key,
-                // so only a winner can be a copy of a list member).
-                if (n_better != 0 && __ballot(lost) != 0ull) {
-                    drop_duplicates<MR, CR>(tlo, chi, clo, lane);
-                    n_better = 0;
-#pragma unroll
-                    for (int r = 0; r < CR; ++r) {
-                        better[r] = __ballot(key_less(chi[r], clo[r], whi, wlo));
-                        n_better += __popcll(better[r]);
-                    }
-                } else if (n_better != 0 && __ballot(forgot) != 0ull) {
-#pragma unroll
-                    for (int r = 0; r < CR; ++r) {
-                        uint64_t m = better[r];
-                        while (m != 0ull) {
-                            const int l = __builtin_ctzll(m);
-                            m &= m - 1;
-                            const uint32_t id = __builtin_amdgcn_readlane(clo[r], l) >> 1;
-                            bool same = false;
-#pragma unroll
-                            for (int t2 = 0; t2 < MR; ++t2) same |= (tlo[t2] >> 1) == id;
-                            if (__ballot(same) != 0ull) {
-                                if (lane == l) { chi[r] = kDummyHi; clo[r] = kInvalidId; }
-                                better[r] &= ~(1ull << l);
-                                --n_better;
-                            }
-                        }
-                    }
-                }
-            }
-            if (n_better != 0) {
-                if (n_better <= kInsertLimit) {
-                    // few winners (the usual case once the list has settled): one ordered
-                    // insertion each instead of the sorting network
-#pragma unroll
-                    for (int r = 0; r < CR; ++r) {
-                        uint64_t m = better[r];
-                        while (m != 0ull) {
-                            const int l = __builtin_ctzll(m);
-                            m &= m - 1;
-                            insert_into_topm<MR>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
-                                                 __builtin_amdgcn_readlane(clo[r], l), lane);
-                        }
-                    }
-                } else if (CR > 1 && n_better <= kWave) {
-                    // the winners fit one register: gather them through LDS (the candidate arrays are
-                    // free until the next pass), sort 64 keys instead of 64 * CR
-                    int before = 0;
-#pragma unroll
-                    for (int r = 0; r < CR; ++r) {
-                        const uint64_t m = better[r];
-                        const int pos = before + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                        if ((m >> lane) & 1ull) { newid[pos] = clo[r]; newdist[pos] = __uint_as_float(chi[r]); }
-                        before += __popcll(m);
-                    }
-                    __syncthreads();
-                    uint32_t whi1[1], wlo1[1];
-                    whi1[0] = lane < n_better ? __float_as_uint(newdist[lane]) : kDummyHi;
-                    wlo1[0] = lane < n_better ? newid[lane] : kInvalidId;
-                    __syncthreads();
-                    bitonic_sort<1>(whi1, wlo1, lane);
-                    merge_into_topm<MR, 1>(thi, tlo, whi1, wlo1, lane);
-                } else {
-                    bitonic_sort<CR>(chi, clo, lane);
-                    merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
-                }
-                // logical length is itopk: whatever lies beyond it is padding and stays dummy
-#pragma unroll
-                for (int r = 0; r < MR; ++r)
-                    if (r * 64 + lane >= P.itopk) { thi[r] = kDummyHi; tlo[r] = kInvalidId; }
-            }
-        }
+        update_topm<MR, CR, KIND == kTableSets>(thi, tlo, chi, clo, P.itopk, lost, forgot, newid, newdist, lane);
         CAGRA_PHASE(3)
         if (it == P.max_iterations) { flags |= 1u; break; }
 

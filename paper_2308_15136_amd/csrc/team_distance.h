@@ -1,0 +1,108 @@
+// Step 3b of the search (Sec. IV-B.1): distances between the query in LDS and a list of dataset
+// rows, one row per team of 4/8/16/32 lanes, 16-byte loads, DPP butterfly reduction.  Shared by
+// the search kernels and the NN-descent rounds of the graph build.
+#pragma once
+#include "device_util.h"
+
+namespace cagra {
+
+// storage types of dataset rows: 0 fp32, 1 fp16, 2 uint8
+template <int ELEM>
+__host__ __device__ constexpr int elems_per_piece() { return ELEM == 0 ? 4 : ELEM == 1 ? 8 : 16; }
+
+// The i-th group of four consecutive elements of a 16-byte piece, widened to fp32.
+template <int ELEM>
+__device__ __forceinline__ float4 widen4(const uint4 &p, int i)
+{
+    const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+    if constexpr (ELEM == 0) {
+        return make_float4(__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3]));
+    } else if constexpr (ELEM == 1) {
+        const uint32_t a = w[2 * i], b = w[2 * i + 1];
+        return make_float4(__half2float(__ushort_as_half((unsigned short)(a & 0xFFFFu))),
+                           __half2float(__ushort_as_half((unsigned short)(a >> 16))),
+                           __half2float(__ushort_as_half((unsigned short)(b & 0xFFFFu))),
+                           __half2float(__ushort_as_half((unsigned short)(b >> 16))));
+    } else {
+        const uint32_t a = w[i];
+        return make_float4((float)(a & 0xFFu), (float)((a >> 8) & 0xFFu), (float)((a >> 16) & 0xFFu), (float)(a >> 24));
+    }
+}
+
+// newdist[c] = distance(query, dataset row newid[c]) for c < n_new (entries equal to kInvalidId are
+// skipped).  Called by all 64 lanes of a wavefront; qlds holds the query as fp32, `ld` is the row
+// stride in elements, RIF the rows each team keeps in flight (all loads of a round are issued
+// before any is used).  metric 0: squared L2, else 0 - <x, q>.
+template <int ELEM, int RIF>
+__device__ __forceinline__ void team_distances(const void *dataset, int64_t ld, int dim, int metric, int team_log2,
+                                               const uint32_t *newid, int n_new, const float *qlds, float *newdist)
+{
+    constexpr int kPiece = elems_per_piece<ELEM>();
+    constexpr int kBytes = 16 / kPiece;
+    const int lane = lane_id();
+    const int team = 1 << team_log2;
+    const int n_teams = kWave >> team_log2;
+    const int g = lane >> team_log2;       // team of this lane
+    const int t = lane & (team - 1);       // lane within the team
+    const int nchunk = dim / kPiece;       // 16-byte pieces per row
+    for (int c0 = 0; c0 < n_new; c0 += RIF * n_teams) {
+        const unsigned char *row[RIF];
+        bool ok[RIF];
+        float acc[RIF];
+#pragma unroll
+        for (int u = 0; u < RIF; ++u) {
+            const int c = c0 + u * n_teams + g;
+            const uint32_t node = c < n_new ? newid[c] : kInvalidId;
+            ok[u] = node != kInvalidId;
+            row[u] = static_cast<const unsigned char *>(dataset) + (size_t)(ok[u] ? node : 0u) * ld * kBytes;
+            acc[u] = 0.f;
+        }
+        for (int base = 0; base < nchunk; base += 4 * team) {
+            uint4 x[RIF][4];
+#pragma unroll
+            for (int u = 0; u < RIF; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int ch = base + i * team + t;
+                    x[u][i] = (ok[u] && ch < nchunk) ? *reinterpret_cast<const uint4 *>(row[u] + 16 * ch)
+                                                     : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ch = base + i * team + t;
+                if (ch < nchunk) {
+#pragma unroll
+                    for (int h = 0; h < kPiece / 4; ++h) {
+                        const float4 qv = *reinterpret_cast<const float4 *>(qlds + kPiece * ch + 4 * h);
+                        if (metric == 0) {
+#pragma unroll
+                            for (int u = 0; u < RIF; ++u) {
+                                const float4 xv = widen4<ELEM>(x[u][i], h);
+                                const float d0 = xv.x - qv.x, d1 = xv.y - qv.y, d2 = xv.z - qv.z, d3 = xv.w - qv.w;
+                                acc[u] = fmaf(d0, d0, acc[u]); acc[u] = fmaf(d1, d1, acc[u]);
+                                acc[u] = fmaf(d2, d2, acc[u]); acc[u] = fmaf(d3, d3, acc[u]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int u = 0; u < RIF; ++u) {
+                                const float4 xv = widen4<ELEM>(x[u][i], h);
+                                acc[u] = fmaf(xv.x, qv.x, acc[u]); acc[u] = fmaf(xv.y, qv.y, acc[u]);
+                                acc[u] = fmaf(xv.z, qv.z, acc[u]); acc[u] = fmaf(xv.w, qv.w, acc[u]);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        // butterfly over the team's lanes; every lane ends with the same bits
+#pragma unroll
+        for (int u = 0; u < RIF; ++u) acc[u] = team_sum(acc[u], team_log2);
+#pragma unroll
+        for (int u = 0; u < RIF; ++u) {
+            if (metric != 0) acc[u] = 0.0f - acc[u];
+            if (t == 0 && ok[u]) newdist[c0 + u * n_teams + g] = acc[u];
+        }
+    }
+}
+
+}  // namespace cagra

@@ -339,3 +339,78 @@ def test_component_counts_against_scipy_and_by_hand():
     path = np.minimum(np.arange(n) + 1, n - 1).astype(np.uint32)[:, None]
     path[-1, 0] = n - 2
     assert oracle.strong_components(path) == n - 1
+
+
+# ---- NN-descent in synchronous rounds (Sec. III-B.1 names NN-descent; the rounds are this build's) --
+
+def _lists_ok(base, ids, dists, metric=oracle.L2):
+    n, k = ids.shape
+    for x in range(0, n, max(1, n // 60)):
+        valid = ids[x] != oracle.INVALID_ID
+        row = ids[x][valid]
+        assert x not in row.tolist() and len(set(row.tolist())) == len(row)
+        assert np.all(valid[: valid.sum()])                                    # unused slots come last
+        keys = list(zip(dists[x][valid].tolist(), row.tolist()))
+        assert keys == sorted(keys)
+        for j in (0, len(row) // 2, len(row) - 1):
+            assert dists[x, j] == oracle.distance(base[x], base[row[j]], metric)
+
+
+def test_nn_descent_round_zero_is_the_best_of_the_drawn_nodes():
+    base = datagen.sift_like(500, 8, 4, seed=2, stream=1)
+    k = 12
+    ids, dists = oracle.nn_descent(base, k, 0, 4, seed=77)
+    b = base.astype(np.float64)
+    for x in (0, 1, 250, 499):
+        drawn = sorted({oracle.seed_id(77, x, j, 500) for j in range(k)} - {x},
+                       key=lambda c: (((b[x] - b[c]) ** 2).sum(), c))
+        assert ids[x][: len(drawn)].tolist() == drawn
+        assert np.all(ids[x][len(drawn):] == oracle.INVALID_ID)
+    _lists_ok(base, ids, dists)
+
+
+def test_nn_descent_one_round_follows_the_stated_rule():
+    # L_t from L_{t-1} re-derived with sets and float64 distances (exact on integer data)
+    n, k, s = 400, 10, 4
+    base = datagen.sift_like(n, 8, 4, seed=3, stream=1)
+    b = base.astype(np.float64)
+    for t in (1, 3):
+        prev, _ = oracle.nn_descent(base, k, t - 1, s, seed=5)
+        cur, _ = oracle.nn_descent(base, k, t, s, seed=5)
+        forward = [[int(v) for v in prev[x][:s] if v != oracle.INVALID_ID] for x in range(n)]
+        reverse = [[] for _ in range(n)]
+        for r in range(s):                       # sources ordered by (rank, source), at most s each
+            for y in range(n):
+                if r < len(prev[y]) and prev[y][r] != oracle.INVALID_ID and len(reverse[prev[y][r]]) < s:
+                    reverse[int(prev[y][r])].append(y)
+        for x in range(0, n, 7):
+            pool = {int(v) for v in prev[x] if v != oracle.INVALID_ID}
+            for v in forward[x] + reverse[x]:
+                pool |= {int(c) for c in prev[v] if c != oracle.INVALID_ID}
+            pool.discard(x)
+            want = sorted(pool, key=lambda c: (((b[x] - b[c]) ** 2).sum(), c))[:k]
+            assert cur[x][: len(want)].tolist() == want
+
+
+def test_nn_descent_improves_monotonically_and_converges():
+    w = datagen.workload("tiny", n=3000, n_queries=1)
+    k, s = 16, 8
+    exact = oracle.knn_graph(w.base, k)
+    last_kth, recalls = None, []
+    for t in (0, 1, 2, 4, 8):
+        ids, dists = oracle.nn_descent(w.base, k, t, s, seed=1)
+        _lists_ok(w.base, ids, dists)
+        if last_kth is not None:
+            assert np.all(dists[:, -1] <= last_kth)          # a list only ever gets better
+        last_kth = dists[:, -1].copy()
+        recalls.append(np.mean([len(set(a.tolist()) & set(e.tolist())) for a, e in zip(ids, exact)]) / k)
+    assert recalls == sorted(recalls) and recalls[0] < 0.05 and recalls[-1] > 0.9
+    # with everything sampled on a small set the lists become the exact ones
+    base = datagen.sift_like(60, 8, 2, seed=4, stream=1)
+    ids, _ = oracle.nn_descent(base, 20, 6, 20, seed=9)
+    np.testing.assert_array_equal(ids, oracle.knn_graph(base, 20))
+    # the exact lists are a fixed point of a round: feeding them back changes nothing is implied by
+    # "a list only gets better" + optimality; inner product works the same way
+    wg = datagen.workload("glove200", n=800, n_queries=1)
+    ids, dists = oracle.nn_descent(wg.base, 8, 5, 8, metric=oracle.IP, seed=2)
+    _lists_ok(wg.base, ids, dists, oracle.IP)
