@@ -87,6 +87,8 @@ def main() -> int:
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from rocprofv3 counters for roofline.traffic (default: the value "
                          "in profiles/search_single_<workload>_pmc.md if it is for the timed configuration)")
+    ap.add_argument("--initial-graph", choices=("exact", "nn-descent"), default="exact",
+                    help="initial k-NN graph of the build (Sec. III-B.1): exhaustive search or NN-descent")
     ap.add_argument("--reorder", choices=("rank", "distance"), default="rank",
                     help="edge reordering of the graph optimisation (Sec. III-B.2); rank is CAGRA's")
     ap.add_argument("--no-graph-report", action="store_true", help="skip the 2-hop / connected-component report")
@@ -123,9 +125,10 @@ def main() -> int:
     queries = torch.from_numpy(w.queries).to(dev)
 
     t0 = time.time()
-    if N <= 2_000_000:
+    if N <= 2_000_000 or args.initial_graph == "nn-descent":
         graph = cagra.build(base, w.degree, w.init_degree, w.metric,
-                            reorder=cagra.REORDER_DISTANCE if args.reorder == "distance" else cagra.REORDER_RANK)
+                            reorder=cagra.REORDER_DISTANCE if args.reorder == "distance" else cagra.REORDER_RANK,
+                            nn_descent=args.initial_graph == "nn-descent")
         torch.cuda.synchronize()
     else:
         # the same two stages as cagra_build, the first in slices of rows so that a long build
@@ -249,7 +252,8 @@ def main() -> int:
                                f"search_width={P_WIDTH}, single-workgroup mode",
                    "itopk": M, "search_width": P_WIDTH, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
                    "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
-                   "graph_build_s": round(build_s, 2), "reorder": args.reorder, "graph_quality": graph_quality},
+                   "graph_build_s": round(build_s, 2), "reorder": args.reorder, "initial_graph": args.initial_graph,
+                   "graph_quality": graph_quality},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None

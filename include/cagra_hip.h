@@ -225,9 +225,10 @@ int cagra_optimize_ex(const uint32_t *knn, const float *knn_dists, int64_t N, in
  * Initial graph by NN-descent (Sec. III-B.1 names it; the details are this library's): synchronous
  * rounds in which every node pulls candidates, so the result does not depend on the order of
  * processing.  Round 0: the k best of k pseudo-random nodes (the generator of the search's step 0
- * on (seed, node, slot)).  Round t: F(x) = the first `sample` entries of x's list, R(x) = up to
- * `sample` nodes y with x in F(y), ordered by (rank of x in F(y), y); the new list of x is the k best
- * of its old list and all entries of the lists of F(x) and R(x), x left out.
+ * on (seed, node, slot)).  Round t: F(x) = `sample` entries of x's list from rank
+ * min(((t - 1) mod ceil(k / sample)) * sample, k - sample) on, R(x) = up to `sample` nodes y with x in
+ * F(y), ordered by (rank of x in F(y), y); the new list of x is the k best of its old list and all
+ * entries of the lists of F(x) and R(x), x left out.
  * knn_out[N, k], dists_out[N, k]: rows ascending by (distance, id); unused slots
  * (CAGRA_INVALID_ID, FLT_MAX).  rounds: number of rounds after round 0, < 0 automatic
  * (about log2(N) / 2 + 5); sample: 1..min(64, k), 0 automatic (32).  1 <= k <= 512, k < N.

@@ -176,7 +176,10 @@ int oracle_knn_graph(const float *X, int64_t N, int32_t dim, int32_t metric,
  * does not depend on the order in which nodes are processed:
  *   round 0   L_0(x) = the k best of k pseudo-random nodes (slot j of node x is
  *             the step-0 generator of the search applied to (seed, x, j));
- *   round t   F(x) = the first s entries of L_{t-1}(x) (its s closest),
+ *   round t   F(x) = the s entries of L_{t-1}(x) from rank w_t on, with the
+ *                    window w_t = min(((t-1) mod ceil(k/s)) * s, k - s) moving
+ *                    through the list from round to round (every entry gets to
+ *                    propose its own neighbours once per cycle),
  *             R(x) = up to s nodes y with x in F(y), ordered by (rank of x in
  *                    F(y), y)  (reverse neighbours matter: a node nobody
  *                    lists would never be proposed to anyone),
@@ -233,11 +236,14 @@ int oracle_nn_descent(const float *X, int64_t N, int32_t dim, int32_t metric, in
     for (int t = 1; t <= rounds; ++t) {
         memcpy(prev_id, ids, sizeof(uint32_t) * (size_t)N * k);
         memcpy(prev_d, dists, sizeof(float) * (size_t)N * k);
+        const int n_win = (k + s - 1) / s;
+        int win = ((t - 1) % n_win) * s;
+        if (win > k - s) win = k - s;
         /* reverse sample: sources in order of (rank, source id), at most s per node */
         memset(rev_len, 0, sizeof(uint32_t) * (size_t)N);
         for (int r = 0; r < s; ++r)
             for (int64_t y = 0; y < N; ++y) {
-                uint32_t x = prev_id[(size_t)y * k + r];
+                uint32_t x = prev_id[(size_t)y * k + win + r];
                 if (x != ORACLE_INVALID_ID && rev_len[x] < (uint32_t)s) rev[(size_t)x * s + rev_len[x]++] = (uint32_t)y;
             }
 #pragma omp parallel
@@ -258,7 +264,7 @@ int oracle_nn_descent(const float *X, int64_t N, int32_t dim, int32_t metric, in
                 for (int pass = 0; pass < 2; ++pass) {
                     const int np = pass == 0 ? s : (int)rev_len[x];
                     for (int i = 0; i < np; ++i) {
-                        uint32_t v = pass == 0 ? prev_id[(size_t)x * k + i] : rev[(size_t)x * s + i];
+                        uint32_t v = pass == 0 ? prev_id[(size_t)x * k + win + i] : rev[(size_t)x * s + i];
                         if (v == ORACLE_INVALID_ID) continue;
                         for (int j = 0; j < k; ++j) {
                             uint32_t c = prev_id[(size_t)v * k + j];

@@ -374,14 +374,15 @@ def test_nn_descent_one_round_follows_the_stated_rule():
     n, k, s = 400, 10, 4
     base = datagen.sift_like(n, 8, 4, seed=3, stream=1)
     b = base.astype(np.float64)
-    for t in (1, 3):
+    for t in (1, 2, 3, 4):      # windows 0, 4, 6 (clipped to k - s), 0
         prev, _ = oracle.nn_descent(base, k, t - 1, s, seed=5)
         cur, _ = oracle.nn_descent(base, k, t, s, seed=5)
-        forward = [[int(v) for v in prev[x][:s] if v != oracle.INVALID_ID] for x in range(n)]
+        win = min(((t - 1) % -(-k // s)) * s, k - s)       # the sample's first rank moves from round to round
+        forward = [[int(v) for v in prev[x][win:win + s] if v != oracle.INVALID_ID] for x in range(n)]
         reverse = [[] for _ in range(n)]
-        for r in range(s):                       # sources ordered by (rank, source), at most s each
+        for r in range(win, win + s):            # sources ordered by (rank, source), at most s each
             for y in range(n):
-                if r < len(prev[y]) and prev[y][r] != oracle.INVALID_ID and len(reverse[prev[y][r]]) < s:
+                if prev[y][r] != oracle.INVALID_ID and len(reverse[prev[y][r]]) < s:
                     reverse[int(prev[y][r])].append(y)
         for x in range(0, n, 7):
             pool = {int(v) for v in prev[x] if v != oracle.INVALID_ID}
