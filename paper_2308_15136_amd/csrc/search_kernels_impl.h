@@ -362,18 +362,28 @@ search_multi_kernel(const SearchParams P)
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (uint32_t)P.workers - 1u) return;
     __threadfence();
-    // last worker: fold the other lists into its own, one bitonic merge each
-    for (int w = 0; w < P.workers; ++w) {
-        if (w == worker) continue;
-        const uint64_t *other = P.lists + ((size_t)qi * P.workers + w) * (64 * MR);
-        uint32_t ohi[MR], olo[MR];
+    // last worker: fold the other lists into its own, one bitonic merge each; the lists are read
+    // four at a time so that their latencies overlap
+    constexpr int kFold = 4;
+    for (int w0 = 0; w0 < P.workers; w0 += kFold) {
+        uint64_t key[kFold][MR];
 #pragma unroll
-        for (int r = 0; r < MR; ++r) {
-            uint64_t key = __builtin_nontemporal_load(other + r * 64 + lane);
-            ohi[r] = (uint32_t)(key >> 32);
-            olo[r] = (uint32_t)key;
+        for (int u = 0; u < kFold; ++u) {
+            const int w = w0 + u;
+            const bool take = w < P.workers && w != worker;
+            const uint64_t *other = P.lists + ((size_t)qi * P.workers + (take ? w : worker)) * (64 * MR);
+#pragma unroll
+            for (int r = 0; r < MR; ++r) key[u][r] = __builtin_nontemporal_load(other + r * 64 + lane);
         }
-        merge_into_topm<MR, MR>(thi, tlo, ohi, olo, lane);
+#pragma unroll
+        for (int u = 0; u < kFold; ++u) {
+            const int w = w0 + u;
+            if (w >= P.workers || w == worker) continue;
+            uint32_t ohi[MR], olo[MR];
+#pragma unroll
+            for (int r = 0; r < MR; ++r) { ohi[r] = (uint32_t)(key[u][r] >> 32); olo[r] = (uint32_t)key[u][r]; }
+            merge_into_topm<MR, MR>(thi, tlo, ohi, olo, lane);
+        }
     }
     write_result<MR>(P, qi, thi, tlo);
 }
