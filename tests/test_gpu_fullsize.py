@@ -79,3 +79,56 @@ def test_large_batch_workload_at_full_size():
             n_ids, n_d = cagra.search(graph, cagra.convert_dataset(base, code), queries, w.k, itopk, width,
                                       w.metric, opts)
             assert torch.equal(n_ids, ids) and torch.equal(n_d, dists)
+
+
+@pytest.mark.parametrize("name,cases", [
+    ("deep1m", ((10, 128, 1), (100, 256, 1), (10, 64, 4))),      # 1M x 96 unit-norm rows, L2, degree 32
+    ("glove200", ((10, 256, 1), (10, 128, 2))),                   # 1,183,514 x 200 unit-norm rows, inner product
+])
+def test_float_workloads_at_full_size(name, cases):
+    """The lower-dimensional and the inner-product configuration at their full sizes: whole batch on
+    the GPU, a sample of the queries on the oracle, the stated bars for floating-point data
+    (distances within 1e-5 relative, id agreement >= 99.5 %, recall within 0.003)."""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2308_15136_amd as cagra
+    cagra.load_library()
+    w = datagen.workload(name)
+    N, dim = w.base.shape
+    print(f"case fullsize {name} N={N} dim={dim} d={w.degree}", flush=True)
+    base = torch.from_numpy(w.base).cuda()
+    queries = torch.from_numpy(w.queries).cuda()
+    graph = cagra.build(base, w.degree, w.init_degree, w.metric)
+    graph_np = _u32(graph)
+    assert graph_np.max() < N
+    # the initial lists behind the graph: sampled rows of the exhaustive search against the oracle
+    rng = np.random.default_rng(1)
+    rows = np.sort(rng.choice(N, size=48, replace=False)).astype(np.int64)
+    knn_rows = torch.cat([cagra.exact_search(base, base[int(r):int(r) + 1], w.init_degree, w.metric, exclude_self=True,
+                                             self_offset=int(r), return_dists=False) for r in rows])
+    np.testing.assert_array_equal(_u32(knn_rows), oracle.knn_graph(w.base, w.init_degree, w.metric, rows=rows))
+    nq = 1200                                    # the oracle runs the first nq queries of the batch
+    gt = _u32(cagra.exact_search(base, queries[:nq], 100, w.metric, return_dists=False))
+    for k, itopk, width in cases:
+        print(f"    k {k} itopk {itopk} search_width {width}", flush=True)
+        opts = cagra.SearchOptions(seed=7, mode=1)
+        ids, dists, st = cagra.search(graph, base, queries, k, itopk, width, w.metric, opts, return_stats=True)
+        ids_np, d_np = _u32(ids), dists.cpu().numpy()
+        o_ids, o_d = oracle.search(graph_np, w.base, w.queries[:nq], k, itopk, width, w.metric, seed=7)
+        agree = sum(len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ids_np[:nq], o_ids)) / float(o_ids.size)
+        assert agree >= 0.995, f"id agreement {agree}"
+        same = ids_np[:nq] == o_ids
+        denom = np.maximum(np.abs(o_d), 1.0 if w.metric == oracle.IP else 0.0)
+        rel = np.abs(d_np[:nq] - o_d)[same] / np.maximum(denom[same], 1e-30)
+        assert rel.max() <= 1e-5, f"distance error {rel.max()}"
+        r_gpu, r_ora = oracle.recall(ids_np[:nq], gt[:, :k]), oracle.recall(o_ids, gt[:, :k])
+        print(f"      id agreement {agree:.5f}  max rel dist err {rel.max():.2e}  recall gpu {r_gpu:.4f} oracle {r_ora:.4f}",
+              flush=True)
+        assert abs(r_gpu - r_ora) <= 0.003
+        # every query of the batch: sorted, unique, valid ids
+        valid = ids_np != oracle.INVALID_ID
+        assert np.all(ids_np[valid] < N) and np.all(np.diff(d_np, axis=1) >= 0)
+        srt = np.sort(ids_np, axis=1)
+        assert np.all((srt[:, 1:] != srt[:, :-1]) | (srt[:, 1:] == oracle.INVALID_ID))
+        assert not np.any(_u32(st)[:, 3] & 2)
