@@ -141,7 +141,8 @@ nnd_round_kernel(const NndParams P)
                 chi[0] = lane < n_new ? f32_to_ordered(newdist[lane]) : kDummyHi;
                 clo[0] = lane < n_new ? (newid[lane] << 1) : kInvalidId;
                 __syncthreads();   // the candidate arrays are scratch for the update below
-                update_topm<MR, 1, true>(thi, tlo, chi, clo, k, lost, forgot, newid, newdist, lane);
+                int unused = 0;
+                update_topm<MR, 1, true>(thi, tlo, chi, clo, k, lost, forgot, newid, newdist, lane, unused);
             }
         }
 

@@ -115,15 +115,17 @@ __device__ __forceinline__ void merge_into_topm(uint32_t (&thi)[MR], uint32_t (&
 // Ordered insertion of one key (wavefront-uniform) into the sorted list t: entries from its
 // position on move up by one element (one lane to the right, lane 63 into lane 0 of the next
 // register), the last element of the list falls off.
+// Returns the position the key went to.
 template <int MR>
-__device__ __forceinline__ void insert_into_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR],
-                                                 uint32_t khi, uint32_t klo, int lane)
+__device__ __forceinline__ int insert_into_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR],
+                                                uint32_t khi, uint32_t klo, int lane)
 {
     int pos = 0;   // entries smaller than the key form a prefix of the sorted list
 #pragma unroll
     for (int r = 0; r < MR; ++r) pos += __popcll(__ballot(key_less(thi[r], tlo[r], khi, klo)));
 #pragma unroll
     for (int r = MR - 1; r >= 0; --r) {
+        if ((r + 1) * kWave <= pos) continue;   // registers wholly below the position stay as they are
         // what arrives in lane 0: the last element of the register below (untouched so far)
         const uint32_t carry_hi = r > 0 ? __builtin_amdgcn_readlane(thi[r > 0 ? r - 1 : 0], 63) : 0u;
         const uint32_t carry_lo = r > 0 ? __builtin_amdgcn_readlane(tlo[r > 0 ? r - 1 : 0], 63) : 0u;
@@ -134,6 +136,7 @@ __device__ __forceinline__ void insert_into_topm(uint32_t (&thi)[MR], uint32_t (
         thi[r] = e > pos ? up_hi : (e == pos ? khi : thi[r]);
         tlo[r] = e > pos ? up_lo : (e == pos ? klo : tlo[r]);
     }
+    return pos;
 }
 
 // Lane i takes the value of lane i - 1, lane 0 that of lane 63 (DPP wave_ror:1).
@@ -188,10 +191,12 @@ constexpr int kInsertLimit = CAGRA_INSERT_LIMIT;
 // entry.  With DEDUP (a visited table that may forget) candidates that repeat a list member or each
 // other are dropped first; `lost` / `forgot` are the table's flags (see sets_insert, sets_confirm).
 // scratch_id / scratch_key: 64 * CR words of LDS each, free at this point.
+// `lead` is the caller's count of leading entries known to carry the parent flag; it is lowered to
+// the first position a candidate (which has no flag) went to.
 template <int MR, int CR, bool DEDUP>
 __device__ __forceinline__ void update_topm(uint32_t (&thi)[MR], uint32_t (&tlo)[MR], uint32_t (&chi)[CR],
                                             uint32_t (&clo)[CR], int length, bool lost, bool forgot,
-                                            uint32_t *scratch_id, float *scratch_key, int lane)
+                                            uint32_t *scratch_id, float *scratch_key, int lane, int &lead)
 {
     const int last = length - 1;
     // key of the last logical entry
@@ -251,11 +256,13 @@ __device__ __forceinline__ void update_topm(uint32_t (&thi)[MR], uint32_t (&tlo)
             while (m != 0ull) {
                 const int l = __builtin_ctzll(m);
                 m &= m - 1;
-                insert_into_topm<MR>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
-                                     __builtin_amdgcn_readlane(clo[r], l), lane);
+                const int pos = insert_into_topm<MR>(thi, tlo, __builtin_amdgcn_readlane(chi[r], l),
+                                                     __builtin_amdgcn_readlane(clo[r], l), lane);
+                lead = pos < lead ? pos : lead;
             }
         }
     } else if (CR > 1 && n_better <= kWave) {
+        lead = 0;
         // the winners fit one register: gather them through LDS, sort 64 keys instead of 64 * CR
         int before = 0;
 #pragma unroll
@@ -274,6 +281,7 @@ __device__ __forceinline__ void update_topm(uint32_t (&thi)[MR], uint32_t (&tlo)
         bitonic_sort<1>(whi1, wlo1, lane);
         merge_into_topm<MR, 1>(thi, tlo, whi1, wlo1, lane);
     } else {
+        lead = 0;
         bitonic_sort<CR>(chi, clo, lane);
         merge_into_topm<MR, CR>(thi, tlo, chi, clo, lane);
     }

@@ -137,6 +137,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     uint32_t n_iter = 0, n_parent_total = 0, n_dist_total = 0, flags = 0;
     bool overflow = false;
     bool forgot = false;                 // kTableSets: the table has dropped an id it once held
+    int lead = 0;                        // entries before this position are known to carry the parent flag
     uint32_t ahead[CR];                  // graph row read ahead for the likely next parent
     uint32_t ahead_id = kInvalidId;
 #pragma unroll
@@ -205,7 +206,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         }
 
         // ---- step 1: top-M update (skipped when no candidate can enter) -------------------
-        update_topm<MR, CR, KIND == kTableSets>(thi, tlo, chi, clo, P.itopk, lost, forgot, newid, newdist, lane);
+        update_topm<MR, CR, KIND == kTableSets>(thi, tlo, chi, clo, P.itopk, lost, forgot, newid, newdist, lane, lead);
         CAGRA_PHASE(3)
         if (it == P.max_iterations) { flags |= 1u; break; }
 
@@ -224,6 +225,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
         int n_par = 0;
 #pragma unroll
         for (int r = 0; r < MR; ++r) {
+            if ((r + 1) * kWave <= lead || n_par == P.search_width) continue;   // nothing to find there
             uint64_t m = __ballot((tlo[r] & 1u) == 0u);
             while (m != 0ull && n_par < P.search_width) {
                 int l = __builtin_ctzll(m);
@@ -232,6 +234,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                 if (lane == l) tlo[r] |= 1u;
                 if (lane == 0) parents[n_par] = w >> 1;
                 ++n_par;
+                lead = r * kWave + l + 1;    // everything up to the parent just taken has the flag
             }
         }
         if (n_par == 0) break;
@@ -254,9 +257,9 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
             ahead_id = kInvalidId;
 #pragma unroll
             for (int r = 0; r < MR; ++r) {
+                if ((r + 1) * kWave <= lead || ahead_id != kInvalidId) continue;
                 const uint64_t m = __ballot((tlo[r] & 1u) == 0u);
-                if (ahead_id == kInvalidId && m != 0ull)
-                    ahead_id = __builtin_amdgcn_readlane(tlo[r], __builtin_ctzll(m)) >> 1;
+                if (m != 0ull) ahead_id = __builtin_amdgcn_readlane(tlo[r], __builtin_ctzll(m)) >> 1;
             }
             if (ahead_id != kInvalidId) {
 #pragma unroll
