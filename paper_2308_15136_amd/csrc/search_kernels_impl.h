@@ -7,10 +7,10 @@
 //     parent flag.  One unsigned 64-bit compare is the (distance, id) order; the flag bit
 //     sits below the id so it cannot change that order (Sec. IV-B.4 keeps the flag in the
 //     index word as well).  Element e of a list is held by lane e % 64 in register e / 64.
-//   - step 1 is a bitonic sort of the candidates followed by a bitonic merge into the
-//     sorted top-M list (Sec. IV-B.2).
+//   - step 1 (update_topm): candidates that beat the last entry enter the sorted list, a few by
+//     ordered insertion, many by a bitonic sort followed by a bitonic merge (Sec. IV-B.2).
 //   - distances are computed by teams of 4/8/16/32 lanes, one dataset row per team,
-//     16-byte loads, butterfly reduction (Sec. IV-B.1).
+//     16-byte loads, butterfly reduction (team_distances; Sec. IV-B.1).
 // Single mode (Sec. IV-C.1): workgroups are persistent and pull query indices from a
 // device counter; the visited table lives in LDS and forgets (Sec. IV-B.3), in one of two
 // ways: kTableSets -- sets of four ids in which a new id replaces the oldest, with
@@ -40,8 +40,6 @@
 namespace cagra {
 
 constexpr int kElem = CAGRA_ELEM;
-constexpr int kElemsPerPiece = elems_per_piece<kElem>();   // elements in 16 bytes
-constexpr int kElemBytes = 16 / kElemsPerPiece;
 
 // Multi mode issues the first probe of every candidate before the dataset rows are fetched and
 // looks at its answer afterwards (the row loads do not wait for the table).  `old` is what the
