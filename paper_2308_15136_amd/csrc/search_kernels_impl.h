@@ -73,6 +73,7 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 // memory-time read and a wait per phase.
 #ifdef CAGRA_PHASE_CLOCKS
 static __device__ unsigned long long g_phase_clocks[8];
+static __device__ unsigned long long g_query_times[2 * 131072];   // start / end wall clock (100 MHz) of the first queries
 #define CAGRA_PHASE_BEGIN() unsigned long long ph_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long ph_t = __builtin_amdgcn_s_memtime();
 #define CAGRA_PHASE(i) { const unsigned long long ph_n = __builtin_amdgcn_s_memtime(); ph_acc[i] += ph_n - ph_t; ph_t = ph_n; }
 #define CAGRA_PHASE_END() if (lane == 0) { _Pragma("unroll") for (int ph_i = 0; ph_i < 8; ++ph_i) if (ph_acc[ph_i]) atomicAdd(&g_phase_clocks[ph_i], ph_acc[ph_i]); }
@@ -323,9 +324,15 @@ search_single_kernel(const SearchParams P)
         if ((int64_t)qi >= P.B) break;
         uint32_t thi[MR], tlo[MR];
         QueryStats qs;
+#ifdef CAGRA_PHASE_CLOCKS
+        if (lane == 0 && qi < 131072u) g_query_times[2 * qi] = wall_clock64();
+#endif
         search_body<MR, CR, KIND, kRowsInFlight>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                                    thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
+#ifdef CAGRA_PHASE_CLOCKS
+        if (lane == 0 && qi < 131072u) g_query_times[2 * qi + 1] = wall_clock64();
+#endif
         if (P.stats != nullptr && lane == 0) {
             uint32_t *s = P.stats + (size_t)qi * 4;
             s[0] = qs.n_iter; s[1] = qs.n_parent; s[2] = qs.n_dist; s[3] = qs.flags;
@@ -440,6 +447,13 @@ hipError_t CAGRA_CAT(launch_search_multi_, CAGRA_ELEM_NAME)(const SearchParams &
 }  // namespace cagra
 
 #ifdef CAGRA_PHASE_CLOCKS
+// Start and end wall clock (100 MHz) of the first n queries of the last single-mode launch.
+extern "C" int CAGRA_CAT(cagra_debug_query_times_, CAGRA_ELEM_NAME)(unsigned long long *out_host, int n)
+{
+    if (hipDeviceSynchronize() != hipSuccess || n < 0 || n > 131072) return -1;
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(cagra::g_query_times), sizeof(unsigned long long) * 2 * n) == hipSuccess ? 0 : -1;
+}
+
 // Reads (and optionally clears) the phase timers of this storage type's kernels; synchronises the device.
 extern "C" int CAGRA_CAT(cagra_debug_phase_clocks_, CAGRA_ELEM_NAME)(unsigned long long *out_host, int clear)
 {
