@@ -57,12 +57,12 @@ class _SearchPlan(C.Structure):
 
 
 def load_library():
-    """Load libcagra_hip.so (built by paper_2308_15136_amd.build) and declare its ABI."""
+    """Load libcagra_hip.so (built by paper_2308_15136_amd.buildlib) and declare its ABI."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        raise CagraError(f"{LIB_PATH} is missing: run `python -m paper_2308_15136_amd.build` "
+        raise CagraError(f"{LIB_PATH} is missing: run `python -m paper_2308_15136_amd.buildlib` "
                          "(there is no CPU fallback)")
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t

@@ -22,7 +22,7 @@ def _declared():
 def test_every_declared_symbol_is_exported():
     import paper_2308_15136_amd as m
     if not os.path.exists(m.LIB_PATH):
-        from paper_2308_15136_amd import build
+        from paper_2308_15136_amd import buildlib as build
         build.build_library()
     lib = ctypes.CDLL(m.LIB_PATH)
     names = _declared()
@@ -70,3 +70,13 @@ def test_describe_reports_the_automatic_parameters():
     assert m.describe(32, 200, 10_000, 10, 64, 1, m.SearchOptions(mode=1))["team_size"] == 16
     with pytest.raises(m.CagraError):
         m.describe(32, 96, 10, 100, 64, 1)          # k > itopk
+
+
+def test_build_entry_point_finds_the_build_script():
+    # the package exports a function called build (graph construction); the script that compiles the
+    # library must stay reachable under its own name for the driver's build() entry point
+    import importlib
+    mod = importlib.import_module("paper_2308_15136_amd.buildlib")
+    assert callable(mod.build_library) and len(mod.sources()) >= 8
+    import __graft_entry__ as g
+    assert callable(g.build) and callable(g.smoke)
