@@ -42,6 +42,10 @@ def _cases():
         team = int(rng.choice([0, 0, 4, 8, 16, 32]))
         pad = int(rng.choice([0, 0, 16, 64]))
         cases.append((i, dim, degree, width, itopk, k, storage, policy, entries, team, pad))
+    # rows longer than one sweep of a team's lanes (more than four 16-byte loads per lane), as for the
+    # 960-dimensional descriptors of Table I
+    cases += [(48, 960, 16, 1, 64, 10, "f32", 0, 0, 0, 0), (49, 960, 16, 2, 100, 10, "f16", 0, 0, 8, 32),
+              (50, 2048, 16, 1, 32, 10, "u8", 1, 0, 4, 0), (51, 1536, 32, 1, 64, 10, "f32", 2, 1024, 16, 0)]
     return cases
 
 
@@ -51,7 +55,7 @@ _built = {}
 def _index(dim, degree):
     key = (dim, degree)
     if key not in _built:
-        base = datagen.sift_like(3000, dim, 12, seed=100 + dim, stream=1)
+        base = datagen.sift_like(3000, dim, 12, seed=100 + dim, stream=1, rank=min(64, dim))
         queries = datagen.sift_like(64, dim, 12, seed=100 + dim, stream=2)
         _built[key] = (base, queries, oracle.build(base, degree, 2 * degree))
     return _built[key]
