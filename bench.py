@@ -94,6 +94,8 @@ def main() -> int:
     ap.add_argument("--no-graph-report", action="store_true", help="skip the 2-hop / connected-component report")
     ap.add_argument("--no-graph", action="store_true", help="skip the captured-graph replay of the batch-1 call")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--ablations", action="store_true",
+                    help="also time the alternatives to the automatic choices (team size, visited table, mode)")
     ap.add_argument("--no-scaling", action="store_true", help="skip the larger-batch runs")
     ap.add_argument("--no-storage", action="store_true", help="skip the fp16 / uint8 storage part")
     ap.add_argument("--no-reference", action="store_true", help="skip the stream / row-gather bandwidth references")
@@ -395,6 +397,66 @@ def main() -> int:
         out["hbm_reference"] = ref
         log(f"[bench] reference: stream read {ref['stream_read_GBs']} GB/s, random {dim * 4}-byte rows "
             f"{ref['best_row_gather_GBs']} GB/s")
+
+    # ---- the choices the library makes by itself, each against its alternatives (the paper's own
+    #      studies of team size, Sec. V-B, of the visited-table management, Sec. IV-B.3, and of the two
+    #      modes over the batch size, Sec. IV-C.3) -----------------------------------------------------
+    if args.ablations:
+        def time_opts(o, p_w, m_itopk, qs, reps=5):
+            nq = qs.shape[0]
+            a_ids = torch.empty((nq, w.k), dtype=torch.int32, device=dev)
+            a_d = torch.empty((nq, w.k), dtype=torch.float32, device=dev)
+            a_st = torch.zeros((nq, 4), dtype=torch.int32, device=dev)
+            a_ws = torch.empty(max(4096, cagra.search_workspace_bytes(N, w.degree, nq, w.k, m_itopk, p_w, o)),
+                               dtype=torch.uint8, device=dev)
+            for _ in range(2):
+                cagra.search(graph, base, qs, w.k, m_itopk, p_w, w.metric, o, out=(a_ids, a_d), workspace=a_ws, stats=a_st)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                cagra.search(graph, base, qs, w.k, m_itopk, p_w, w.metric, o, out=(a_ids, a_d), workspace=a_ws, stats=a_st)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            rec_a = recall_at_k(a_ids.cpu().numpy().view(np.uint32), gt_np[:nq])
+            nd = float(a_st.cpu().numpy().view(np.uint32)[:, 2].astype(np.int64).mean())
+            return ms, rec_a, nd, a_ids
+        abl = {"configuration": {"search_width": P_WIDTH, "itopk": M}}
+        auto_plan = cagra.describe(w.degree, dim, B, w.k, M, P_WIDTH, opts)
+        abl["automatic"] = {k2: auto_plan[k2] for k2 in ("team_size", "table_entries", "table_policy", "workgroups")}
+        rows = []
+        for team in (4, 8, 16, 32):
+            ms, rec_a, nd, a_ids = time_opts(cagra.SearchOptions(seed=opts.seed, mode=1, team_size=team), P_WIDTH, M, queries)
+            rows.append({"team_size": team, "kernel_ms": round(ms, 4), "qps": round(B / ms * 1e3, 1),
+                         "same_ids": bool(torch.equal(a_ids, ids))})
+            log(f"[bench] team size {team}: {ms:.3f} ms")
+        abl["team_size"] = rows
+        rows = []
+        for pol, entries in ((2, 1024), (2, 2048), (2, 3072), (2, 4096), (2, 8192), (1, 2048), (1, 4096), (1, 8192)):
+            try:
+                ms, rec_a, nd, a_ids = time_opts(cagra.SearchOptions(seed=opts.seed, mode=1, table_policy=pol,
+                                                                     table_entries=entries), P_WIDTH, M, queries)
+            except cagra.CagraError as exc:
+                rows.append({"table_policy": pol, "table_entries": entries, "rejected": str(exc)})
+                continue
+            rows.append({"table_policy": "replacement" if pol == 2 else "periodic reset", "table_entries": entries,
+                         "kernel_ms": round(ms, 4), "qps": round(B / ms * 1e3, 1),
+                         "distances_per_query": round(nd, 1), "same_ids": bool(torch.equal(a_ids, ids))})
+            log(f"[bench] table policy {pol} entries {entries}: {ms:.3f} ms, {nd:.0f} distances per query")
+        abl["visited_table"] = rows
+        rows = []
+        for nb in (1, 16, 64, 256, 1024, 4096, B):
+            qs = queries[:nb]
+            ms1, rec1, _, _ = time_opts(cagra.SearchOptions(seed=opts.seed, mode=1), P_WIDTH, M, qs, reps=10)
+            ms2, rec2, _, _ = time_opts(cagra.SearchOptions(seed=opts.seed, mode=2, wg_per_query=8, max_iterations=16),
+                                        1, 256, qs, reps=10)
+            rows.append({"batch": nb, "single_ms": round(ms1, 4), "single_recall": round(rec1, 4),
+                         "multi_ms": round(ms2, 4), "multi_recall": round(rec2, 4),
+                         "automatic_mode": cagra.auto_mode(nb, M)})
+            log(f"[bench] batch {nb}: single {ms1:.3f} ms (recall {rec1:.3f}), multi W=8 I_max=16 {ms2:.3f} ms (recall {rec2:.3f})")
+        abl["mode_over_batch_size"] = rows
+        out["ablations"] = abl
 
     # ---- small batches in multi-workgroup mode: host-side latency per call (Sec. IV-C.2) -------
     # Workers per query W and the pass limit I_max are swept (itopk = 32 W, so every worker keeps

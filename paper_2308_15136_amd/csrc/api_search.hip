@@ -83,8 +83,9 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
 
     // Visited table in LDS (Sec. IV-B.3), in one of two managements.
     //  - replacement (default): sets of four ids, a new id replaces the oldest of its set.  Any size
-    //    works; automatic size 3072 entries (12 KB + 768 bytes of per-set cursors), the measured optimum
-    //    on the 1M x 128 workload for itopk 64..256: smaller tables forget more, larger ones cost wavefronts per CU.
+    //    works; automatic size 3072 to 4096 entries (12 to 16 KB plus a byte of cursor per set), the
+    //    measured optimum on the 1M x 128 workload: smaller tables forget more, larger ones cost
+    //    wavefronts per CU.
     //  - periodic reset (the paper's; chosen by table_policy 1, or when hash_bits or reset_interval
     //    are given): open addressing.  Between two resets the table receives at most
     //    itopk + interval * n_cand ids; probing in LDS is cheap, so it may fill up to 7/8.
@@ -105,7 +106,10 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
         const int want = ((itopk + 8 * n_cand) * 8 / 7 + 63) & ~63;
         words = std::min(8192, std::max(4096, want));
     } else {
-        words = kAutoSetTableEntries;
+        // measured on the 1M x 128 workload: 3072 entries for up to 64 candidates per pass, 3584 for up to
+        // 128, 4096 beyond (wider passes insert more per pass, and their candidate buffers already cost
+        // wavefronts per CU)
+        words = n_cand <= 64 ? kAutoSetTableEntries : n_cand <= 128 ? kAutoSetTableEntries + 512 : kAutoSetTableEntries + 1024;
     }
     pl.table_words = words;
     pl.table_policy = reset ? 1 : 2;
