@@ -295,6 +295,41 @@ def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, m
     return (ids, dists, stats) if return_stats else (ids, dists)
 
 
+class PreparedSearch:
+    """A search call with everything but the launch resolved once: tensors checked, options
+    marshalled, outputs and workspace allocated.  Calling it enqueues one search of the `queries`
+    buffer it was made for (write new queries into that buffer between calls) on the current stream
+    and returns (ids, dists): the same tensors every time.  For loops that issue many small calls."""
+
+    def __init__(self, graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,
+                 options: Optional[SearchOptions] = None):
+        torch = _torch()
+        self._lib = load_library()
+        graph = _dev_i32(graph, "graph")
+        dataset, dtype = _dev_dataset(dataset)
+        queries = _dev_f32(queries, "queries")
+        dev = dataset.device
+        B = queries.shape[0]
+        o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype)
+        self._copts = _copts(o)
+        self.ids = torch.empty((B, k), dtype=torch.int32, device=dev)
+        self.dists = torch.empty((B, k), dtype=torch.float32, device=dev)
+        N, degree = graph.shape
+        self._ws = _workspace(self._lib.cagra_search_workspace_bytes(N, degree, B, k, itopk, search_width,
+                                                                     C.byref(self._copts)), dev)
+        self._keep = (graph, dataset, queries)          # the call holds raw pointers into these
+        self._device = dev
+        self._args = (graph.data_ptr(), N, degree, dataset.data_ptr(), dataset.shape[1], dataset.stride(0), metric,
+                      queries.data_ptr(), B, queries.stride(0), k, itopk, search_width, C.byref(self._copts),
+                      self.ids.data_ptr(), self.dists.data_ptr(), self._ws.data_ptr(), self._ws.numel())
+
+    def __call__(self):
+        rc = self._lib.cagra_search(*self._args, _stream(self._device))
+        if rc != 0:
+            _check(rc, "cagra_search")
+        return self.ids, self.dists
+
+
 def exact_search(dataset, queries, k: int, metric: int = L2, exclude_self: bool = False,
                  self_offset: int = 0, return_dists: bool = True):
     """Exhaustive k nearest neighbours (Eq. 1): (ids[B, k] int32, dists[B, k] float32)."""

@@ -80,3 +80,30 @@ def test_build_entry_point_finds_the_build_script():
     assert callable(mod.build_library) and len(mod.sources()) >= 8
     import __graft_entry__ as g
     assert callable(g.build) and callable(g.smoke)
+
+
+def test_python_structs_match_the_header_layout(tmp_path):
+    # the binding mirrors the header's structs by hand: compile the header with gcc and compare
+    # sizes and field offsets
+    import subprocess
+    import paper_2308_15136_amd as m
+    fields = {"cagra_search_opts": [f for f, _ in m._SearchOpts._fields_],
+              "cagra_search_plan": [f for f, _ in m._SearchPlan._fields_],
+              "cagra_build_opts": [f for f, _ in m._BuildOpts._fields_]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', f'#include "{os.path.join(ROOT, "include", "cagra_hip.h")}"',
+             'int main(void) {']
+    for s, fs in fields.items():
+        lines.append(f'  printf("{s} %zu\\n", sizeof({s}));')
+        for f in fs:
+            lines.append(f'  printf("{s}.{f} %zu\\n", offsetof({s}, {f}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-o", str(exe), str(src)], check=True)
+    got = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for s, cls in (("cagra_search_opts", m._SearchOpts), ("cagra_search_plan", m._SearchPlan),
+                   ("cagra_build_opts", m._BuildOpts)):
+        assert int(got[s]) == ctypes.sizeof(cls), s
+        for f, _ in cls._fields_:
+            assert int(got[f"{s}.{f}"]) == getattr(cls, f).offset, f"{s}.{f}"

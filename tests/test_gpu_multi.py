@@ -125,3 +125,29 @@ def test_auto_mode_rule(cagra):
     # itopk beyond the single-workgroup limit goes to the multi mode
     ids, dists = cagra.search(gd, bd, qd, 10, 1024, 8, w.metric, cagra.SearchOptions(seed=1))
     assert oracle.recall(ids.cpu().numpy().view(np.uint32), gt) > 0.9
+
+
+def test_prepared_search_gives_the_same_answers(cagra):
+    import torch
+    w, g, gt, (gd, bd, qd) = _setup("sift1m", 20_000, 200, 64)
+    # single mode: deterministic, so the prepared call must reproduce search() exactly, call after call
+    opts = cagra.SearchOptions(seed=3, mode=1)
+    qbuf = qd[:50].clone()
+    prepared = cagra.PreparedSearch(gd, bd, qbuf, 10, 64, 2, w.metric, opts)
+    for lo in (0, 50, 150):
+        qbuf.copy_(qd[lo:lo + 50])
+        ids, dists = prepared()
+        e_ids, e_d = cagra.search(gd, bd, qd[lo:lo + 50], 10, 64, 2, w.metric, opts)
+        assert torch.equal(ids, e_ids) and torch.equal(dists, e_d)
+    # multi mode, one query at a time
+    mopts = cagra.SearchOptions(seed=3, mode=2, wg_per_query=8, max_iterations=12)
+    q1 = qd[:1].clone()
+    one = cagra.PreparedSearch(gd, bd, q1, 10, 256, 1, w.metric, mopts)
+    hits = 0
+    for b in range(60):
+        q1.copy_(qd[b:b + 1])
+        ids, dists = one()
+        row = ids.cpu().numpy().view(np.uint32)[0]
+        hits += len(set(row.tolist()) & set(gt[b].tolist()))
+        assert np.all(np.diff(dists.cpu().numpy()[0]) >= 0) and len(set(row.tolist())) == 10
+    assert hits / 600.0 > 0.9
