@@ -62,9 +62,9 @@ def measured_traffic(workload: str, width: int, itopk: int):
         text = open(path).read()
     except OSError:
         return None
-    m = re.search(r"traffic_bytes_per_launch:\s*(\d+)\s*\(search_width (\d+), itopk (\d+)", text)
-    if m and int(m.group(2)) == width and int(m.group(3)) == itopk:
-        return float(m.group(1))
+    for m in re.finditer(r"traffic_bytes_per_launch:\s*(\d+)\s*\(search_width (\d+), itopk (\d+)", text):
+        if int(m.group(2)) == width and int(m.group(3)) == itopk:
+            return float(m.group(1))
     return None
 
 
@@ -208,7 +208,7 @@ def main() -> int:
     for p in widths:
         prev = None
         for M in sweep_list:
-            if M < w.k or p * w.degree > 256:
+            if M < w.k or p * w.degree > 2048:
                 continue
             wall_ms, dev_ms = timed(M, p, 5, 2)
             rec = recall_at_k(ids.cpu().numpy().view(np.uint32), gt_np)
@@ -260,7 +260,8 @@ def main() -> int:
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None
                      else measured_traffic(w.name, P_WIDTH, M),
-                     "kernel": "search_single_kernel", "kernel_ms": round(dev_ms, 4),
+                     "kernel": "search_single_wide_kernel" if P_WIDTH * w.degree > 256 else "search_single_kernel",
+                     "kernel_ms": round(dev_ms, 4),
                      "algorithmic_bytes_per_launch": ab["total_bytes"],
                      "gathered_vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
                      "n_dist_per_query": round(ab["n_dist"] / B, 1),

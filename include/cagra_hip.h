@@ -108,8 +108,9 @@ typedef struct {
  * if fewer than k nodes were reached the tail is (CAGRA_INVALID_ID, FLT_MAX).
  * dim and ld (in elements) must be multiples of the elements in 16 bytes of the storage type
  * (4 for fp32, 8 for fp16, 16 for uint8).
- * Requirements: 1 <= k <= itopk; single mode: itopk <= 512 and
- * search_width * degree <= 256; multi mode: see cagra_search_opts.
+ * Requirements: 1 <= k <= itopk; single mode: itopk <= 512, search_width <= 64 and
+ * search_width * degree <= 2048 (beyond 256 candidates a pass takes them in chunks of 256, the
+ * large-candidate-list case of Sec. IV-B.2); multi mode: see cagra_search_opts.
  * B == 0 is allowed and does nothing.
  */
 int cagra_search(const uint32_t *graph, int64_t N, int32_t degree,

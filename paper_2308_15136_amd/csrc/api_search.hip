@@ -60,19 +60,24 @@ constexpr int kAutoSetTableEntries = CAGRA_AUTO_SET_TABLE;
 
 struct SinglePlan {
     int mr, cr, table_words, table_policy, reset_interval, team_log2, max_iterations;
+    bool wide;   // more than 256 candidates per pass: taken in chunks of 256
     size_t smem;
     int off_query, off_newid, off_newdist, off_parents;
 };
+
+constexpr int kMaxCandidates = 2048;   // search_width * degree, single mode
+constexpr int kMaxWidth = 64;          // parents per pass (their ids sit in a 64-entry LDS array)
 
 static int plan_single(int degree, int dim, int itopk, int width, const cagra_search_opts &o, SinglePlan &pl)
 {
     const int pieces = dim / elems_per_piece(o.dataset_type);   // 16-byte pieces per dataset row
     if (itopk > 512) return CAGRA_ERR_BAD_TOPK;
     const int n_cand = width * degree;
-    if (n_cand > 256) return CAGRA_ERR_BAD_TOPK;
+    if (n_cand > kMaxCandidates || width > kMaxWidth) return CAGRA_ERR_BAD_TOPK;
     int mr = (itopk + 63) / 64;
     pl.mr = mr <= 1 ? 1 : mr <= 2 ? 2 : mr <= 4 ? 4 : 8;
     pl.cr = n_cand <= 64 ? 1 : n_cand <= 128 ? 2 : 4;
+    pl.wide = n_cand > 256;
 
     int team = o.team_size == 0 ? auto_team(pieces) : o.team_size;
     if (team != 4 && team != 8 && team != 16 && team != 32) return CAGRA_ERR_BAD_OPTION;
@@ -110,6 +115,8 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
         // 128, 4096 beyond (wider passes insert more per pass, and their candidate buffers already cost
         // wavefronts per CU)
         words = n_cand <= 64 ? kAutoSetTableEntries : n_cand <= 128 ? kAutoSetTableEntries + 512 : kAutoSetTableEntries + 1024;
+        // (also beyond 256 candidates: measured with 320 to 2048 per pass, larger tables lose more to the
+        // wavefronts they displace than they save in distances computed twice)
     }
     pl.table_words = words;
     pl.table_policy = reset ? 1 : 2;
@@ -345,9 +352,15 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const void *d
     const DeviceInfo &di = device_info();
     // persistent grid: as many single-wavefront workgroups as fit (LDS-bound, at most 16 per CU)
     int grid = (int)std::min<int64_t>(B, (int64_t)single_per_cu(o, pl, di) * di.cus);
-    hipError_t e = o.dataset_type == CAGRA_F32   ? launch_search_single_f32(P, pl.mr, pl.cr, grid, pl.smem, stream)
-                   : o.dataset_type == CAGRA_F16 ? launch_search_single_f16(P, pl.mr, pl.cr, grid, pl.smem, stream)
-                                                 : launch_search_single_u8(P, pl.mr, pl.cr, grid, pl.smem, stream);
+    hipError_t e;
+    if (pl.wide)
+        e = o.dataset_type == CAGRA_F32   ? launch_search_wide_f32(P, pl.mr, grid, pl.smem, stream)
+            : o.dataset_type == CAGRA_F16 ? launch_search_wide_f16(P, pl.mr, grid, pl.smem, stream)
+                                          : launch_search_wide_u8(P, pl.mr, grid, pl.smem, stream);
+    else
+        e = o.dataset_type == CAGRA_F32   ? launch_search_single_f32(P, pl.mr, pl.cr, grid, pl.smem, stream)
+            : o.dataset_type == CAGRA_F16 ? launch_search_single_f16(P, pl.mr, pl.cr, grid, pl.smem, stream)
+                                          : launch_search_single_u8(P, pl.mr, pl.cr, grid, pl.smem, stream);
     return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
 }
 

@@ -279,6 +279,141 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
 }
 
+// Candidate lists beyond 256 entries (search_width * degree up to 2048): the pass takes its
+// candidates in chunks of 256 (four per lane), each through the same first-time test, distance
+// computation and top-M update as a whole narrow pass.  The list after the last chunk holds the
+// itopk best of (list + all candidates of the pass), whatever the chunking, because an entry the
+// update drops is worse than itopk others and stays so.  Where the paper sorts such a candidate
+// list with a radix sort (Sec. IV-B.2), the update here keeps only the candidates that beat the
+// list's last entry (a threshold already at hand) and sorts those few.
+template <int MR, int KIND, int RIF>
+__device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t qi,
+                                                 uint32_t *table, float *qlds, uint32_t *newid,
+                                                 float *newdist, uint32_t *parents,
+                                                 uint32_t (&thi)[MR], uint32_t (&tlo)[MR], QueryStats &qs)
+{
+    constexpr int CR = 4;
+    constexpr int kChunk = CR * kWave;
+    static_assert(KIND == kTableSets || KIND == kTableReset, "single mode only");
+    const int lane = lane_id();
+    const int n_cand = P.search_width * P.degree;
+    const int table_words = P.table_words;
+    uint32_t *cursor = table + table_words;
+    const uint32_t sets = (uint32_t)table_words >> 2;
+
+    const float *q = P.queries + (size_t)qi * P.ld_queries;
+    for (int j = lane; j < P.dim; j += kWave) qlds[j] = q[j];
+    for (int j = 4 * lane; j < table_words; j += 4 * kWave)
+        *reinterpret_cast<uint4 *>(table + j) = make_uint4(kInvalidId, kInvalidId, kInvalidId, kInvalidId);
+    if (KIND == kTableSets)
+        for (int j = lane; j < (int)(sets + 3) / 4; j += kWave) cursor[j] = 0u;
+#pragma unroll
+    for (int r = 0; r < MR; ++r) { thi[r] = kDummyHi; tlo[r] = kInvalidId; }
+    const uint64_t qh = seed_query_hash(P.seed, qi);
+    __syncthreads();
+
+    uint32_t n_iter = 0, n_parent_total = 0, n_dist_total = 0, flags = 0;
+    bool overflow = false, forgot = false;
+    int lead = 0, n_par = 0;
+
+    for (int it = 0;; ++it) {
+        // sources of this pass: the random slots of step 0 (Sec. IV-A), later the parents' graph rows
+        const int n_src = it == 0 ? n_cand : n_par * P.degree;
+        auto fetch = [&](int base, uint32_t (&dst)[CR]) {
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                const int c = base + r * kWave + lane;
+                if (it == 0) {
+                    dst[r] = c < n_src ? seed_slot_id(qh, (uint64_t)c, (uint64_t)P.N) : kInvalidId;
+                } else {
+                    const int pi = c / P.degree;
+                    const bool v = c < n_src;
+                    dst[r] = v ? P.graph[(size_t)parents[v ? pi : 0] * P.degree + (c - pi * P.degree)] : kInvalidId;
+                }
+            }
+        };
+        uint32_t raw[CR], nxt[CR];
+        fetch(0, raw);
+        for (int base = 0; base < n_src; base += kChunk) {
+            // the next chunk's graph entries travel while this chunk's distances are computed
+            if (base + kChunk < n_src) fetch(base + kChunk, nxt);
+            int n_new = 0;
+            bool lost = false;
+            bool fresh[CR];
+            if constexpr (KIND == kTableSets) {
+                uint32_t set[CR], way[CR];
+#pragma unroll
+                for (int r = 0; r < CR; ++r) fresh[r] = sets_lookup(table, sets, raw[r], raw[r] != kInvalidId, set[r]);
+                lds_order();
+#pragma unroll
+                for (int r = 0; r < CR; ++r) way[r] = fresh[r] ? sets_insert(table, cursor, set[r], raw[r], forgot) : 0u;
+                lds_order();
+#pragma unroll
+                for (int r = 0; r < CR; ++r) fresh[r] = fresh[r] && sets_confirm(table, cursor, set[r], way[r], raw[r], forgot, lost);
+            }
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                bool isnew = false;
+                if constexpr (KIND == kTableSets) isnew = fresh[r];
+                else if (raw[r] != kInvalidId) isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
+                const uint64_t m = __ballot(isnew);
+                const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                if (isnew) newid[pos] = raw[r];
+                n_new += __popcll(m);
+            }
+            n_dist_total += (uint32_t)n_new;
+            __syncthreads();
+            team_distances<kElem, RIF>(P.dataset, P.ld, P.dim, P.metric, P.team_log2, newid, n_new, qlds, newdist);
+            __syncthreads();
+            uint32_t chi[CR], clo[CR];
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                const int c = r * kWave + lane;
+                const bool v = c < n_new;
+                chi[r] = v ? f32_to_ordered(newdist[c]) : kDummyHi;
+                clo[r] = v ? (newid[c] << 1) : kInvalidId;
+            }
+            update_topm<MR, CR, KIND == kTableSets>(thi, tlo, chi, clo, P.itopk, lost, forgot, newid, newdist, lane, lead);
+            __syncthreads();   // the update used newid / newdist as its staging space
+#pragma unroll
+            for (int r = 0; r < CR; ++r) raw[r] = nxt[r];
+        }
+        if (it == P.max_iterations) { flags |= 1u; break; }
+
+        if (KIND == kTableReset && P.reset_interval > 0 && it > 0 && (it % P.reset_interval) == 0) {
+            for (int j = lane; j < table_words; j += kWave) table[j] = kInvalidId;
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < MR; ++r)
+                if (tlo[r] != kInvalidId) (void)visited_insert(table, (uint32_t)table_words, tlo[r] >> 1, overflow);
+        }
+
+        // step 2: parents = first search_width entries without the flag
+        n_par = 0;
+#pragma unroll
+        for (int r = 0; r < MR; ++r) {
+            if ((r + 1) * kWave <= lead || n_par == P.search_width) continue;
+            uint64_t m = __ballot((tlo[r] & 1u) == 0u);
+            while (m != 0ull && n_par < P.search_width) {
+                const int l = __builtin_ctzll(m);
+                m &= m - 1;
+                const uint32_t w = __builtin_amdgcn_readlane(tlo[r], l);
+                if (lane == l) tlo[r] |= 1u;
+                if (lane == 0) parents[n_par] = w >> 1;
+                ++n_par;
+                lead = r * kWave + l + 1;
+            }
+        }
+        if (n_par == 0) break;
+        n_parent_total += (uint32_t)n_par;
+        ++n_iter;
+        __syncthreads();
+    }
+    if (__ballot(overflow) != 0ull) flags |= 2u;
+    qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
+}
+
 // First k of the sorted list -> ids / dists (Sec. IV-A, last sentence).
 template <int MR>
 __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
@@ -333,6 +468,35 @@ search_single_kernel(const SearchParams P)
 #ifdef CAGRA_PHASE_CLOCKS
         if (lane == 0 && qi < 131072u) g_query_times[2 * qi + 1] = wall_clock64();
 #endif
+        if (P.stats != nullptr && lane == 0) {
+            uint32_t *s = P.stats + (size_t)qi * 4;
+            s[0] = qs.n_iter; s[1] = qs.n_parent; s[2] = qs.n_dist; s[3] = qs.flags;
+        }
+        __syncthreads();
+    }
+}
+
+// Single mode with more than 256 candidates per pass (search_body_wide).
+template <int ELEM, int MR, int KIND>
+__global__ void __launch_bounds__(kWave)
+search_single_wide_kernel(const SearchParams P)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *qlds = reinterpret_cast<float *>(smem + P.off_query);
+    uint32_t *newid = reinterpret_cast<uint32_t *>(smem + P.off_newid);
+    float *newdist = reinterpret_cast<float *>(smem + P.off_newdist);
+    uint32_t *parents = reinterpret_cast<uint32_t *>(smem + P.off_parents);
+    uint32_t *table = reinterpret_cast<uint32_t *>(smem);
+    const int lane = lane_id();
+    for (;;) {
+        uint32_t qi = 0;
+        if (lane == 0) qi = atomicAdd(P.counter, 1u);
+        qi = __builtin_amdgcn_readfirstlane(qi);
+        if ((int64_t)qi >= P.B) break;
+        uint32_t thi[MR], tlo[MR];
+        QueryStats qs;
+        search_body_wide<MR, KIND, kRowsInFlight>(P, qi, table, qlds, newid, newdist, parents, thi, tlo, qs);
+        write_result<MR>(P, qi, thi, tlo);
         if (P.stats != nullptr && lane == 0) {
             uint32_t *s = P.stats + (size_t)qi * 4;
             s[0] = qs.n_iter; s[1] = qs.n_parent; s[2] = qs.n_dist; s[3] = qs.flags;
@@ -407,6 +571,17 @@ static hipError_t launch_single_one(const SearchParams &P, int grid, size_t smem
     return hipGetLastError();
 }
 
+template <int MR>
+static hipError_t launch_wide_one(const SearchParams &P, int grid, size_t smem, hipStream_t stream)
+{
+    launch_zero_counter(P.counter, stream);
+    if (P.reset_interval > 0)
+        hipLaunchKernelGGL((search_single_wide_kernel<kElem, MR, kTableReset>), dim3(grid), dim3(kWave), smem, stream, P);
+    else
+        hipLaunchKernelGGL((search_single_wide_kernel<kElem, MR, kTableSets>), dim3(grid), dim3(kWave), smem, stream, P);
+    return hipGetLastError();
+}
+
 template <int MR, int CR>
 static hipError_t launch_multi_one(const SearchParams &P, size_t smem, hipStream_t stream)
 {
@@ -442,6 +617,17 @@ hipError_t CAGRA_CAT(launch_search_single_, CAGRA_ELEM_NAME)(const SearchParams 
 hipError_t CAGRA_CAT(launch_search_multi_, CAGRA_ELEM_NAME)(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream)
 {
     CAGRA_DISPATCH(launch_multi_one, P, smem, stream)
+}
+
+hipError_t CAGRA_CAT(launch_search_wide_, CAGRA_ELEM_NAME)(const SearchParams &P, int mr, int grid, size_t smem, hipStream_t stream)
+{
+    switch (mr) {
+        case 1: return launch_wide_one<1>(P, grid, smem, stream);
+        case 2: return launch_wide_one<2>(P, grid, smem, stream);
+        case 4: return launch_wide_one<4>(P, grid, smem, stream);
+        case 8: return launch_wide_one<8>(P, grid, smem, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace cagra

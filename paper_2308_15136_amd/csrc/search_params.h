@@ -30,11 +30,12 @@ struct SearchParams {
     int32_t off_query, off_newid, off_newdist, off_parents;
 };
 
-// One launcher pair per storage type of the dataset (fp32, fp16, uint8).
+// One set of launchers per storage type of the dataset (fp32, fp16, uint8).
 #define CAGRA_DECLARE_LAUNCHERS(T)                                                                  \
     hipError_t launch_search_single_##T(const SearchParams &P, int mr, int cr, int grid, size_t smem, \
                                         hipStream_t stream);                                        \
-    hipError_t launch_search_multi_##T(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream);
+    hipError_t launch_search_multi_##T(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream); \
+    hipError_t launch_search_wide_##T(const SearchParams &P, int mr, int grid, size_t smem, hipStream_t stream);
 CAGRA_DECLARE_LAUNCHERS(f32)
 CAGRA_DECLARE_LAUNCHERS(f16)
 CAGRA_DECLARE_LAUNCHERS(u8)

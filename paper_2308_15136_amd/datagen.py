@@ -175,20 +175,21 @@ def workload(name: str, n: Optional[int] = None, n_queries: Optional[int] = None
         b = n_queries or 10_000
         base = sift_like(n, 128, 256, seed=1, stream=1)
         qs = sift_like(b, 128, 256, seed=1, stream=2)
-        return Workload(name, base, qs, L2, 64, 128, 10, (32, 48, 64, 96, 128, 192, 256))
+        return Workload(name, base, qs, L2, 64, 128, 10, (10, 12, 16, 20, 24, 32, 48, 64, 96, 128, 192, 256),
+                        search_widths=(1, 2, 4, 5, 6, 7, 8, 10, 12))
     if name == "deep1m":        # large batch, lower dim: 1M x 96 unit norm
         n = n or 1_000_000
         b = n_queries or 10_000
         base = unit_mixture(n, 96, 1024, 40, 1.5, 0.1, seed=2, stream=1)
         qs = unit_mixture(b, 96, 1024, 40, 1.5, 0.1, seed=2, stream=2)
-        return Workload(name, base, qs, L2, 32, 64, 10, (64, 128, 256, 512))
+        return Workload(name, base, qs, L2, 32, 64, 10, (16, 32, 64, 128, 256, 512), search_widths=(1, 2, 4, 8, 16, 32))
     if name == "glove200":      # angular, higher dim: 1,183,514 x 200, inner product
         n = n or 1_183_514
         b = n_queries or 10_000
         kw = dict(seed=3, log_var_range=(0.1, 10.0))
         base = unit_mixture(n, 200, 2000, 128, 1.5, 0.1, stream=1, **kw)
         qs = unit_mixture(b, 200, 2000, 128, 1.5, 0.1, stream=2, **kw)
-        return Workload(name, base, qs, IP, 64, 128, 10, (128, 256, 512))
+        return Workload(name, base, qs, IP, 64, 128, 10, (32, 64, 128, 256, 512), search_widths=(1, 2, 4, 8, 16))
     if name == "deep10m":       # small batch / scale: 10M x 96 unit norm
         n = n or 10_000_000
         b = n_queries or 1_000

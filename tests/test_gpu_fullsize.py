@@ -53,8 +53,9 @@ def test_large_batch_workload_at_full_size():
 
     # search: whole batch on the GPU, a sample of it on the oracle (integer data: bit-exact)
     print("  search", flush=True)
-    # (search_width, itopk): the point bench.py times (4, 48), and the one-parent search at the same recall
-    for width, itopk in ((4, 48), (1, 128)):
+    # (search_width, itopk): the points bench.py's sweep ends on at recall 0.95 with passes of 384 and 512
+    # candidates (taken in chunks of 256), the best with at most 256 candidates, and the one-parent search
+    for width, itopk in ((6, 20), (8, 10), (4, 48), (1, 128)):
         print(f"    search_width {width} itopk {itopk}", flush=True)
         opts = cagra.SearchOptions(seed=20230815, mode=1)
         ids, dists, st = cagra.search(graph, base, queries, w.k, itopk, width, w.metric, opts, return_stats=True)
@@ -82,8 +83,8 @@ def test_large_batch_workload_at_full_size():
 
 
 @pytest.mark.parametrize("name,cases", [
-    ("deep1m", ((10, 128, 1), (100, 256, 1), (10, 64, 4))),      # 1M x 96 unit-norm rows, L2, degree 32
-    ("glove200", ((10, 256, 1), (10, 128, 2))),                   # 1,183,514 x 200 unit-norm rows, inner product
+    ("deep1m", ((10, 128, 1), (100, 256, 1), (10, 64, 4), (10, 32, 16))),   # 1M x 96 unit-norm rows, L2, degree 32
+    ("glove200", ((10, 256, 1), (10, 128, 2), (10, 64, 8))),                 # 1,183,514 x 200 unit-norm rows, inner product
 ])
 def test_float_workloads_at_full_size(name, cases):
     """The lower-dimensional and the inner-product configuration at their full sizes: whole batch on

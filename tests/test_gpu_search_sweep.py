@@ -87,3 +87,60 @@ def test_sweep(cagra, i, dim, degree, width, itopk, k, storage, policy, entries,
     st = st.cpu().numpy().view(np.uint32)
     np.testing.assert_array_equal(st[:, :2], r_st[:, :2])
     assert np.all(st[:, 2] >= r_st[:, 2]) and not np.any(st[:, 3] & 2)
+
+
+# More than 256 candidates per pass (Sec. IV-B.2's large candidate lists): the pass takes them in chunks.
+# Ragged last chunks, degrees that do not divide the chunk, both table policies, tables far too small.
+_WIDE = [
+    # dim, degree, width, itopk, k, storage, policy, entries
+    (32, 64, 5, 64, 10, "f32", 0, 0),          # 320
+    (48, 96, 5, 128, 10, "f16", 1, 0),         # 480, periodic reset
+    (16, 48, 11, 200, 200, "u8", 2, 1024),     # 528, table much smaller than two passes
+    (128, 64, 16, 512, 10, "f32", 0, 0),       # 1024
+    (32, 32, 64, 256, 100, "f32", 2, 0),       # 2048, the most parents per pass
+    (64, 128, 16, 100, 10, "f32", 1, 8192),    # 2048, periodic reset every pass or two
+    (32, 24, 40, 33, 7, "f32", 0, 256),        # 960 candidates into a 256-entry table
+    (96, 256, 8, 512, 512, "f16", 0, 0),       # 2048 from the largest degree, k = itopk
+]
+
+_wide_built = {}
+
+
+def _wide_index(dim, degree):
+    key = (dim, degree)
+    if key not in _wide_built:
+        base = datagen.sift_like(8000, dim, 12, seed=300 + dim, stream=1, rank=min(64, dim))
+        queries = datagen.sift_like(48, dim, 12, seed=300 + dim, stream=2)
+        _wide_built[key] = (base, queries, oracle.build(base, degree, 2 * degree))
+    return _wide_built[key]
+
+
+@pytest.mark.parametrize("dim,degree,width,itopk,k,storage,policy,entries", _WIDE)
+def test_wide_passes(cagra, dim, degree, width, itopk, k, storage, policy, entries):
+    import torch
+    print(f"case wide: dim={dim} d={degree} p={width} M={itopk} k={k} {storage} policy={policy} entries={entries}",
+          flush=True)
+    base, queries, g = _wide_index(dim, degree)
+    dev_base = torch.from_numpy(base).cuda()
+    data = dev_base if storage == "f32" else cagra.convert_dataset(dev_base, cagra.F16 if storage == "f16" else cagra.U8)
+    opts = cagra.SearchOptions(seed=77, mode=1, table_policy=policy, table_entries=entries)
+    ids, dists, st = cagra.search(torch.from_numpy(g.view(np.int32)).cuda(), data, torch.from_numpy(queries).cuda(),
+                                  k, itopk, width, cagra.L2, opts, return_stats=True)
+    r_ids, r_d, r_st = oracle.search(g, base, queries, k, itopk, width, oracle.L2, seed=77, return_stats=True)
+    np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), r_ids)
+    np.testing.assert_array_equal(dists.cpu().numpy(), r_d)
+    st = st.cpu().numpy().view(np.uint32)
+    np.testing.assert_array_equal(st[:, :2], r_st[:, :2])
+    assert np.all(st[:, 2] >= r_st[:, 2]) and not np.any(st[:, 3] & 2)
+
+
+def test_wide_limits(cagra):
+    import torch
+    base, queries, g = _wide_index(32, 64)
+    gd, bd, qd = torch.from_numpy(g.view(np.int32)).cuda(), torch.from_numpy(base).cuda(), torch.from_numpy(queries).cuda()
+    one = cagra.SearchOptions(mode=1)
+    with pytest.raises(cagra.CagraError):
+        cagra.search(gd, bd, qd, 10, 64, 33, cagra.L2, one)        # 2112 candidates
+    with pytest.raises(cagra.CagraError):
+        cagra.search(gd[:, :16].contiguous(), bd, qd, 10, 128, 65, cagra.L2, one)   # 65 parents
+    torch.cuda.synchronize()
