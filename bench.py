@@ -81,6 +81,7 @@ def main() -> int:
     ap.add_argument("--full-sweep", action="store_true",
                     help="per search_width go on beyond the first itopk that reaches the recall target")
     ap.add_argument("--cpu-sample", type=int, default=10000, help="queries given to the CPU oracle")
+    ap.add_argument("--no-short", action="store_true", help="skip the sweep of lists shorter than the named itopk range")
     ap.add_argument("--no-latency", action="store_true", help="skip the small-batch (multi mode) latency part")
     ap.add_argument("--latency-workers", type=int, default=8, help="workgroups per query in the latency part")
     ap.add_argument("--latency-itopk", type=int, default=128)
@@ -205,22 +206,28 @@ def main() -> int:
     sweep_list = (args.itopk,) if args.itopk else w.itopk
     best = None
     interpolated = []
+
+    def sweep_point(M, p):
+        wall_ms, dev_ms = timed(M, p, 5, 2)
+        rec = recall_at_k(ids.cpu().numpy().view(np.uint32), gt_np)
+        ab = algorithmic_bytes(stats.cpu().numpy().view(np.uint32), dim, w.degree, w.k)
+        pt = {"search_width": p, "itopk": M, "recall": round(rec, 5), "qps": round(B / (wall_ms * 1e-3), 1),
+              "kernel_ms": round(dev_ms, 4),
+              "vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
+              "iterations": round(ab["iterations_mean"], 2),
+              "n_dist_per_query": round(ab["n_dist"] / B, 1)}
+        log(f"[bench] width {p} itopk {M}: recall@{w.k} {rec:.4f}  {pt['qps']:.0f} QPS  "
+            f"{pt['vector_GBs']:.0f} GB/s gathered")
+        return pt
+
     for p in widths:
         prev = None
         for M in sweep_list:
             if M < w.k or p * w.degree > 2048:
                 continue
-            wall_ms, dev_ms = timed(M, p, 5, 2)
-            rec = recall_at_k(ids.cpu().numpy().view(np.uint32), gt_np)
-            ab = algorithmic_bytes(stats.cpu().numpy().view(np.uint32), dim, w.degree, w.k)
-            pt = {"search_width": p, "itopk": M, "recall": round(rec, 5), "qps": round(B / (wall_ms * 1e-3), 1),
-                  "kernel_ms": round(dev_ms, 4),
-                  "vector_GBs": round(ab["vector_bytes"] / (dev_ms * 1e-3) / 1e9, 1),
-                  "iterations": round(ab["iterations_mean"], 2),
-                  "n_dist_per_query": round(ab["n_dist"] / B, 1)}
+            pt = sweep_point(M, p)
+            rec = pt["recall"]
             sweep.append(pt)
-            log(f"[bench] width {p} itopk {M}: recall@{w.k} {rec:.4f}  {pt['qps']:.0f} QPS  "
-                f"{pt['vector_GBs']:.0f} GB/s gathered")
             if rec >= TARGET_RECALL:
                 if best is None or pt["qps"] > best["qps"]:
                     best = pt
@@ -269,6 +276,27 @@ def main() -> int:
                      "queries_stopped_by_cap": ab["hit_cap"]},
         "sweep": sweep,
     }
+
+    # ---- lists shorter than the itopk range the benchmark configuration names, with wider passes: reported
+    #      beside the headline, never as `value` ------------------------------------------------------
+    short = w.extra.get("short_itopk") if not (args.itopk or args.width or args.no_short) else None
+    if short:
+        pts, best_short = [], None
+        for p in (5, 6, 7, 8, 10, 12):
+            for M_s in short:
+                if M_s < w.k or p * w.degree > 2048:
+                    continue
+                pt = sweep_point(M_s, p)
+                pts.append(pt)
+                if pt["recall"] >= TARGET_RECALL:
+                    if best_short is None or pt["qps"] > best_short["qps"]:
+                        best_short = pt
+                    break
+        run(M, P_WIDTH)                      # the shared result buffers hold the timed configuration again
+        torch.cuda.synchronize()
+        out["short_lists"] = {"note": f"itopk below {min(w.itopk)} (outside the sweep range of the benchmark configuration), "
+                                      "search_width 5..12; 5 timed launches per point",
+                              "best_at_target_recall": best_short, "sweep": pts}
 
     # ---- the same search on larger batches (the queries repeated; a query's seeds depend on its index
     #      in the batch, so the copies walk different paths): how much of the 10,000-query time is the

@@ -66,6 +66,11 @@ __device__ __forceinline__ bool visited_resolve_global(uint32_t *table, int bits
 #endif
 constexpr int kRowsInFlight = CAGRA_ROWS_IN_FLIGHT;
 constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, registers do not
+// Wide passes of fp32 rows: the kernel is bound to 8 wavefronts per CU by its LDS, which leaves each
+// wavefront 256 VGPRs, enough for eight rows in flight (measured 1 to 2 % faster).  Not with the
+// longest lists or the narrow storage types, where eight rows would halve the wavefronts per CU.
+template <int ELEM, int MR>
+constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= 4) ? 8 : kRowsInFlight; }
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
@@ -301,6 +306,7 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
     uint32_t *cursor = table + table_words;
     const uint32_t sets = (uint32_t)table_words >> 2;
 
+    CAGRA_PHASE_BEGIN()
     const float *q = P.queries + (size_t)qi * P.ld_queries;
     for (int j = lane; j < P.dim; j += kWave) qlds[j] = q[j];
     for (int j = 4 * lane; j < table_words; j += 4 * kWave)
@@ -316,6 +322,7 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
     bool overflow = false, forgot = false;
     int lead = 0, n_par = 0;
 
+    CAGRA_PHASE(0)
     for (int it = 0;; ++it) {
         // sources of this pass: the random slots of step 0 (Sec. IV-A), later the parents' graph rows
         const int n_src = it == 0 ? n_cand : n_par * P.degree;
@@ -364,8 +371,10 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
             }
             n_dist_total += (uint32_t)n_new;
             __syncthreads();
+            CAGRA_PHASE(1)
             team_distances<kElem, RIF>(P.dataset, P.ld, P.dim, P.metric, P.team_log2, newid, n_new, qlds, newdist);
             __syncthreads();
+            CAGRA_PHASE(2)
             uint32_t chi[CR], clo[CR];
 #pragma unroll
             for (int r = 0; r < CR; ++r) {
@@ -378,6 +387,7 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
             __syncthreads();   // the update used newid / newdist as its staging space
 #pragma unroll
             for (int r = 0; r < CR; ++r) raw[r] = nxt[r];
+            CAGRA_PHASE(3)
         }
         if (it == P.max_iterations) { flags |= 1u; break; }
 
@@ -409,7 +419,9 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
         n_parent_total += (uint32_t)n_par;
         ++n_iter;
         __syncthreads();
+        CAGRA_PHASE(5)
     }
+    CAGRA_PHASE_END()
     if (__ballot(overflow) != 0ull) flags |= 2u;
     qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
 }
@@ -495,8 +507,14 @@ search_single_wide_kernel(const SearchParams P)
         if ((int64_t)qi >= P.B) break;
         uint32_t thi[MR], tlo[MR];
         QueryStats qs;
-        search_body_wide<MR, KIND, kRowsInFlight>(P, qi, table, qlds, newid, newdist, parents, thi, tlo, qs);
+#ifdef CAGRA_PHASE_CLOCKS
+        if (lane == 0 && qi < 131072u) g_query_times[2 * qi] = wall_clock64();
+#endif
+        search_body_wide<MR, KIND, rows_in_flight_wide<ELEM, MR>()>(P, qi, table, qlds, newid, newdist, parents, thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
+#ifdef CAGRA_PHASE_CLOCKS
+        if (lane == 0 && qi < 131072u) g_query_times[2 * qi + 1] = wall_clock64();
+#endif
         if (P.stats != nullptr && lane == 0) {
             uint32_t *s = P.stats + (size_t)qi * 4;
             s[0] = qs.n_iter; s[1] = qs.n_parent; s[2] = qs.n_dist; s[3] = qs.flags;

@@ -53,9 +53,9 @@ def test_large_batch_workload_at_full_size():
 
     # search: whole batch on the GPU, a sample of it on the oracle (integer data: bit-exact)
     print("  search", flush=True)
-    # (search_width, itopk): the points bench.py's sweep ends on at recall 0.95 with passes of 384 and 512
-    # candidates (taken in chunks of 256), the best with at most 256 candidates, and the one-parent search
-    for width, itopk in ((6, 20), (8, 10), (4, 48), (1, 128)):
+    # (search_width, itopk): the point bench.py times (320 candidates per pass, taken in chunks of 256), two of
+    # its short-list points (448 and 512 candidates), the best with at most 256 candidates, the one-parent search
+    for width, itopk in ((5, 32), (7, 16), (8, 10), (4, 48), (1, 128)):
         print(f"    search_width {width} itopk {itopk}", flush=True)
         opts = cagra.SearchOptions(seed=20230815, mode=1)
         ids, dists, st = cagra.search(graph, base, queries, w.k, itopk, width, w.metric, opts, return_stats=True)
