@@ -168,6 +168,31 @@ int cagra_exact_search(const float *dataset, int64_t N, int32_t dim, int64_t ld,
 
 size_t cagra_exact_search_workspace_bytes(int64_t N, int64_t B, int32_t k);
 
+/* How the exhaustive search does its arithmetic; the result is the same bit for bit. */
+typedef enum {
+    CAGRA_EXACT_AUTO = 0,      /* filtered for N >= 131072, else plain */
+    CAGRA_EXACT_PLAIN = 1,     /* every distance by the fused multiply-add chain on the vector units */
+    CAGRA_EXACT_FILTERED = 2   /* approximate distances from fp16 copies on the matrix cores (MFMA) pick a few
+                                  thousand candidates per query, the chain ranks those; a block of query rows for
+                                  which that cannot be shown to give the exact answer (the candidate buffer
+                                  overflowed, or fewer than k candidates lie below the filter threshold) is done
+                                  again by the plain kernels inside the same call.  N >= 4096 */
+} cagra_exact_algo;
+
+/* cagra_exact_search with the choice of algorithm (cagra_exact_search itself is the plain one).  The
+ * filtered algorithm keeps fp16 copies of dataset and queries in the workspace, hence `dim` in its size;
+ * queries == dataset with equal strides is recognised and copied once.  blocks_redone_out (device, may be
+ * NULL) receives the number of blocks of 2048 query rows that the plain kernels had to do again (0 with
+ * the plain algorithm). */
+int cagra_exact_search_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                          const float *queries, int64_t B, int64_t ld_queries,
+                          int32_t k, int32_t exclude_self, int64_t self_offset, cagra_exact_algo algo,
+                          uint32_t *ids_out, float *dists_out /* may be NULL */,
+                          uint32_t *blocks_redone_out /* device, may be NULL */,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+size_t cagra_exact_search_ex_workspace_bytes(int64_t N, int32_t dim, int64_t B, int32_t k, cagra_exact_algo algo);
+
 /* ---- graph construction (Sec. III-B) -------------------------------------------------------- */
 
 /*
@@ -248,6 +273,8 @@ typedef struct {
     int32_t nnd_rounds;     /* NN-descent: rounds, 0 or < 0 automatic */
     int32_t nnd_sample;     /* NN-descent: sample, 0 automatic */
     uint64_t seed;          /* NN-descent: seed of round 0 */
+    int32_t exact_algo;     /* exact initial graph: a cagra_exact_algo */
+    int32_t reserved;       /* 0 */
 } cagra_build_opts;
 
 /* cagra_build with choices (opts may be NULL).  The initial graph, and for the distance-based

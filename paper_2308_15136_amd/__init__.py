@@ -28,6 +28,9 @@ F16 = 1
 U8 = 2
 REORDER_RANK = 0
 REORDER_DISTANCE = 1
+EXACT_AUTO = 0
+EXACT_PLAIN = 1
+EXACT_FILTERED = 2
 INVALID_ID = -1  # 0xFFFFFFFF seen through int32
 
 _lib = None
@@ -47,7 +50,7 @@ class _SearchOpts(C.Structure):
 
 class _BuildOpts(C.Structure):
     _fields_ = [("reorder", C.c_int32), ("initial_graph", C.c_int32), ("nnd_rounds", C.c_int32),
-                ("nnd_sample", C.c_int32), ("seed", C.c_uint64)]
+                ("nnd_sample", C.c_int32), ("seed", C.c_uint64), ("exact_algo", C.c_int32), ("reserved", C.c_int32)]
 
 
 class _SearchPlan(C.Structure):
@@ -87,6 +90,11 @@ def load_library():
                                        vp, vp, vp, sz, vp]
     lib.cagra_exact_search_workspace_bytes.restype = sz
     lib.cagra_exact_search_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.cagra_exact_search_ex.restype = C.c_int
+    lib.cagra_exact_search_ex.argtypes = [vp, i64, i32, i64, C.c_int, vp, i64, i64, i32, i32, i64, C.c_int,
+                                          vp, vp, vp, vp, sz, vp]
+    lib.cagra_exact_search_ex_workspace_bytes.restype = sz
+    lib.cagra_exact_search_ex_workspace_bytes.argtypes = [i64, i32, i64, i32, C.c_int]
     lib.cagra_build.restype = C.c_int
     lib.cagra_build.argtypes = [vp, i64, i32, i64, C.c_int, i32, i32, vp, vp, sz, vp]
     lib.cagra_build_workspace_bytes.restype = sz
@@ -331,8 +339,11 @@ class PreparedSearch:
 
 
 def exact_search(dataset, queries, k: int, metric: int = L2, exclude_self: bool = False,
-                 self_offset: int = 0, return_dists: bool = True):
-    """Exhaustive k nearest neighbours (Eq. 1): (ids[B, k] int32, dists[B, k] float32)."""
+                 self_offset: int = 0, return_dists: bool = True, algo: int = EXACT_AUTO, blocks_redone=None):
+    """Exhaustive k nearest neighbours (Eq. 1): (ids[B, k] int32, dists[B, k] float32).  algo: EXACT_PLAIN,
+    EXACT_FILTERED (matrix-core filter in front of the exact arithmetic, same result) or EXACT_AUTO.
+    blocks_redone: optional int32 tensor of one element that receives how many blocks of query rows the
+    filtered algorithm had to hand to the plain kernels."""
     torch = _torch()
     lib = load_library()
     dataset = _dev_f32(dataset, "dataset")
@@ -341,27 +352,29 @@ def exact_search(dataset, queries, k: int, metric: int = L2, exclude_self: bool 
     B, N = queries.shape[0], dataset.shape[0]
     ids = torch.empty((B, k), dtype=torch.int32, device=dev)
     dists = torch.empty((B, k), dtype=torch.float32, device=dev) if return_dists else None
-    ws = _workspace(lib.cagra_exact_search_workspace_bytes(N, B, k), dev)
-    rc = lib.cagra_exact_search(dataset.data_ptr(), N, dataset.shape[1], dataset.stride(0), metric,
-                                queries.data_ptr(), B, queries.stride(0), k, int(exclude_self),
-                                self_offset, ids.data_ptr(),
-                                dists.data_ptr() if dists is not None else None,
-                                ws.data_ptr(), ws.numel(), _stream(dev))
-    _check(rc, "cagra_exact_search")
+    ws = _workspace(lib.cagra_exact_search_ex_workspace_bytes(N, dataset.shape[1], B, k, algo), dev)
+    rc = lib.cagra_exact_search_ex(dataset.data_ptr(), N, dataset.shape[1], dataset.stride(0), metric,
+                                   queries.data_ptr(), B, queries.stride(0), k, int(exclude_self),
+                                   self_offset, algo, ids.data_ptr(),
+                                   dists.data_ptr() if dists is not None else None,
+                                   blocks_redone.data_ptr() if blocks_redone is not None else None,
+                                   ws.data_ptr(), ws.numel(), _stream(dev))
+    _check(rc, "cagra_exact_search_ex")
     return (ids, dists) if return_dists else ids
 
 
 def build(dataset, degree: int, init_degree: int = 0, metric: int = L2, reorder: int = REORDER_RANK,
-          nn_descent: bool = False, nnd_rounds: int = 0, nnd_sample: int = 0, seed: int = 0):
+          nn_descent: bool = False, nnd_rounds: int = 0, nnd_sample: int = 0, seed: int = 0,
+          exact_algo: int = EXACT_AUTO):
     """dataset[N, dim] -> CAGRA graph[N, degree] (int32 tensor).  nn_descent: initial graph by
-    NN-descent instead of the exhaustive search."""
+    NN-descent instead of the exhaustive search; exact_algo: how the exhaustive search computes."""
     torch = _torch()
     lib = load_library()
     dataset = _dev_f32(dataset, "dataset")
     dev = dataset.device
     N, dim = dataset.shape
     graph = torch.empty((N, degree), dtype=torch.int32, device=dev)
-    bo = _BuildOpts(reorder, 1 if nn_descent else 0, nnd_rounds, nnd_sample, seed)
+    bo = _BuildOpts(reorder, 1 if nn_descent else 0, nnd_rounds, nnd_sample, seed, exact_algo, 0)
     ws = _workspace(lib.cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, C.byref(bo)), dev)
     rc = lib.cagra_build_ex(dataset.data_ptr(), N, dim, dataset.stride(0), metric, degree, init_degree, C.byref(bo),
                             graph.data_ptr(), ws.data_ptr(), ws.numel(), _stream(dev))

@@ -107,6 +107,63 @@ int cagra_exact_search(const float *dataset, int64_t N, int32_t dim, int64_t ld,
     return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
 }
 
+// The algorithm a request resolves to: 1 plain, 2 filtered; 0 for an unusable request.
+static int resolve_exact_algo(int algo, int64_t N)
+{
+    if (algo == CAGRA_EXACT_AUTO) return N >= 131072 ? CAGRA_EXACT_FILTERED : CAGRA_EXACT_PLAIN;
+    if (algo == CAGRA_EXACT_PLAIN) return CAGRA_EXACT_PLAIN;
+    if (algo == CAGRA_EXACT_FILTERED && N >= 4096) return CAGRA_EXACT_FILTERED;
+    return 0;
+}
+
+size_t cagra_exact_search_ex_workspace_bytes(int64_t N, int32_t dim, int64_t B, int32_t k, cagra_exact_algo algo)
+{
+    const size_t plain = cagra_exact_search_workspace_bytes(N, B, k);
+    if (N < 1 || B < 1 || k < 1 || dim < 1 || resolve_exact_algo((int)algo, N) != CAGRA_EXACT_FILTERED) return plain;
+    // sized for distinct queries; a call with queries == dataset needs less and accepts this too
+    return plain + plan_exact_filter(N, dim, B, k, false).bytes;
+}
+
+int cagra_exact_search_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cagra_metric metric,
+                          const float *queries, int64_t B, int64_t ld_queries, int32_t k,
+                          int32_t exclude_self, int64_t self_offset, cagra_exact_algo algo, uint32_t *ids_out,
+                          float *dists_out, uint32_t *blocks_redone_out, void *workspace, size_t workspace_bytes,
+                          void *hip_stream)
+{
+    if (N < 1) return CAGRA_ERR_BAD_SHAPE;
+    const int resolved = resolve_exact_algo((int)algo, N);
+    if (resolved == 0) return CAGRA_ERR_BAD_OPTION;
+    if (resolved == CAGRA_EXACT_PLAIN) {
+        int rc = cagra_exact_search(dataset, N, dim, ld, metric, queries, B, ld_queries, k, exclude_self, self_offset,
+                                    ids_out, dists_out, workspace, workspace_bytes, hip_stream);
+        if (rc == CAGRA_OK && blocks_redone_out != nullptr) {
+            launch_fill_u32(blocks_redone_out, 1, 0u, static_cast<hipStream_t>(hip_stream));
+            if (hipGetLastError() != hipSuccess) rc = CAGRA_ERR_LAUNCH;
+        }
+        return rc;
+    }
+    if (!dataset) return CAGRA_ERR_NULL_POINTER;
+    if (B > 0 && (!queries || !ids_out)) return CAGRA_ERR_NULL_POINTER;
+    int rc = check_matrix(dataset, N, dim, ld);
+    if (rc == CAGRA_OK) rc = check_matrix(queries, B, dim, ld_queries);
+    if (rc != CAGRA_OK) return rc;
+    if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
+    if (k < 1 || k > 512 || k > N) return CAGRA_ERR_BAD_TOPK;
+    if (exclude_self && (self_offset < 0 || self_offset + B > N)) return CAGRA_ERR_BAD_SHAPE;
+    if (B == 0) return CAGRA_OK;
+    const bool share = queries == dataset && ld_queries == ld && B <= N;
+    const size_t plain = cagra_exact_search_workspace_bytes(N, B, k);
+    const FilterPlan pl = plan_exact_filter(N, dim, B, k, share);
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < plain + pl.bytes)
+        return CAGRA_ERR_WORKSPACE;
+    hipError_t e = launch_exact_filter(dataset, N, dim, ld, (int)metric, queries, B, ld_queries, k,
+                                       exclude_self ? 1 : 0, self_offset, ids_out, dists_out,
+                                       static_cast<float *>(workspace), exact_block_rows(N, B),
+                                       static_cast<unsigned char *>(workspace) + plain, pl, share, blocks_redone_out,
+                                       static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+}
+
 size_t cagra_optimize_workspace_bytes(int64_t N, int32_t init_degree, int32_t degree)
 {
     (void)init_degree;
@@ -157,7 +214,6 @@ static int nnd_sample_of(const cagra_build_opts &o, int init_degree)
 size_t cagra_build_ex_workspace_bytes(int64_t N, int32_t dim, int32_t degree, int32_t init_degree,
                                       const cagra_build_opts *opts)
 {
-    (void)dim;
     cagra_build_opts o = {};
     if (opts) o = *opts;
     if (init_degree == 0) init_degree = 2 * degree;
@@ -168,7 +224,8 @@ size_t cagra_build_ex_workspace_bytes(int64_t N, int32_t dim, int32_t degree, in
     // the scratch of the first stage is dead once the k-NN graph exists, so the optimisation reuses its space
     const size_t first = o.initial_graph == 1
                              ? nn_descent_workspace_bytes(N, init_degree, nnd_sample_of(o, init_degree))
-                             : cagra_exact_search_workspace_bytes(N, N, init_degree);
+                             : cagra_exact_search_ex_workspace_bytes(N, dim, N, init_degree,
+                                                                     (cagra_exact_algo)o.exact_algo);
     return knn + std::max(first, cagra_optimize_workspace_bytes(N, init_degree, degree));
 }
 
@@ -189,6 +246,7 @@ int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cag
     if (init_degree == 0) init_degree = 2 * degree;
     if (o.reorder != CAGRA_REORDER_RANK && o.reorder != CAGRA_REORDER_DISTANCE) return CAGRA_ERR_BAD_OPTION;
     if (o.initial_graph != 0 && o.initial_graph != 1) return CAGRA_ERR_BAD_OPTION;
+    if (o.initial_graph == 0 && resolve_exact_algo(o.exact_algo, N) == 0) return CAGRA_ERR_BAD_OPTION;
     if (!dataset || !graph_out) return CAGRA_ERR_NULL_POINTER;
     if (N < 2) return CAGRA_ERR_BAD_SHAPE;
     int rc = check_matrix(dataset, N, dim, ld);
@@ -216,6 +274,11 @@ int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cag
         const int rounds = o.nnd_rounds <= 0 ? nn_descent_auto_rounds(N) : o.nnd_rounds;
         e = launch_nn_descent(dataset, N, dim, ld, (int)metric, init_degree, rounds, sample, o.seed, knn, knn_dists,
                               rest, stream);
+    } else if (resolve_exact_algo(o.exact_algo, N) == CAGRA_EXACT_FILTERED) {
+        const FilterPlan pl = plan_exact_filter(N, dim, N, init_degree, true);
+        e = launch_exact_filter(dataset, N, dim, ld, (int)metric, dataset, N, ld, init_degree, 1, 0, knn, knn_dists,
+                                reinterpret_cast<float *>(rest), exact_block_rows(N, N),
+                                rest + cagra_exact_search_workspace_bytes(N, N, init_degree), pl, true, nullptr, stream);
     } else {
         e = launch_exact_search(dataset, N, dim, ld, (int)metric, dataset, N, ld, init_degree, 1, 0,
                                 knn, knn_dists, reinterpret_cast<float *>(rest), exact_block_rows(N, N), stream);

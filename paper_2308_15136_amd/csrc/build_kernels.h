@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stddef.h>
 
 namespace cagra {
 
@@ -11,6 +12,32 @@ hipError_t launch_exact_search(const float *X, int64_t N, int dim, int64_t ldX, 
                                const float *Q, int64_t B, int64_t ldQ, int k, int exclude_self,
                                int64_t self_offset, uint32_t *ids, float *dists, float *scratch,
                                int64_t block_rows, hipStream_t stream);
+
+// The same for query rows row_begin .. row_end only; with a gate (device) every kernel of it returns at
+// once unless *gate != 0.
+hipError_t launch_exact_search_gated(const float *X, int64_t N, int dim, int64_t ldX, int metric,
+                                     const float *Q, int64_t row_end, int64_t ldQ, int64_t row_begin, int k,
+                                     int exclude_self, int64_t self_offset, uint32_t *ids, float *dists,
+                                     float *scratch, int64_t block_rows, const uint32_t *gate, hipStream_t stream);
+// k smallest (value, column) of every row of a dense block D[rows, pitch]
+void launch_row_select(const float *D, int64_t pitch, int64_t rows, int k, uint32_t *ids_out, float *best_d,
+                       hipStream_t stream);
+
+// Exhaustive search with an fp16 matrix-core filter in front of the exact arithmetic
+// (exact_filter.hip); same results as launch_exact_search.  `extra` holds plan.bytes.
+constexpr int kFilterCap = 4096;   // candidates kept per query row
+struct FilterPlan {
+    int dimP, t;
+    int64_t block_rows, stride, n_sample, sample_pitch, n_blocks;
+    size_t off_x16, off_nx, off_q16, off_nq, off_max, off_thr_ids, off_thr_d, off_count, off_buf, off_flags, bytes;
+};
+void launch_fill_u32(uint32_t *p, int64_t n, uint32_t value, hipStream_t stream);   // p[0..n) = value
+FilterPlan plan_exact_filter(int64_t N, int dim, int64_t B, int k, bool share_queries);
+hipError_t launch_exact_filter(const float *X, int64_t N, int dim, int64_t ldX, int metric, const float *Q,
+                               int64_t B, int64_t ldQ, int k, int exclude_self, int64_t self_offset, uint32_t *ids,
+                               float *dists, float *plain_scratch, int64_t plain_block_rows, void *extra,
+                               const FilterPlan &plan, bool share_queries, uint32_t *blocks_redone /* device, may be null */,
+                               hipStream_t stream);
 
 struct OptimizeScratch {
     uint32_t *indeg;      // [N]

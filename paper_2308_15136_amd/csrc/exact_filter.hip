@@ -1,0 +1,431 @@
+// Exhaustive k-nearest-neighbour search (Eq. 1) with the bulk of the arithmetic on the matrix
+// cores, and the result still that of the plain path bit for bit.
+//
+// The distance matrix of a block of query rows against the dataset is a dense contraction, the one
+// place in this library where MFMA applies.  An fp16 product does not round like the sequential
+// fp32 chain that defines the result, so it only *filters*:
+//   1. the dataset (and the queries) are copied once as fp16, scaled by a power of two so that
+//      the largest magnitude lies in [2^13, 2^14), together with their squared norms in fp32;
+//   2. per block of query rows, approximate distances to every `stride`-th dataset row give a
+//      per-row threshold tau (the t-th smallest of the sample, so that about t * stride dataset
+//      rows lie below it);
+//   3. the filter kernel forms approximate distances to all dataset rows tile by tile
+//      (v_mfma_f32_32x32x8_f16) and appends the ids with  approx <= tau + eps  to the row's
+//      candidate buffer, eps bounding |approx - exact| for the pair;
+//   4. the re-rank kernel computes the exact distance (the same fused multiply-add chain as the
+//      plain path) of every buffered candidate and sorts by (distance, id).  Every dataset row
+//      whose exact distance is <= tau is in the buffer (by the choice of eps), so if the buffer
+//      did not overflow and holds at least k entries with exact distance <= tau, its first k
+//      are the global first k.  Otherwise the row raises its block's flag;
+//   5. a block whose flag is up is done again by the plain kernels (they are always enqueued
+//      and return at once when the flag is down), so the call stays asynchronous and exact
+//      whatever the data: duplicates in their thousands or an unlucky sample only cost time.
+//
+// Bound used for eps (u = 2^-24; x~, q~ the fp16 copies; g = |x| |q|, S = |x|^2 + |q|^2):
+//   fp16 rounding of both operands: |x~.q~ - x.q| <= (2^-10 + 2^-22) sum|x_i q_i| <= 2^-10 * 1.001 * g
+//   (scaled values below the fp16 normal range add at most dim * 2^-38 * g);
+//   fp32 accumulation inside the MFMA (rounded or truncated), of the norms, the final additions, and the
+//   rounding of the exact chain itself: together <= (5 dim + 9) u S for squared L2, <= (3 dim + 4) u g for
+//   the inner product.
+//   squared L2 (the product enters twice):  eps = 2 * 1.01 * 2^-10 * g + (8 dim + 32) u * S
+//   inner product:                          eps = 2 * (1.01 * 2^-10 + (8 dim + 32) u) * g   (twice what is needed)
+// g rather than S in the leading term keeps the filter sharp when queries and dataset rows differ
+// much in norm.
+#include <algorithm>
+#include "device_util.h"
+#include "build_kernels.h"
+
+namespace cagra {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kFT = 128;          // output tile edge (4 wavefronts, 64 x 64 each)
+constexpr int kFK = 32;           // dimensions staged per step
+constexpr int kFRow = kFK + 8;    // halfs per staged row in LDS (80 bytes: 16-byte aligned, banks spread)
+constexpr int kCap = kFilterCap;  // candidate buffer entries per query row
+
+// ---- step 1: fp16 copy and norms ------------------------------------------------------------
+
+// Largest |x| of a matrix as the bit pattern of a non-negative float (ordered like the value).
+__global__ void __launch_bounds__(256)
+maxabs_kernel(const float *__restrict__ X, int64_t rows, int dim, int64_t ld, uint32_t *out)
+{
+    uint32_t m = 0;
+    const int64_t total = rows * dim;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / dim;
+        const uint32_t b = __float_as_uint(X[r * ld + (i - r * dim)]) & 0x7FFFFFFFu;
+        m = b > m ? b : m;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const uint32_t v = (uint32_t)__shfl_xor((int)m, o);
+        m = v > m ? v : m;
+    }
+    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(out, m);
+}
+
+// Power of two that brings a largest magnitude with the given bits into [2^13, 2^14).
+__device__ __forceinline__ float scale_of(uint32_t maxbits)
+{
+    if (maxbits == 0) return 1.0f;
+    int e = (int)(maxbits >> 23) - 127;
+    if (e < -100) e = -100;                       // denormal-sized data: any finite scale will do
+    return __uint_as_float((uint32_t)(127 + 13 - e) << 23);
+}
+
+// X16[r, 0..dimP) = fp16(X[r, :] * scale), zero beyond dim; norms[r] = sum of squares in fp32.
+__global__ void __launch_bounds__(256)
+to_half_kernel(const float *__restrict__ X, int64_t rows, int dim, int64_t ld, const uint32_t *maxbits,
+               _Float16 *__restrict__ X16, int dimP, float *__restrict__ norms)
+{
+    const float scale = scale_of(*maxbits);
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // one wavefront per row
+    if (r >= rows) return;
+    float acc = 0.f;
+    for (int c = lane; c < dimP; c += 64) {
+        const float v = c < dim ? X[r * ld + c] : 0.f;
+        acc = fmaf(v, v, acc);
+        X16[r * dimP + c] = (_Float16)(v * scale);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) norms[r] = acc;
+}
+
+static __global__ void filter_fill_kernel(uint32_t *p, int64_t n, uint32_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ---- steps 2 and 3: approximate distances on the matrix cores -----------------------------------
+
+struct FilterParams {
+    const _Float16 *Q16;      // fp16 queries, rows dimP apart
+    const _Float16 *X16;      // fp16 dataset, rows dimP apart
+    const float *nq, *nx;     // squared norms (original scale)
+    const uint32_t *q_maxbits, *x_maxbits;
+    int64_t q_row0, q_rows;   // the block: query rows q_row0 .. ; rows >= q_rows do not exist
+    int64_t n_cols;           // columns: dataset rows j * col_step for j < n_cols
+    int64_t col_step;
+    int dimP, metric;
+    float c16, c32;           // eps = 2 c16 |q||x| + c32 (|q|^2 + |x|^2)  (L2),  2 (c16 + c32) |q||x|  (inner product)
+    // dense output (the sample): out[local row, column], +inf beyond n_cols
+    float *out;
+    int64_t pitch;
+    // filter output: ids with approx <= thr[local row * thr_stride] + eps appended to buf[local row, 0..cap)
+    const float *thr;
+    int64_t thr_stride;
+    uint32_t *count, *buf;
+    int exclude_self;
+    int64_t self_offset;
+};
+
+template <bool DENSE>
+__global__ void __launch_bounds__(256)
+mfma_tile_kernel(const FilterParams P)
+{
+    __shared__ __align__(16) _Float16 As[kFT * kFRow];
+    __shared__ __align__(16) _Float16 Xs[kFT * kFRow];
+    __shared__ float s_nq[kFT], s_thr[kFT];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t tile_r = (int64_t)blockIdx.y * kFT;    // local row of the block
+    const int64_t tile_c = (int64_t)blockIdx.x * kFT;    // column
+    const int m0 = (wave >> 1) * 64, n0 = (wave & 1) * 64;
+
+    if (tid < kFT) {
+        const int64_t grow = P.q_row0 + tile_r + tid;
+        const bool ok = grow < P.q_rows;
+        s_nq[tid] = ok ? P.nq[grow] : 0.f;
+        if (!DENSE) s_thr[tid] = ok ? P.thr[(tile_r + tid) * P.thr_stride] : 0.f;
+    }
+
+    // staging: 512 16-byte pieces per operand and step, two per thread
+    const _Float16 *src_a[2], *src_x[2];
+    bool ok_a[2], ok_x[2];
+    int dst[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int p = tid + 256 * u;
+        const int row = p >> 2, part = p & 3;
+        const int64_t grow = P.q_row0 + tile_r + row;
+        const int64_t col = tile_c + row;
+        ok_a[u] = grow < P.q_rows;
+        ok_x[u] = col < P.n_cols;
+        src_a[u] = P.Q16 + (ok_a[u] ? grow : 0) * P.dimP + part * 8;
+        src_x[u] = P.X16 + (ok_x[u] ? col * P.col_step : 0) * P.dimP + part * 8;
+        dst[u] = row * kFRow + part * 8;
+    }
+
+    floatx16_t acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    for (int k0 = 0; k0 < P.dimP; k0 += kFK) {
+        uint4 va[2], vx[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            va[u] = ok_a[u] ? *reinterpret_cast<const uint4 *>(src_a[u] + k0) : zero4;
+            vx[u] = ok_x[u] ? *reinterpret_cast<const uint4 *>(src_x[u] + k0) : zero4;
+        }
+        __syncthreads();                       // the previous step's fragments have been read
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            *reinterpret_cast<uint4 *>(&As[dst[u]]) = va[u];
+            *reinterpret_cast<uint4 *>(&Xs[dst[u]]) = vx[u];
+        }
+        __syncthreads();
+        // operand layout of v_mfma_f32_32x32x8_f16: lane l holds row (l % 32), k = 4 * (l / 32) .. + 3
+        const int fr = lane & 31, fk = (lane >> 5) * 4;
+#pragma unroll
+        for (int ks = 0; ks < kFK / 8; ++ks) {
+            half4_t a[2], b[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                a[h] = *reinterpret_cast<const half4_t *>(&As[(m0 + h * 32 + fr) * kFRow + ks * 8 + fk]);
+                b[h] = *reinterpret_cast<const half4_t *>(&Xs[(n0 + h * 32 + fr) * kFRow + ks * 8 + fk]);
+            }
+#pragma unroll
+            for (int ma = 0; ma < 2; ++ma)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[ma][nb] = __builtin_amdgcn_mfma_f32_32x32x8f16(a[ma], b[nb], acc[ma][nb], 0, 0, 0);
+        }
+    }
+
+    // result layout: register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4, column l % 32
+    const float inv = 1.0f / (scale_of(*P.q_maxbits) * scale_of(*P.x_maxbits));   // powers of two: exact
+    const float inf = __uint_as_float(0x7F800000u);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int64_t col = tile_c + n0 + nb * 32 + (lane & 31);
+        const bool col_ok = col < P.n_cols;
+        const float nxv = col_ok ? P.nx[col * P.col_step] : 0.f;
+#pragma unroll
+        for (int ma = 0; ma < 2; ++ma)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int64_t lr = tile_r + lrow;
+                const int64_t grow = P.q_row0 + lr;
+                if (grow >= P.q_rows) continue;
+                const float dot = acc[ma][nb][r] * inv;
+                const float nqv = s_nq[lrow];
+                const float approx = P.metric == 0 ? (nqv + nxv) - 2.0f * dot : 0.0f - dot;
+                if (DENSE) {
+                    if (col < P.pitch) P.out[lr * P.pitch + col] = col_ok ? approx : inf;
+                } else if (col_ok) {
+                    const int64_t id = col * P.col_step;
+                    const float g = 2.0f * sqrtf(nqv * nxv);
+                    const float eps = P.metric == 0 ? P.c16 * g + P.c32 * (nqv + nxv) : (P.c16 + P.c32) * g;
+                    if (approx <= s_thr[lrow] + eps && !(P.exclude_self && id == P.self_offset + grow)) {
+                        const uint32_t pos = atomicAdd(&P.count[lr], 1u);
+                        if (pos < (uint32_t)kCap) P.buf[lr * kCap + pos] = (uint32_t)id;
+                    }
+                }
+            }
+    }
+}
+
+// ---- step 4: exact distances of the candidates, order, certificate ----------------------------
+
+__device__ void sort_keys(uint64_t *keys, int n_pow2, int tid)
+{
+    for (int k = 2; k <= n_pow2; k <<= 1)
+        for (int j = k >> 1; j >= 1; j >>= 1) {
+            __syncthreads();
+            for (int i = tid; i < n_pow2 / 2; i += 256) {
+                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                const int hi = lo | j;
+                const uint64_t a = keys[lo], b = keys[hi];
+                const bool asc = (lo & k) == 0;
+                if ((a > b) == asc) { keys[lo] = b; keys[hi] = a; }
+            }
+        }
+    __syncthreads();
+}
+
+__global__ void __launch_bounds__(256)
+rerank_kernel(const float *__restrict__ X, int dim, int64_t ldX, int metric, const float *__restrict__ Q,
+              int64_t ldQ, int64_t q_row0, const uint32_t *__restrict__ count, const uint32_t *__restrict__ buf,
+              const float *__restrict__ thr, int64_t thr_stride, int k, uint32_t *__restrict__ ids_out,
+              float *__restrict__ dists_out, uint32_t *flag)
+{
+    __shared__ uint64_t keys[kCap];
+    extern __shared__ __align__(16) float qs[];
+    const int tid = threadIdx.x;
+    const int64_t lr = blockIdx.x, grow = q_row0 + lr;
+    const uint32_t offered = count[lr];
+    const int n = offered < (uint32_t)kCap ? (int)offered : kCap;
+    for (int j = tid; j < dim; j += 256) qs[j] = Q[grow * ldQ + j];
+    int n_pow2 = 256;
+    while (n_pow2 < n) n_pow2 <<= 1;
+    __syncthreads();
+    for (int i = tid; i < n_pow2; i += 256) {
+        uint64_t key = ~0ull;
+        if (i < n) {
+            const uint32_t id = buf[lr * kCap + i];
+            const float *x = X + (int64_t)id * ldX;
+            float acc = 0.f;
+            // the plain path's chain: one fused multiply-add per dimension, in order
+            if (metric == 0) {
+                for (int j = 0; j < dim; j += 4) {
+                    const float4 xv = *reinterpret_cast<const float4 *>(x + j);
+                    float t = qs[j] - xv.x;     acc = fmaf(t, t, acc);
+                    t = qs[j + 1] - xv.y;       acc = fmaf(t, t, acc);
+                    t = qs[j + 2] - xv.z;       acc = fmaf(t, t, acc);
+                    t = qs[j + 3] - xv.w;       acc = fmaf(t, t, acc);
+                }
+            } else {
+                for (int j = 0; j < dim; j += 4) {
+                    const float4 xv = *reinterpret_cast<const float4 *>(x + j);
+                    acc = fmaf(qs[j], xv.x, acc);     acc = fmaf(qs[j + 1], xv.y, acc);
+                    acc = fmaf(qs[j + 2], xv.z, acc); acc = fmaf(qs[j + 3], xv.w, acc);
+                }
+                acc = 0.0f - acc;
+            }
+            key = ((uint64_t)f32_to_ordered(acc) << 32) | id;
+        }
+        keys[i] = key;
+    }
+    sort_keys(keys, n_pow2, tid);
+    // certificate: no overflow, and the k-th exact distance does not exceed the threshold
+    const uint32_t tau = f32_to_ordered(thr[lr * thr_stride]);
+    const bool certain = offered <= (uint32_t)kCap && n >= k && (uint32_t)(keys[k - 1] >> 32) <= tau;
+    if (tid == 0 && !certain) atomicOr(flag, 1u);
+    for (int i = tid; i < k; i += 256) {
+        const bool ok = i < n;
+        const uint64_t key = keys[i < n_pow2 ? i : 0];
+        ids_out[grow * k + i] = ok ? (uint32_t)key : kInvalidId;
+        if (dists_out) dists_out[grow * k + i] = ok ? ordered_to_f32((uint32_t)(key >> 32)) : __uint_as_float(kFltMaxBits);
+    }
+}
+
+// *out = number of flags that are up (one flag per block of query rows)
+static __global__ void count_flags_kernel(const uint32_t *flags, int64_t n, uint32_t *out)
+{
+    uint32_t c = 0;
+    for (int64_t i = threadIdx.x; i < n; i += 64) c += flags[i] != 0u;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) c += (uint32_t)__shfl_xor((int)c, o);
+    if (threadIdx.x == 0) *out = c;
+}
+
+// ---- host side --------------------------------------------------------------------------------
+
+void launch_fill_u32(uint32_t *p, int64_t n, uint32_t value, hipStream_t stream)
+{
+    hipLaunchKernelGGL(filter_fill_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n, value);
+}
+
+static size_t up256f(size_t v) { return (v + 255) & ~(size_t)255; }
+
+FilterPlan plan_exact_filter(int64_t N, int dim, int64_t B, int k, bool share_queries)
+{
+    FilterPlan pl = {};
+    pl.dimP = (dim + kFK - 1) / kFK * kFK;
+    pl.block_rows = std::min<int64_t>(2048, (B + kFT - 1) / kFT * kFT);
+    pl.stride = std::max<int64_t>(32, (N + (1 << 20) - 1) >> 20);
+    pl.n_sample = (N + pl.stride - 1) / pl.stride;
+    const int64_t target = std::max<int64_t>(768, 3 * (int64_t)k);
+    pl.t = (int)std::min<int64_t>(512, std::max<int64_t>(1, (target + pl.stride - 1) / pl.stride));
+    pl.sample_pitch = (pl.n_sample + kFT - 1) / kFT * kFT;
+    pl.n_blocks = (B + pl.block_rows - 1) / pl.block_rows;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += up256f(bytes); return at; };
+    pl.off_x16 = take((size_t)N * pl.dimP * 2);
+    pl.off_nx = take((size_t)N * 4);
+    pl.off_q16 = share_queries ? pl.off_x16 : take((size_t)B * pl.dimP * 2);
+    pl.off_nq = share_queries ? pl.off_nx : take((size_t)B * 4);
+    pl.off_max = take(2 * 4);
+    pl.off_thr_ids = take((size_t)pl.block_rows * pl.t * 4);
+    pl.off_thr_d = take((size_t)pl.block_rows * pl.t * 4);
+    pl.off_count = take((size_t)pl.block_rows * 4);
+    pl.off_buf = take((size_t)pl.block_rows * kCap * 4);
+    pl.off_flags = take((size_t)pl.n_blocks * 4);
+    pl.bytes = off;
+    return pl;
+}
+
+hipError_t launch_exact_filter(const float *X, int64_t N, int dim, int64_t ldX, int metric, const float *Q,
+                               int64_t B, int64_t ldQ, int k, int exclude_self, int64_t self_offset, uint32_t *ids,
+                               float *dists, float *plain_scratch, int64_t plain_block_rows, void *extra,
+                               const FilterPlan &pl, bool share_queries, uint32_t *blocks_redone, hipStream_t stream)
+{
+    unsigned char *w = static_cast<unsigned char *>(extra);
+    _Float16 *X16 = reinterpret_cast<_Float16 *>(w + pl.off_x16);
+    _Float16 *Q16 = reinterpret_cast<_Float16 *>(w + pl.off_q16);
+    float *nx = reinterpret_cast<float *>(w + pl.off_nx), *nq = reinterpret_cast<float *>(w + pl.off_nq);
+    uint32_t *maxbits = reinterpret_cast<uint32_t *>(w + pl.off_max);
+    uint32_t *thr_ids = reinterpret_cast<uint32_t *>(w + pl.off_thr_ids);
+    float *thr_d = reinterpret_cast<float *>(w + pl.off_thr_d);
+    uint32_t *count = reinterpret_cast<uint32_t *>(w + pl.off_count);
+    uint32_t *buf = reinterpret_cast<uint32_t *>(w + pl.off_buf);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(w + pl.off_flags);
+
+    // step 1
+    hipLaunchKernelGGL(filter_fill_kernel, dim3(1), dim3(64), 0, stream, maxbits, (int64_t)2, 0u);
+    hipLaunchKernelGGL(filter_fill_kernel, dim3((unsigned)((pl.n_blocks + 255) / 256)), dim3(256), 0, stream, flags,
+                       pl.n_blocks, 0u);
+    hipLaunchKernelGGL(maxabs_kernel, dim3(2048), dim3(256), 0, stream, X, N, dim, ldX, maxbits);
+    hipLaunchKernelGGL(to_half_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, X, N, dim, ldX, maxbits,
+                       X16, pl.dimP, nx);
+    if (!share_queries) {
+        hipLaunchKernelGGL(maxabs_kernel, dim3(2048), dim3(256), 0, stream, Q, B, dim, ldQ, maxbits + 1);
+        hipLaunchKernelGGL(to_half_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, stream, Q, B, dim, ldQ,
+                           maxbits + 1, Q16, pl.dimP, nq);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    FilterParams P = {};
+    P.Q16 = Q16; P.X16 = X16; P.nq = nq; P.nx = nx;
+    P.q_maxbits = share_queries ? maxbits : maxbits + 1; P.x_maxbits = maxbits;
+    P.q_rows = B; P.dimP = pl.dimP; P.metric = metric;
+    P.c16 = 1.01f / 1024.0f;
+    P.c32 = (float)(8 * dim + 32) / 16777216.0f;
+    P.thr = thr_d + (pl.t - 1); P.thr_stride = pl.t;
+    P.count = count; P.buf = buf; P.exclude_self = exclude_self; P.self_offset = self_offset;
+
+    for (int64_t b = 0; b < pl.n_blocks; ++b) {
+        const int64_t r0 = b * pl.block_rows;
+        const int64_t rows = std::min<int64_t>(pl.block_rows, B - r0);
+        const unsigned row_tiles = (unsigned)((rows + kFT - 1) / kFT);
+        P.q_row0 = r0;
+        // step 2: the sample, dense, into the plain path's distance block; its t-th smallest per row
+        FilterParams S = P;
+        S.n_cols = pl.n_sample; S.col_step = pl.stride; S.out = plain_scratch; S.pitch = pl.sample_pitch;
+        hipLaunchKernelGGL(mfma_tile_kernel<true>, dim3((unsigned)(pl.sample_pitch / kFT), row_tiles), dim3(256), 0,
+                           stream, S);
+        launch_row_select(plain_scratch, pl.sample_pitch, rows, pl.t, thr_ids, thr_d, stream);
+        // step 3
+        hipLaunchKernelGGL(filter_fill_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, count, rows, 0u);
+        FilterParams F = P;
+        F.n_cols = N; F.col_step = 1;
+        hipLaunchKernelGGL(mfma_tile_kernel<false>, dim3((unsigned)((N + kFT - 1) / kFT), row_tiles), dim3(256), 0,
+                           stream, F);
+        // step 4
+        hipLaunchKernelGGL(rerank_kernel, dim3((unsigned)rows), dim3(256), (size_t)dim * 4, stream, X, dim, ldX, metric,
+                           Q, ldQ, r0, count, buf, P.thr, P.thr_stride, k, ids, dists, flags + b);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        // step 5: the plain kernels over the same rows, gated by the block's flag
+        e = launch_exact_search_gated(X, N, dim, ldX, metric, Q, r0 + rows, ldQ, r0, k, exclude_self, self_offset, ids,
+                                      dists, plain_scratch, plain_block_rows, flags + b, stream);
+        if (e != hipSuccess) return e;
+    }
+    if (blocks_redone != nullptr)
+        hipLaunchKernelGGL(count_flags_kernel, dim3(1), dim3(64), 0, stream, flags, pl.n_blocks, blocks_redone);
+    return hipGetLastError();
+}
+
+}  // namespace cagra

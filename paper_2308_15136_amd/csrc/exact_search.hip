@@ -24,8 +24,10 @@ constexpr int kPad = 4;
 __global__ void __launch_bounds__(256)
 dist_tile_kernel(const float *__restrict__ A, int64_t rowsA, int64_t ldA, int64_t row0,
                  const float *__restrict__ X, int64_t N, int64_t ldX, int dim, int metric,
-                 int exclude_self, int64_t self_offset, float *__restrict__ D, int64_t pitch)
+                 int exclude_self, int64_t self_offset, float *__restrict__ D, int64_t pitch,
+                 const uint32_t *gate)
 {
+    if (gate != nullptr && *gate == 0u) return;   // a launch that is only needed when the flag is up
     __shared__ float As[kKC][kTile + kPad];
     __shared__ float Xs[kKC][kTile + kPad];
     const int tid = threadIdx.x;
@@ -133,8 +135,9 @@ __device__ void pool_sort(uint64_t *pool, int tid)
 __global__ void __launch_bounds__(256)
 row_select_kernel(const float *__restrict__ D, int64_t pitch, int64_t rows, int k,
                   uint32_t *__restrict__ ids_out, float *__restrict__ best_d, int64_t out_row0,
-                  int64_t best_row0, int64_t col0, int carry)
+                  int64_t best_row0, int64_t col0, int carry, const uint32_t *gate)
 {
+    if (gate != nullptr && *gate == 0u) return;
     __shared__ uint64_t pool[kPool];
     __shared__ int count;
     const int tid = threadIdx.x;
@@ -198,31 +201,49 @@ int64_t exact_search_pitch(int64_t N)
     return (cols + kTile - 1) / kTile * kTile;
 }
 
+// The k smallest of every row of a dense block D[rows, pitch] (columns are the ids); no carry.
+void launch_row_select(const float *D, int64_t pitch, int64_t rows, int k, uint32_t *ids_out, float *best_d,
+                       hipStream_t stream)
+{
+    hipLaunchKernelGGL(row_select_kernel, dim3((unsigned)rows), dim3(256), 0, stream, D, pitch, rows, k, ids_out,
+                       best_d, (int64_t)0, (int64_t)0, (int64_t)0, 0, (const uint32_t *)nullptr);
+}
+
 // scratch: block_rows x exact_search_pitch(N) floats, then block_rows x k floats (the running
-// distances of a block when the caller does not ask for distances)
-hipError_t launch_exact_search(const float *X, int64_t N, int dim, int64_t ldX, int metric,
-                               const float *Q, int64_t B, int64_t ldQ, int k, int exclude_self,
-                               int64_t self_offset, uint32_t *ids, float *dists, float *scratch,
-                               int64_t block_rows, hipStream_t stream)
+// distances of a block when the caller does not ask for distances).  Query rows row_begin .. row_end;
+// with a gate every kernel returns at once unless *gate != 0.
+hipError_t launch_exact_search_gated(const float *X, int64_t N, int dim, int64_t ldX, int metric,
+                                     const float *Q, int64_t row_end, int64_t ldQ, int64_t row_begin, int k,
+                                     int exclude_self, int64_t self_offset, uint32_t *ids, float *dists,
+                                     float *scratch, int64_t block_rows, const uint32_t *gate, hipStream_t stream)
 {
     const int64_t pitch = exact_search_pitch(N);
     float *running = scratch + block_rows * pitch;
-    for (int64_t r0 = 0; r0 < B; r0 += block_rows) {
-        const int64_t rows = B - r0 < block_rows ? B - r0 : block_rows;
+    for (int64_t r0 = row_begin; r0 < row_end; r0 += block_rows) {
+        const int64_t rows = row_end - r0 < block_rows ? row_end - r0 : block_rows;
         for (int64_t c0 = 0; c0 < N; c0 += kMaxCols) {
             const int64_t cols = N - c0 < kMaxCols ? N - c0 : kMaxCols;
             dim3 grid((unsigned)(pitch / kTile), (unsigned)((rows + kTile - 1) / kTile));
             // rows of X from c0 on; the row to leave out is given relative to that slice
             hipLaunchKernelGGL(dist_tile_kernel, grid, dim3(256), 0, stream, Q, r0 + rows, ldQ, r0, X + c0 * ldX,
-                               cols, ldX, dim, metric, exclude_self, self_offset - c0, scratch, pitch);
+                               cols, ldX, dim, metric, exclude_self, self_offset - c0, scratch, pitch, gate);
             hipLaunchKernelGGL(row_select_kernel, dim3((unsigned)rows), dim3(256), 0, stream, scratch, pitch,
                                rows, k, ids, dists ? dists : running, r0, dists ? r0 : (int64_t)0, c0,
-                               c0 > 0 ? 1 : 0);
+                               c0 > 0 ? 1 : 0, gate);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
     }
     return hipSuccess;
+}
+
+hipError_t launch_exact_search(const float *X, int64_t N, int dim, int64_t ldX, int metric,
+                               const float *Q, int64_t B, int64_t ldQ, int k, int exclude_self,
+                               int64_t self_offset, uint32_t *ids, float *dists, float *scratch,
+                               int64_t block_rows, hipStream_t stream)
+{
+    return launch_exact_search_gated(X, N, dim, ldX, metric, Q, B, ldQ, 0, k, exclude_self, self_offset, ids, dists,
+                                     scratch, block_rows, nullptr, stream);
 }
 
 }  // namespace cagra

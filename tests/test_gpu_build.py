@@ -160,3 +160,77 @@ def test_distance_based_reordering_bit_exact(cagra, name, n, d):
                                   oracle.build(w.base, d, 0, w.metric, reorder=oracle.DISTANCE))
     # integer data has many equal distances (strict comparisons matter); the two reorderings differ
     assert not np.array_equal(_u32(graph), oracle.optimize(g0, d))
+
+
+def _check_filtered(cagra, base, queries, k, metric, exclude_self=False, expect_redone=None):
+    import torch
+    bd = _dev(base)
+    qd = bd if queries is None else _dev(queries)
+    redone = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    ids, dists = cagra.exact_search(bd, qd, k, metric, exclude_self=exclude_self, algo=cagra.EXACT_FILTERED,
+                                    blocks_redone=redone)
+    if exclude_self:
+        ref, ref_d = oracle.knn_graph(base, k, metric, return_dists=True)
+    else:
+        ref, ref_d = oracle.exact_search(base, queries, k, metric)
+    np.testing.assert_array_equal(_u32(ids), ref)
+    np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
+    n = int(redone.item())
+    if expect_redone is not None:
+        assert (n > 0) == expect_redone, f"blocks redone by the plain kernels: {n}"
+    return n
+
+
+def test_filtered_exact_search_bit_exact(cagra):
+    # The matrix-core filter in front of the exact arithmetic: same ids and distances as the oracle's brute
+    # force, and on ordinary data no block of query rows has to be handed to the plain kernels.
+    print("case filtered: integer rows, distinct queries", flush=True)
+    w = datagen.workload("sift1m", n=20_000, n_queries=300)
+    _check_filtered(cagra, w.base, w.queries, 64, w.metric, expect_redone=False)
+    print("case filtered: unit-norm rows, k-NN graph (rows of the dataset as queries, self left out)", flush=True)
+    w = datagen.workload("deep1m", n=8_000, n_queries=1)
+    _check_filtered(cagra, w.base, None, 64, w.metric, exclude_self=True, expect_redone=False)
+    print("case filtered: inner product, dim 200 (padded to 224), k = 128", flush=True)
+    w = datagen.workload("glove200", n=6_000, n_queries=130)
+    _check_filtered(cagra, w.base, w.queries, 128, w.metric, expect_redone=False)
+    print("case filtered: largest k on the smallest N the filter takes", flush=True)
+    w = datagen.workload("tiny", n=4_096, n_queries=70)
+    _check_filtered(cagra, w.base, w.queries, 512, w.metric)
+    print("case filtered: k = 1", flush=True)
+    _check_filtered(cagra, w.base, w.queries, 1, w.metric, expect_redone=False)
+
+
+def test_filtered_exact_search_scales(cagra):
+    # magnitudes far outside the fp16 range are brought into it by a power of two
+    w = datagen.workload("deep1m", n=5_000, n_queries=64)
+    for scale in (1e6, 1e-6, 3e4):
+        print(f"case filtered: rows scaled by {scale}", flush=True)
+        _check_filtered(cagra, (w.base * np.float32(scale)).astype(np.float32),
+                        (w.queries * np.float32(scale)).astype(np.float32), 32, w.metric, expect_redone=False)
+    # queries of a very different magnitude than the dataset
+    _check_filtered(cagra, w.base, (w.queries * np.float32(1e3)).astype(np.float32), 32, oracle.IP, expect_redone=False)
+
+
+def test_filtered_exact_search_falls_back_when_it_cannot_certify(cagra):
+    # 20,000 rows that are copies of 3 vectors: more rows tie below any threshold than the candidate buffer
+    # holds (4,096), so the block must be done again by the plain kernels, with the plain result (ties by id).
+    rng = np.random.default_rng(11)
+    protos = rng.integers(0, 50, size=(3, 32)).astype(np.float32)
+    base = protos[rng.integers(0, 3, size=20_000)]
+    queries = protos[[0, 1, 2, 0]] + np.float32(1.0)
+    print("case filtered: massive duplicates", flush=True)
+    _check_filtered(cagra, base, queries, 100, oracle.L2, expect_redone=True)
+    _check_filtered(cagra, base, None, 16, oracle.L2, exclude_self=True, expect_redone=True)
+
+
+def test_build_with_either_exact_algorithm_gives_the_same_graph(cagra):
+    w = datagen.workload("sift1m", n=12_000, n_queries=1)
+    b = _dev(w.base)
+    plain = cagra.build(b, 32, 64, w.metric, exact_algo=cagra.EXACT_PLAIN)
+    filtered = cagra.build(b, 32, 64, w.metric, exact_algo=cagra.EXACT_FILTERED)
+    np.testing.assert_array_equal(_u32(plain), _u32(filtered))
+    np.testing.assert_array_equal(_u32(filtered), oracle.build(w.base, 32, 64, w.metric))
+    with pytest.raises(cagra.CagraError):
+        cagra.exact_search(b[:2000], b[:10], 8, algo=cagra.EXACT_FILTERED)      # N below 4096
+    with pytest.raises(cagra.CagraError):
+        cagra.exact_search(b, b[:10], 8, algo=7)
