@@ -10,7 +10,7 @@
 //      per-row threshold tau (the t-th smallest of the sample, so that about t * stride dataset
 //      rows lie below it);
 //   3. the filter kernel forms approximate distances to all dataset rows tile by tile
-//      (v_mfma_f32_32x32x8_f16) and appends the ids with  approx <= tau + eps  to the row's
+//      (v_mfma_f32_32x32x16_f16) and appends the ids with  approx <= tau + eps  to the row's
 //      candidate buffer, eps bounding |approx - exact| for the pair;
 //   4. the re-rank kernel computes the exact distance (the same fused multiply-add chain as the
 //      plain path) of every buffered candidate and sorts by (distance, id).  Every dataset row
@@ -37,12 +37,14 @@
 
 namespace cagra {
 
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16 bytes in flight between global memory and LDS
 
 constexpr int kFT = 128;          // output tile edge (4 wavefronts, 64 x 64 each)
-constexpr int kFK = 32;           // dimensions staged per step
-constexpr int kFRow = kFK + 8;    // halfs per staged row in LDS (80 bytes: 16-byte aligned, banks spread)
+constexpr int kFK = 64;           // dimensions staged per step
+constexpr int kFRow = kFK + 8;    // halfs per staged row in LDS (144 bytes: 16-byte aligned, banks spread)
+constexpr int kStrip = 8;         // column tiles per workgroup
 constexpr int kCap = kFilterCap;  // candidate buffer entries per query row
 
 // ---- step 1: fp16 copy and norms ------------------------------------------------------------
@@ -66,12 +68,20 @@ maxabs_kernel(const float *__restrict__ X, int64_t rows, int dim, int64_t ld, ui
     if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(out, m);
 }
 
+// Data whose largest magnitude lies below 2^kMinExponent is not scaled all the way up, and the error
+// bound of the filter does not cover it: the re-rank kernel then certifies nothing.
+constexpr int kMinExponent = -40;
+__device__ __forceinline__ bool too_small(uint32_t maxbits)
+{
+    return maxbits != 0 && (int)(maxbits >> 23) - 127 < kMinExponent;
+}
+
 // Power of two that brings a largest magnitude with the given bits into [2^13, 2^14).
 __device__ __forceinline__ float scale_of(uint32_t maxbits)
 {
     if (maxbits == 0) return 1.0f;
     int e = (int)(maxbits >> 23) - 127;
-    if (e < -100) e = -100;                       // denormal-sized data: any finite scale will do
+    if (e < kMinExponent) e = kMinExponent;       // keeps the product of two scales finite; see too_small()
     return __uint_as_float((uint32_t)(127 + 13 - e) << 23);
 }
 
@@ -124,43 +134,83 @@ struct FilterParams {
     int64_t self_offset;
 };
 
+// One workgroup: a tile of 128 query rows against a strip of kStrip tiles of 128 columns.  The
+// operands travel global -> registers -> LDS in steps of 64 dimensions; the loads of the next step are
+// issued before the matrix instructions of the current one.  Four wavefronts, 64 x 64 outputs each
+// (2 x 2 blocks of v_mfma_f32_32x32x16_f16).
+//
+// Filter test without forming the distance: with inv = 1 / (scale_q scale_x) and acc the raw product,
+//   squared L2:     |q|^2 + |x|^2 - 2 acc inv <= thr + 2 c16 |q||x| + c32 (|q|^2 + |x|^2)
+//              <=>  acc >= Rr[row] + Cn[col] - Xr[row] |x|,   Rr = (|q|^2 (1 - c32) - thr) / (2 inv),
+//                   Cn = |x|^2 (1 - c32) / (2 inv),  Xr = c16 |q| / inv
+//   inner product:  -acc inv <= thr + 2 (c16 + c32) |q||x|
+//              <=>  acc >= Rr[row] - Xr[row] |x|,   Rr = -thr / inv,  Xr = 2 (c16 + c32) |q| / inv
+// (c32 leaves room for the few roundings of this rearrangement.)
 template <bool DENSE>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)     // two wavefronts per SIMD: two workgroups per CU
 mfma_tile_kernel(const FilterParams P)
 {
     __shared__ __align__(16) _Float16 As[kFT * kFRow];
     __shared__ __align__(16) _Float16 Xs[kFT * kFRow];
-    __shared__ float s_nq[kFT], s_thr[kFT];
+    __shared__ float2 s_row[kFT];     // filter: (Rr, Xr); dense: (|q|^2, unused)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int64_t tile_r = (int64_t)blockIdx.y * kFT;    // local row of the block
-    const int64_t tile_c = (int64_t)blockIdx.x * kFT;    // column
+    const int64_t tile_r = (int64_t)blockIdx.y * kFT;                 // local row of the block
+    const int64_t strip_c = (int64_t)blockIdx.x * (kFT * kStrip);     // first column of the strip
     const int m0 = (wave >> 1) * 64, n0 = (wave & 1) * 64;
+    const float inv = 1.0f / (scale_of(*P.q_maxbits) * scale_of(*P.x_maxbits));   // powers of two: exact
+    const float half_inv = 0.5f / inv;
 
     if (tid < kFT) {
         const int64_t grow = P.q_row0 + tile_r + tid;
         const bool ok = grow < P.q_rows;
-        s_nq[tid] = ok ? P.nq[grow] : 0.f;
-        if (!DENSE) s_thr[tid] = ok ? P.thr[(tile_r + tid) * P.thr_stride] : 0.f;
+        const float nqv = ok ? P.nq[grow] : 0.f;
+        if (DENSE) {
+            s_row[tid] = make_float2(nqv, 0.f);
+        } else {
+            const float thr = ok ? P.thr[(tile_r + tid) * P.thr_stride] : 0.f;
+            const float sq = sqrtf(nqv);
+            s_row[tid] = P.metric == 0 ? make_float2((nqv * (1.0f - P.c32) - thr) * half_inv, P.c16 * sq / inv)
+                                       : make_float2((0.0f - thr) / inv, 2.0f * (P.c16 + P.c32) * sq / inv);
+        }
     }
 
-    // staging: 512 16-byte pieces per operand and step, two per thread
-    const _Float16 *src_a[2], *src_x[2];
-    bool ok_a[2], ok_x[2];
-    int dst[2];
+    // staging: 1024 16-byte pieces per operand and step, four per thread
+    const int n_chunks = P.dimP / kFK;
+    int64_t n_tiles = (P.n_cols - strip_c + kFT - 1) / kFT;
+    if (DENSE) n_tiles = (P.pitch - strip_c) / kFT;                   // the padding columns are written too
+    if (n_tiles > kStrip) n_tiles = kStrip;
+    const int total = (int)n_tiles * n_chunks;
+    int dst[4];
+    const _Float16 *src_a[4];
+    bool ok_a[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 4; ++u) {
         const int p = tid + 256 * u;
-        const int row = p >> 2, part = p & 3;
+        const int row = p >> 3, part = p & 7;
         const int64_t grow = P.q_row0 + tile_r + row;
-        const int64_t col = tile_c + row;
         ok_a[u] = grow < P.q_rows;
-        ok_x[u] = col < P.n_cols;
         src_a[u] = P.Q16 + (ok_a[u] ? grow : 0) * P.dimP + part * 8;
-        src_x[u] = P.X16 + (ok_x[u] ? col * P.col_step : 0) * P.dimP + part * 8;
         dst[u] = row * kFRow + part * 8;
     }
-
+    // the 16-byte pieces this thread stages in one step: piece tid + 256 u of the 128 x 64 block of each operand
+    u32x4_t va[4], vx[4];
+#define CAGRA_FETCH_ONE(U)                                                                                       \
+    {                                                                                                            \
+        const int f_row = (tid + 256 * U) >> 3, f_part = (tid + 256 * U) & 7;                                    \
+        const int64_t f_col = strip_c + (int64_t)f_tile * kFT + f_row;                                           \
+        va[U] = ok_a[U] ? *reinterpret_cast<const u32x4_t *>(src_a[U] + f_k0) : zero4;                             \
+        vx[U] = f_col < P.n_cols                                                                                 \
+                    ? *reinterpret_cast<const u32x4_t *>(P.X16 + f_col * P.col_step * P.dimP + f_part * 8 + f_k0) \
+                    : zero4;                                                                                     \
+    }
+#define CAGRA_FETCH_STEP(STEP)                                                                                   \
+    {                                                                                                            \
+        const int f_step = (STEP);                                                                               \
+        const int f_tile = f_step / n_chunks, f_k0 = (f_step - f_tile * n_chunks) * kFK;                         \
+        CAGRA_FETCH_ONE(0) CAGRA_FETCH_ONE(1) CAGRA_FETCH_ONE(2) CAGRA_FETCH_ONE(3)                              \
+    }
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
     floatx16_t acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -169,72 +219,86 @@ mfma_tile_kernel(const FilterParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    for (int k0 = 0; k0 < P.dimP; k0 += kFK) {
-        uint4 va[2], vx[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            va[u] = ok_a[u] ? *reinterpret_cast<const uint4 *>(src_a[u] + k0) : zero4;
-            vx[u] = ok_x[u] ? *reinterpret_cast<const uint4 *>(src_x[u] + k0) : zero4;
-        }
+    CAGRA_FETCH_STEP(0)
+    const float inf = __uint_as_float(0x7F800000u);
+    // operand layout of v_mfma_f32_32x32x16_f16: lane l holds row (l % 32), k = 8 * (l / 32) .. + 7
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+    for (int step = 0; step < total; ++step) {
         __syncthreads();                       // the previous step's fragments have been read
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            *reinterpret_cast<uint4 *>(&As[dst[u]]) = va[u];
-            *reinterpret_cast<uint4 *>(&Xs[dst[u]]) = vx[u];
+        for (int u = 0; u < 4; ++u) {
+            *reinterpret_cast<u32x4_t *>(&As[dst[u]]) = va[u];
+            *reinterpret_cast<u32x4_t *>(&Xs[dst[u]]) = vx[u];
         }
         __syncthreads();
-        // operand layout of v_mfma_f32_32x32x8_f16: lane l holds row (l % 32), k = 4 * (l / 32) .. + 3
-        const int fr = lane & 31, fk = (lane >> 5) * 4;
+        // (the last step fetches itself once more rather than branch around the loads)
+        CAGRA_FETCH_STEP(step + 1 < total ? step + 1 : step)
 #pragma unroll
-        for (int ks = 0; ks < kFK / 8; ++ks) {
-            half4_t a[2], b[2];
+        for (int ks = 0; ks < kFK / 16; ++ks) {
+            half8_t a[2], b[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                a[h] = *reinterpret_cast<const half4_t *>(&As[(m0 + h * 32 + fr) * kFRow + ks * 8 + fk]);
-                b[h] = *reinterpret_cast<const half4_t *>(&Xs[(n0 + h * 32 + fr) * kFRow + ks * 8 + fk]);
+                a[h] = *reinterpret_cast<const half8_t *>(&As[(m0 + h * 32 + fr) * kFRow + ks * 16 + fk]);
+                b[h] = *reinterpret_cast<const half8_t *>(&Xs[(n0 + h * 32 + fr) * kFRow + ks * 16 + fk]);
             }
 #pragma unroll
             for (int ma = 0; ma < 2; ++ma)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[ma][nb] = __builtin_amdgcn_mfma_f32_32x32x8f16(a[ma], b[nb], acc[ma][nb], 0, 0, 0);
+                    acc[ma][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ma], b[nb], acc[ma][nb], 0, 0, 0);
         }
-    }
+        const int tile = step / n_chunks;
+        if (step - tile * n_chunks != n_chunks - 1) continue;
 
-    // result layout: register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4, column l % 32
-    const float inv = 1.0f / (scale_of(*P.q_maxbits) * scale_of(*P.x_maxbits));   // powers of two: exact
-    const float inf = __uint_as_float(0x7F800000u);
+        // the tile is complete.  Result layout: register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4,
+        // column l % 32
+        const int64_t tile_c = strip_c + (int64_t)tile * kFT;
+        uint64_t hits = 0;                     // filter: bit nb * 32 + ma * 16 + r of this lane passed the test
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int64_t col = tile_c + n0 + nb * 32 + (lane & 31);
-        const bool col_ok = col < P.n_cols;
-        const float nxv = col_ok ? P.nx[col * P.col_step] : 0.f;
+        for (int nb = 0; nb < 2; ++nb) {
+            const int64_t col = tile_c + n0 + nb * 32 + (lane & 31);
+            const bool col_ok = col < P.n_cols;
+            const float nxv = col_ok ? P.nx[col * P.col_step] : 0.f;
+            const float sx = sqrtf(nxv);
+            const float cn = P.metric == 0 ? nxv * (1.0f - P.c32) * half_inv : 0.f;
 #pragma unroll
-        for (int ma = 0; ma < 2; ++ma)
+            for (int ma = 0; ma < 2; ++ma)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int64_t lr = tile_r + lrow;
-                const int64_t grow = P.q_row0 + lr;
-                if (grow >= P.q_rows) continue;
-                const float dot = acc[ma][nb][r] * inv;
-                const float nqv = s_nq[lrow];
-                const float approx = P.metric == 0 ? (nqv + nxv) - 2.0f * dot : 0.0f - dot;
-                if (DENSE) {
-                    if (col < P.pitch) P.out[lr * P.pitch + col] = col_ok ? approx : inf;
-                } else if (col_ok) {
-                    const int64_t id = col * P.col_step;
-                    const float g = 2.0f * sqrtf(nqv * nxv);
-                    const float eps = P.metric == 0 ? P.c16 * g + P.c32 * (nqv + nxv) : (P.c16 + P.c32) * g;
-                    if (approx <= s_thr[lrow] + eps && !(P.exclude_self && id == P.self_offset + grow)) {
-                        const uint32_t pos = atomicAdd(&P.count[lr], 1u);
-                        if (pos < (uint32_t)kCap) P.buf[lr * kCap + pos] = (uint32_t)id;
+                for (int r = 0; r < 16; ++r) {
+                    const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const float2 rc = s_row[lrow];
+                    const float v = acc[ma][nb][r];
+                    acc[ma][nb][r] = 0.f;
+                    if (DENSE) {
+                        const int64_t lr = tile_r + lrow;
+                        if (P.q_row0 + lr < P.q_rows) {
+                            const float dot = v * inv;
+                            const float approx = P.metric == 0 ? (rc.x + nxv) - 2.0f * dot : 0.0f - dot;
+                            P.out[lr * P.pitch + col] = col_ok ? approx : inf;
+                        }
+                    } else if (v >= fmaf(0.0f - rc.y, sx, rc.x + cn) && col_ok) {
+                        hits |= 1ull << (nb * 32 + ma * 16 + r);
                     }
                 }
+        }
+        // the few that passed (about one in a thousand): append to the row's candidates
+        while (hits != 0ull) {
+            const int bit = __builtin_ctzll(hits);
+            hits &= hits - 1;
+            const int nb = bit >> 5, ma = (bit >> 4) & 1, r = bit & 15;
+            const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            const int64_t lr = tile_r + lrow, grow = P.q_row0 + lr;
+            const int64_t id = (tile_c + n0 + nb * 32 + (lane & 31)) * P.col_step;
+            if (grow < P.q_rows && !(P.exclude_self && id == P.self_offset + grow)) {
+                const uint32_t pos = atomicAdd(&P.count[lr], 1u);
+                if (pos < (uint32_t)kCap) P.buf[lr * kCap + pos] = (uint32_t)id;
             }
+        }
     }
 }
+
+#undef CAGRA_FETCH_STEP
+#undef CAGRA_FETCH_ONE
 
 // ---- step 4: exact distances of the candidates, order, certificate ----------------------------
 
@@ -257,8 +321,9 @@ __device__ void sort_keys(uint64_t *keys, int n_pow2, int tid)
 __global__ void __launch_bounds__(256)
 rerank_kernel(const float *__restrict__ X, int dim, int64_t ldX, int metric, const float *__restrict__ Q,
               int64_t ldQ, int64_t q_row0, const uint32_t *__restrict__ count, const uint32_t *__restrict__ buf,
-              const float *__restrict__ thr, int64_t thr_stride, int k, uint32_t *__restrict__ ids_out,
-              float *__restrict__ dists_out, uint32_t *flag)
+              const float *__restrict__ thr, int64_t thr_stride, const uint32_t *q_maxbits,
+              const uint32_t *x_maxbits, int k, uint32_t *__restrict__ ids_out, float *__restrict__ dists_out,
+              uint32_t *flag)
 {
     __shared__ uint64_t keys[kCap];
     extern __shared__ __align__(16) float qs[];
@@ -300,7 +365,8 @@ rerank_kernel(const float *__restrict__ X, int dim, int64_t ldX, int metric, con
     sort_keys(keys, n_pow2, tid);
     // certificate: no overflow, and the k-th exact distance does not exceed the threshold
     const uint32_t tau = f32_to_ordered(thr[lr * thr_stride]);
-    const bool certain = offered <= (uint32_t)kCap && n >= k && (uint32_t)(keys[k - 1] >> 32) <= tau;
+    const bool certain = offered <= (uint32_t)kCap && n >= k && (uint32_t)(keys[k - 1] >> 32) <= tau &&
+                         !too_small(*q_maxbits) && !too_small(*x_maxbits);
     if (tid == 0 && !certain) atomicOr(flag, 1u);
     for (int i = tid; i < k; i += 256) {
         const bool ok = i < n;
@@ -404,18 +470,19 @@ hipError_t launch_exact_filter(const float *X, int64_t N, int dim, int64_t ldX, 
         // step 2: the sample, dense, into the plain path's distance block; its t-th smallest per row
         FilterParams S = P;
         S.n_cols = pl.n_sample; S.col_step = pl.stride; S.out = plain_scratch; S.pitch = pl.sample_pitch;
-        hipLaunchKernelGGL(mfma_tile_kernel<true>, dim3((unsigned)(pl.sample_pitch / kFT), row_tiles), dim3(256), 0,
+        hipLaunchKernelGGL(mfma_tile_kernel<true>,
+                           dim3((unsigned)((pl.sample_pitch + kFT * kStrip - 1) / (kFT * kStrip)), row_tiles), dim3(256), 0,
                            stream, S);
         launch_row_select(plain_scratch, pl.sample_pitch, rows, pl.t, thr_ids, thr_d, stream);
         // step 3
         hipLaunchKernelGGL(filter_fill_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, count, rows, 0u);
         FilterParams F = P;
         F.n_cols = N; F.col_step = 1;
-        hipLaunchKernelGGL(mfma_tile_kernel<false>, dim3((unsigned)((N + kFT - 1) / kFT), row_tiles), dim3(256), 0,
-                           stream, F);
+        hipLaunchKernelGGL(mfma_tile_kernel<false>,
+                           dim3((unsigned)((N + kFT * kStrip - 1) / (kFT * kStrip)), row_tiles), dim3(256), 0, stream, F);
         // step 4
         hipLaunchKernelGGL(rerank_kernel, dim3((unsigned)rows), dim3(256), (size_t)dim * 4, stream, X, dim, ldX, metric,
-                           Q, ldQ, r0, count, buf, P.thr, P.thr_stride, k, ids, dists, flags + b);
+                           Q, ldQ, r0, count, buf, P.thr, P.thr_stride, P.q_maxbits, P.x_maxbits, k, ids, dists, flags + b);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         // step 5: the plain kernels over the same rows, gated by the block's flag
