@@ -81,6 +81,8 @@ def main() -> int:
     ap.add_argument("--full-sweep", action="store_true",
                     help="per search_width go on beyond the first itopk that reaches the recall target")
     ap.add_argument("--cpu-sample", type=int, default=10000, help="queries given to the CPU oracle")
+    ap.add_argument("--exact-algo", choices=("auto", "plain", "filtered"), default="auto",
+                    help="arithmetic of the exhaustive search behind the exact initial graph (same graph either way)")
     ap.add_argument("--no-short", action="store_true", help="skip the sweep of lists shorter than the named itopk range")
     ap.add_argument("--no-latency", action="store_true", help="skip the small-batch (multi mode) latency part")
     ap.add_argument("--latency-workers", type=int, default=8, help="workgroups per query in the latency part")
@@ -127,11 +129,12 @@ def main() -> int:
     base = torch.from_numpy(w.base).to(dev)
     queries = torch.from_numpy(w.queries).to(dev)
 
+    exact_algo = {"auto": cagra.EXACT_AUTO, "plain": cagra.EXACT_PLAIN, "filtered": cagra.EXACT_FILTERED}[args.exact_algo]
     t0 = time.time()
     if N <= 2_000_000 or args.initial_graph == "nn-descent":
         graph = cagra.build(base, w.degree, w.init_degree, w.metric,
                             reorder=cagra.REORDER_DISTANCE if args.reorder == "distance" else cagra.REORDER_RANK,
-                            nn_descent=args.initial_graph == "nn-descent")
+                            nn_descent=args.initial_graph == "nn-descent", exact_algo=exact_algo)
         torch.cuda.synchronize()
     else:
         # the same two stages as cagra_build, the first in slices of rows so that a long build
@@ -142,7 +145,7 @@ def main() -> int:
         for lo in range(0, N, step):
             hi = min(N, lo + step)
             part = cagra.exact_search(base, base[lo:hi], w.init_degree, w.metric, exclude_self=True,
-                                      self_offset=lo, return_dists=knn_d is not None)
+                                      self_offset=lo, return_dists=knn_d is not None, algo=exact_algo)
             if knn_d is not None:
                 knn[lo:hi], knn_d[lo:hi] = part
             else:
@@ -262,6 +265,7 @@ def main() -> int:
                    "itopk": M, "search_width": P_WIDTH, "recall_at_k": round(rec, 5), "target_recall": TARGET_RECALL,
                    "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
                    "graph_build_s": round(build_s, 2), "reorder": args.reorder, "initial_graph": args.initial_graph,
+                   "exact_algo": args.exact_algo,
                    "graph_quality": graph_quality},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -126,12 +126,14 @@ def test_exact_search_beyond_one_slice_of_dataset_rows(cagra):
     for lo, hi in [(0, 40), (2**20 - 20, 2**20 + 20), (n - 40, n)]:
         print(f"case sliced exact search rows {lo}..{hi}", flush=True)
         rows = np.arange(lo, hi, dtype=np.int64)
-        ids = cagra.exact_search(bd, bd[lo:hi], k, cagra.L2, exclude_self=True, self_offset=lo, return_dists=False)
         ref, ref_d = oracle.knn_graph(base, k, oracle.L2, rows=rows, return_dists=True)
-        np.testing.assert_array_equal(_u32(ids), ref)
-        ids2, d2 = cagra.exact_search(bd, bd[lo:hi], k, cagra.L2, exclude_self=True, self_offset=lo)
-        np.testing.assert_array_equal(_u32(ids2), ref)
-        np.testing.assert_array_equal(d2.cpu().numpy(), ref_d)
+        for algo in (cagra.EXACT_PLAIN, cagra.EXACT_FILTERED):      # the slices are the plain algorithm's
+            ids = cagra.exact_search(bd, bd[lo:hi], k, cagra.L2, exclude_self=True, self_offset=lo, return_dists=False,
+                                     algo=algo)
+            np.testing.assert_array_equal(_u32(ids), ref)
+            ids2, d2 = cagra.exact_search(bd, bd[lo:hi], k, cagra.L2, exclude_self=True, self_offset=lo, algo=algo)
+            np.testing.assert_array_equal(_u32(ids2), ref)
+            np.testing.assert_array_equal(d2.cpu().numpy(), ref_d)
     # plain queries (nothing left out), fewer valid neighbours than k cannot happen here; k = 1 edge
     q = datagen.sift_like(16, dim, 64, seed=5, stream=2)
     ids, d = cagra.exact_search(bd, torch.from_numpy(q).cuda(), 1, cagra.L2)
