@@ -122,6 +122,8 @@ struct FilterParams {
     int64_t n_cols;           // columns: dataset rows j * col_step for j < n_cols
     int64_t col_step;
     int dimP, metric;
+    int row_tiles;            // tiles of 128 query rows in the block
+    int64_t n_strips;         // strips of kStrip column tiles
     float c16, c32;           // eps = 2 c16 |q||x| + c32 (|q|^2 + |x|^2)  (L2),  2 (c16 + c32) |q||x|  (inner product)
     // dense output (the sample): out[local row, column], +inf beyond n_cols
     float *out;
@@ -155,8 +157,14 @@ mfma_tile_kernel(const FilterParams P)
     __shared__ float2 s_row[kFT];     // filter: (Rr, Xr); dense: (|q|^2, unused)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int64_t tile_r = (int64_t)blockIdx.y * kFT;                 // local row of the block
-    const int64_t strip_c = (int64_t)blockIdx.x * (kFT * kStrip);     // first column of the strip
+    // Workgroups are handed to the eight XCDs in turn, and each XCD has its own L2: the row tiles of
+    // one column strip are numbered so that they all run on the same XCD, one after the other, and
+    // the strip is fetched from memory once instead of once per row tile.
+    const int64_t within = blockIdx.x % (8 * P.row_tiles);
+    const int64_t strip = blockIdx.x / (8 * P.row_tiles) * 8 + within % 8;
+    if (strip >= P.n_strips) return;
+    const int64_t tile_r = within / 8 * kFT;                          // local row of the block
+    const int64_t strip_c = strip * (kFT * kStrip);                   // first column of the strip
     const int m0 = (wave >> 1) * 64, n0 = (wave & 1) * 64;
     const float inv = 1.0f / (scale_of(*P.q_maxbits) * scale_of(*P.x_maxbits));   // powers of two: exact
     const float half_inv = 0.5f / inv;
@@ -470,16 +478,17 @@ hipError_t launch_exact_filter(const float *X, int64_t N, int dim, int64_t ldX, 
         // step 2: the sample, dense, into the plain path's distance block; its t-th smallest per row
         FilterParams S = P;
         S.n_cols = pl.n_sample; S.col_step = pl.stride; S.out = plain_scratch; S.pitch = pl.sample_pitch;
-        hipLaunchKernelGGL(mfma_tile_kernel<true>,
-                           dim3((unsigned)((pl.sample_pitch + kFT * kStrip - 1) / (kFT * kStrip)), row_tiles), dim3(256), 0,
+        S.row_tiles = (int)row_tiles; S.n_strips = (pl.sample_pitch + kFT * kStrip - 1) / (kFT * kStrip);
+        hipLaunchKernelGGL(mfma_tile_kernel<true>, dim3((unsigned)((S.n_strips + 7) / 8 * 8 * row_tiles)), dim3(256), 0,
                            stream, S);
         launch_row_select(plain_scratch, pl.sample_pitch, rows, pl.t, thr_ids, thr_d, stream);
         // step 3
         hipLaunchKernelGGL(filter_fill_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, count, rows, 0u);
         FilterParams F = P;
         F.n_cols = N; F.col_step = 1;
-        hipLaunchKernelGGL(mfma_tile_kernel<false>,
-                           dim3((unsigned)((N + kFT * kStrip - 1) / (kFT * kStrip)), row_tiles), dim3(256), 0, stream, F);
+        F.row_tiles = (int)row_tiles; F.n_strips = (N + kFT * kStrip - 1) / (kFT * kStrip);
+        hipLaunchKernelGGL(mfma_tile_kernel<false>, dim3((unsigned)((F.n_strips + 7) / 8 * 8 * row_tiles)), dim3(256), 0,
+                           stream, F);
         // step 4
         hipLaunchKernelGGL(rerank_kernel, dim3((unsigned)rows), dim3(256), (size_t)dim * 4, stream, X, dim, ldX, metric,
                            Q, ldQ, r0, count, buf, P.thr, P.thr_stride, P.q_maxbits, P.x_maxbits, k, ids, dists, flags + b);
