@@ -591,8 +591,14 @@ def main() -> int:
         inter = sum(len(np.intersect1d(a, b)) for a, b in zip(gpu_ids[:ns], o_ids))
         same = gpu_ids[:ns] == o_ids
         rel = float(np.max(np.abs(gpu_d[:ns] - o_d)[same] / np.maximum(np.abs(o_d[same]), 1e-30))) if same.any() else 0.0
+        cpu_model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "unknown")
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": round(ns / cpu_s, 1), "unit": "queries/s", "cores": oracle.num_threads(),
-                               "kind": "oracle", "sample": f"first {ns} of the {B} queries, same graph, "
+                               "kind": "oracle", "cpu_model": cpu_model, "host_cpus": os.cpu_count(), "sample": f"first {ns} of the {B} queries, same graph, "
                                f"itopk={M}, search_width={P_WIDTH}, OpenMP over queries, "
                                f"{cpu_s:.2f}s per pass over the sample, {reps} passes"}
         out["parity_at_full_size"] = {"sample": ns, "id_agreement": round(inter / float(ns * w.k), 6),
