@@ -151,3 +151,25 @@ def test_prepared_search_gives_the_same_answers(cagra):
         hits += len(set(row.tolist()) & set(gt[b].tolist()))
         assert np.all(np.diff(dists.cpu().numpy()[0]) >= 0) and len(set(row.tolist())) == 10
     assert hits / 600.0 > 0.9
+
+
+@pytest.mark.parametrize("workers", [2, 4, 7])
+def test_lists_that_hold_every_node_give_the_exact_answer(cagra, workers):
+    # However the workers interleave: a node belongs to the worker that registered it first, and with
+    # local lists longer than the dataset no list ever drops a node, so every node reachable from the
+    # seeds ends up in exactly one list and the merged result is the exact k nearest of those.  On a
+    # strongly connected graph that is the brute-force answer, id for id (integer data: distances too).
+    import torch
+    n, nq, degree, k = 400, 60, 8, 10
+    w = datagen.workload("sift1m", n=n, n_queries=nq)
+    g = oracle.build(w.base, degree, 2 * degree, w.metric)
+    assert oracle.strong_components(g) == 1
+    ref_ids, ref_d = oracle.exact_search(w.base, w.queries, k, w.metric)
+    print(f"case multi exhaustive lists W={workers}", flush=True)
+    opts = cagra.SearchOptions(seed=21, mode=2, wg_per_query=workers, max_iterations=600)
+    ids, dists = cagra.search(torch.from_numpy(g.view(np.int32)).cuda(), torch.from_numpy(w.base).cuda(),
+                              torch.from_numpy(w.queries).cuda(), k, 512 * workers, 1, w.metric, opts)
+    plan = cagra.describe(degree, w.base.shape[1], nq, k, 512 * workers, 1, opts)
+    assert plan["itopk_local"] >= n and plan["wg_per_query"] == workers
+    np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), ref_ids)
+    np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
