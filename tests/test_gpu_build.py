@@ -236,3 +236,27 @@ def test_build_with_either_exact_algorithm_gives_the_same_graph(cagra):
         cagra.exact_search(b[:2000], b[:10], 8, algo=cagra.EXACT_FILTERED)      # N below 4096
     with pytest.raises(cagra.CagraError):
         cagra.exact_search(b, b[:10], 8, algo=7)
+
+
+def test_filtered_exact_search_with_padded_rows(cagra):
+    # rows further apart than dim (views into wider matrices), a dimension that the fp16 copies pad (48 -> 64)
+    import torch
+    w = datagen.workload("sift1m", n=9_000, n_queries=150)
+    dim = 48
+    base, queries = np.ascontiguousarray(w.base[:, :dim]), np.ascontiguousarray(w.queries[:, :dim])
+    wide_b = torch.full((base.shape[0], dim + 8), 9.0, dtype=torch.float32, device="cuda")
+    wide_b[:, :dim] = torch.from_numpy(base).cuda()
+    wide_q = torch.full((queries.shape[0], dim + 4), -3.0, dtype=torch.float32, device="cuda")
+    wide_q[:, :dim] = torch.from_numpy(queries).cuda()
+    print("case filtered: padded rows", flush=True)
+    redone = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    ids, dists = cagra.exact_search(wide_b[:, :dim], wide_q[:, :dim], 40, cagra.L2, algo=cagra.EXACT_FILTERED,
+                                    blocks_redone=redone)
+    ref, ref_d = oracle.exact_search(base, queries, 40, oracle.L2)
+    np.testing.assert_array_equal(_u32(ids), ref)
+    np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
+    assert int(redone.item()) == 0
+    # the k-NN graph over the padded view: the query rows are the dataset rows
+    g = cagra.exact_search(wide_b[:, :dim], wide_b[:, :dim], 24, cagra.L2, exclude_self=True, return_dists=False,
+                           algo=cagra.EXACT_FILTERED)
+    np.testing.assert_array_equal(_u32(g), oracle.knn_graph(base, 24, oracle.L2))
