@@ -42,7 +42,7 @@ typedef float floatx16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // 16 bytes in flight between global memory and LDS
 
 constexpr int kFT = 128;          // output tile edge (4 wavefronts, 64 x 64 each)
-constexpr int kFK = 64;           // dimensions staged per step
+constexpr int kFK = 64;           // dimensions staged per step (rows are padded to a multiple of 32)
 constexpr int kFRow = kFK + 8;    // halfs per staged row in LDS (144 bytes: 16-byte aligned, banks spread)
 constexpr int kStrip = 8;         // column tiles per workgroup
 constexpr int kCap = kFilterCap;  // candidate buffer entries per query row
@@ -184,7 +184,7 @@ mfma_tile_kernel(const FilterParams P)
     }
 
     // staging: 1024 16-byte pieces per operand and step, four per thread
-    const int n_chunks = P.dimP / kFK;
+    const int n_chunks = (P.dimP + kFK - 1) / kFK;       // dimP is a multiple of 32: the last step may be half a step
     int64_t n_tiles = (P.n_cols - strip_c + kFT - 1) / kFT;
     if (DENSE) n_tiles = (P.pitch - strip_c) / kFT;                   // the padding columns are written too
     if (n_tiles > kStrip) n_tiles = kStrip;
@@ -207,8 +207,9 @@ mfma_tile_kernel(const FilterParams P)
     {                                                                                                            \
         const int f_row = (tid + 256 * U) >> 3, f_part = (tid + 256 * U) & 7;                                    \
         const int64_t f_col = strip_c + (int64_t)f_tile * kFT + f_row;                                           \
-        va[U] = ok_a[U] ? *reinterpret_cast<const u32x4_t *>(src_a[U] + f_k0) : zero4;                             \
-        vx[U] = f_col < P.n_cols                                                                                 \
+        const bool f_in = f_part * 8 + f_k0 < P.dimP;                                                            \
+        va[U] = ok_a[U] && f_in ? *reinterpret_cast<const u32x4_t *>(src_a[U] + f_k0) : zero4;                   \
+        vx[U] = f_col < P.n_cols && f_in                                                                         \
                     ? *reinterpret_cast<const u32x4_t *>(P.X16 + f_col * P.col_step * P.dimP + f_part * 8 + f_k0) \
                     : zero4;                                                                                     \
     }
@@ -241,8 +242,10 @@ mfma_tile_kernel(const FilterParams P)
         __syncthreads();
         // (the last step fetches itself once more rather than branch around the loads)
         CAGRA_FETCH_STEP(step + 1 < total ? step + 1 : step)
+        const int k0 = (step % n_chunks) * kFK;
 #pragma unroll
         for (int ks = 0; ks < kFK / 16; ++ks) {
+            if (k0 + ks * 16 >= P.dimP) break;          // the half step: its second half holds zeros
             half8_t a[2], b[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -406,7 +409,7 @@ static size_t up256f(size_t v) { return (v + 255) & ~(size_t)255; }
 FilterPlan plan_exact_filter(int64_t N, int dim, int64_t B, int k, bool share_queries)
 {
     FilterPlan pl = {};
-    pl.dimP = (dim + kFK - 1) / kFK * kFK;
+    pl.dimP = (dim + 31) / 32 * 32;
     pl.block_rows = std::min<int64_t>(2048, (B + kFT - 1) / kFT * kFT);
     pl.stride = std::max<int64_t>(32, (N + (1 << 20) - 1) >> 20);
     pl.n_sample = (N + pl.stride - 1) / pl.stride;
