@@ -59,7 +59,7 @@ typedef enum {
     CAGRA_ERR_BAD_TOPK = -4,       /* k, itopk, search_width out of range */
     CAGRA_ERR_BAD_OPTION = -5,     /* a cagra_search_opts field is not supported */
     CAGRA_ERR_WORKSPACE = -6,      /* workspace missing, misaligned or too small */
-    CAGRA_ERR_HASH_CAPACITY = -7,  /* periodic-reset table cannot hold itopk + interval * width * degree at load 7/8 */
+    CAGRA_ERR_HASH_CAPACITY = -7,  /* periodic-reset table cannot hold what it receives between two resets at load 7/8 */
     CAGRA_ERR_LAUNCH = -8          /* the HIP runtime refused a launch */
 } cagra_status;
 
@@ -75,8 +75,9 @@ typedef struct {
                                  (Sec. IV-B.3); 0 automatic (the library picks a size, not necessarily a power
                                  of two) */
     int32_t reset_interval;   /* single mode, periodic-reset table: passes between resets, 0 automatic (the
-                                 largest for which itopk + interval * search_width * degree stays within 7/8 of
-                                 the table) */
+                                 largest for which both itopk + interval * search_width * degree and, for the
+                                 seeds and the passes before the first reset, (interval + 1) * search_width *
+                                 degree stay within 7/8 of the table) */
     int32_t wg_per_query;     /* multi mode: workgroups per query, 0 => search_width */
     int32_t table_entries;    /* single mode: entries of the LDS visited table given directly (multiple of 64,
                                  256..8192); 0 => from hash_bits.  Not both. */

@@ -122,10 +122,14 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
     pl.table_policy = reset ? 1 : 2;
     pl.reset_interval = 0;
     if (reset) {
+        // Between two resets the table receives the list (itopk ids) and `interval` passes of candidates; before
+        // the first reset, which follows pass `interval`, it receives the seeds and `interval` passes.
         const int capacity = words / 8 * 7;
         int interval = o.reset_interval;
-        if (interval == 0) interval = (capacity - itopk) / n_cand;
-        if (interval < 1 || itopk + (int64_t)interval * n_cand > capacity) return CAGRA_ERR_HASH_CAPACITY;
+        if (interval == 0) interval = std::min((capacity - itopk) / n_cand, capacity / n_cand - 1);
+        if (interval < 1 || itopk + (int64_t)interval * n_cand > capacity ||
+            ((int64_t)interval + 1) * n_cand > capacity)
+            return CAGRA_ERR_HASH_CAPACITY;
         pl.reset_interval = interval;
     }
 
@@ -219,7 +223,7 @@ const char *cagra_strerror(int code)
         case CAGRA_ERR_BAD_TOPK: return "k, itopk or search_width out of range";
         case CAGRA_ERR_BAD_OPTION: return "unsupported value in cagra_search_opts";
         case CAGRA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
-        case CAGRA_ERR_HASH_CAPACITY: return "visited table too small for itopk + interval * width * degree";
+        case CAGRA_ERR_HASH_CAPACITY: return "visited table too small for what it receives between two resets";
         case CAGRA_ERR_LAUNCH: return "HIP launch failed";
     }
     return "unknown cagra status";

@@ -46,6 +46,9 @@ def _cases():
     # 960-dimensional descriptors of Table I
     cases += [(48, 960, 16, 1, 64, 10, "f32", 0, 0, 0, 0), (49, 960, 16, 2, 100, 10, "f16", 0, 0, 8, 32),
               (50, 2048, 16, 1, 32, 10, "u8", 1, 0, 4, 0), (51, 1536, 32, 1, 64, 10, "f32", 2, 1024, 16, 0)]
+    # a periodic-reset table that just holds the list and two passes (32 + 2 * 96 of 224) but not the seeds and
+    # the two passes before the first reset (3 * 96): the automatic interval must be 1, and nothing overflows
+    cases += [(52, 16, 24, 4, 32, 32, "f16", 1, 256, 32, 0)]
     return cases
 
 
