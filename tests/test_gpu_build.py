@@ -260,3 +260,46 @@ def test_filtered_exact_search_with_padded_rows(cagra):
     g = cagra.exact_search(wide_b[:, :dim], wide_b[:, :dim], 24, cagra.L2, exclude_self=True, return_dists=False,
                            algo=cagra.EXACT_FILTERED)
     np.testing.assert_array_equal(_u32(g), oracle.knn_graph(base, 24, oracle.L2))
+
+
+def _filtered_cases():
+    rng = np.random.default_rng(123)
+    cases = []
+    for i in range(36):
+        n = int(rng.choice([4096, 5000, 8191, 12000]))
+        dim = int(rng.choice([4, 8, 20, 32, 36, 64, 96, 100, 128, 200]))
+        k = int(rng.choice([1, 7, 32, 64, 128, 300, 512]))
+        metric = int(rng.choice([0, 1]))
+        kind = str(rng.choice(["gauss", "ints", "unit", "clusters", "dups", "scaled", "sparse"]))
+        own = bool(rng.integers(0, 2))
+        cases.append((i, n, dim, k, metric, kind, own, int(rng.integers(0, 2**31))))
+    return cases
+
+
+@pytest.mark.parametrize("i,n,dim,k,metric,kind,own,seed", _filtered_cases())
+def test_filtered_exact_search_over_data_kinds(cagra, i, n, dim, k, metric, kind, own, seed):
+    # shapes off every tile size, value distributions that stress the filter: ties by the thousand, sparse rows,
+    # magnitudes from 1e-8 to 1e8; whatever the filter certifies or hands back, the answer is the oracle's
+    print(f"case filtered kinds {i}: n={n} dim={dim} k={k} metric={metric} {kind} own={own}", flush=True)
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n, dim)).astype(np.float32)
+    if kind == "ints":
+        x = np.clip(np.round(x * 20), -128, 127)
+    elif kind == "unit":
+        x /= np.linalg.norm(x, axis=1, keepdims=True)
+    elif kind == "clusters":
+        x = (rng.standard_normal((50, dim)) * 3)[rng.integers(0, 50, n)] + 0.2 * x
+    elif kind == "dups":
+        c = np.round(rng.standard_normal((int(rng.choice([3, 40, 1000])), dim)) * 5)
+        x = c[rng.integers(0, c.shape[0], n)]
+    elif kind == "scaled":
+        x = x * np.float32(10.0 ** rng.uniform(-8, 8))
+    elif kind == "sparse":
+        x = x * (rng.random((n, dim)) < 0.15)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if own:
+        _check_filtered(cagra, x, None, k, metric, exclude_self=True)
+    else:
+        nq = int(rng.choice([1, 100, 129]))
+        q = (x[rng.integers(0, n, nq)] + 0.05 * rng.standard_normal((nq, dim)) * np.abs(x).mean()).astype(np.float32)
+        _check_filtered(cagra, x, q, k, metric)

@@ -147,3 +147,58 @@ def test_wide_limits(cagra):
     with pytest.raises(cagra.CagraError):
         cagra.search(gd[:, :16].contiguous(), bd, qd, 10, 128, 65, cagra.L2, one)   # 65 parents
     torch.cuda.synchronize()
+
+
+def _mixed_cases():
+    # a second seeded batch over narrow and wide passes alike (search_width up to 64)
+    rng = np.random.default_rng(77)
+    cases = []
+    for i in range(150):
+        dim = int(rng.choice([16, 32, 48, 64, 96, 128, 208]))
+        degree = int(rng.choice([4, 8, 16, 24, 32, 48, 64]))
+        width = int(rng.choice([1, 2, 3, 4, 5, 6, 8, 11, 16, 23, 32, 64]))
+        while width * degree > 2048:
+            width //= 2
+        itopk = int(rng.choice([1, 5, 10, 16, 32, 33, 64, 100, 128, 256, 512]))
+        k = int(rng.choice([1, min(10, itopk), itopk]))
+        storage = str(rng.choice(["f32", "f32", "f16", "u8"]))
+        if storage == "u8" and dim % 16:
+            storage = "f16" if dim % 8 == 0 else "f32"
+        policy = int(rng.choice([0, 1, 2]))
+        entries = int(rng.choice([0, 0, 256, 1024, 4096, 8192]))
+        if policy == 1 and entries and max(itopk + width * degree, 2 * width * degree) > entries // 8 * 7:
+            entries = 0                      # a periodic-reset table must hold at least one window
+        team = int(rng.choice([0, 0, 4, 8, 16, 32]))
+        cases.append((i, dim, degree, width, itopk, k, storage, policy, entries, team))
+    return cases
+
+
+_mixed_built = {}
+
+
+def _mixed_index(dim, degree):
+    key = (dim, degree)
+    if key not in _mixed_built:
+        base = datagen.sift_like(2500, dim, 12, seed=500 + dim + degree, stream=1, rank=min(64, dim))
+        queries = datagen.sift_like(40, dim, 12, seed=500 + dim + degree, stream=2)
+        _mixed_built[key] = (base, queries, oracle.build(base, degree, 2 * degree))
+    return _mixed_built[key]
+
+
+@pytest.mark.parametrize("i,dim,degree,width,itopk,k,storage,policy,entries,team", _mixed_cases())
+def test_mixed_sweep(cagra, i, dim, degree, width, itopk, k, storage, policy, entries, team):
+    import torch
+    print(f"case mixed {i}: dim={dim} d={degree} p={width} M={itopk} k={k} {storage} policy={policy} "
+          f"entries={entries} team={team}", flush=True)
+    base, queries, g = _mixed_index(dim, degree)
+    dev_base = torch.from_numpy(base).cuda()
+    data = dev_base if storage == "f32" else cagra.convert_dataset(dev_base, cagra.F16 if storage == "f16" else cagra.U8)
+    opts = cagra.SearchOptions(seed=4000 + i, mode=1, table_policy=policy, table_entries=entries, team_size=team)
+    ids, dists, st = cagra.search(torch.from_numpy(g.view(np.int32)).cuda(), data, torch.from_numpy(queries).cuda(),
+                                  k, itopk, width, cagra.L2, opts, return_stats=True)
+    r_ids, r_d, r_st = oracle.search(g, base, queries, k, itopk, width, oracle.L2, seed=4000 + i, return_stats=True)
+    np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), r_ids)
+    np.testing.assert_array_equal(dists.cpu().numpy(), r_d)
+    st = st.cpu().numpy().view(np.uint32)
+    np.testing.assert_array_equal(st[:, :2], r_st[:, :2])
+    assert np.all(st[:, 2] >= r_st[:, 2]) and not np.any(st[:, 3] & 2)
