@@ -284,6 +284,58 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
 }
 
+// One chunk of a wide pass: up to 64 * CRC candidates (raw[], kInvalidId where there is none) through the
+// first-time test, the distance computation and the top-M update.
+template <int MR, int CRC, int KIND, int RIF>
+__device__ __forceinline__ void wide_chunk(const SearchParams &P, const uint32_t (&raw)[4], uint32_t *table,
+                                           float *qlds, uint32_t *newid, float *newdist,
+                                           uint32_t (&thi)[MR], uint32_t (&tlo)[MR], uint32_t &n_dist_total,
+                                           bool &forgot, bool &overflow, int &lead, int lane)
+{
+    const int table_words = P.table_words;
+    uint32_t *cursor = table + table_words;
+    const uint32_t sets = (uint32_t)table_words >> 2;
+    int n_new = 0;
+    bool lost = false;
+    bool fresh[CRC];
+    if constexpr (KIND == kTableSets) {
+        uint32_t set[CRC], way[CRC];
+#pragma unroll
+        for (int r = 0; r < CRC; ++r) fresh[r] = sets_lookup(table, sets, raw[r], raw[r] != kInvalidId, set[r]);
+        lds_order();
+#pragma unroll
+        for (int r = 0; r < CRC; ++r) way[r] = fresh[r] ? sets_insert(table, cursor, set[r], raw[r], forgot) : 0u;
+        lds_order();
+#pragma unroll
+        for (int r = 0; r < CRC; ++r) fresh[r] = fresh[r] && sets_confirm(table, cursor, set[r], way[r], raw[r], forgot, lost);
+    }
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) {
+        bool isnew = false;
+        if constexpr (KIND == kTableSets) isnew = fresh[r];
+        else if (raw[r] != kInvalidId) isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
+        const uint64_t m = __ballot(isnew);
+        const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        if (isnew) newid[pos] = raw[r];
+        n_new += __popcll(m);
+    }
+    n_dist_total += (uint32_t)n_new;
+    __syncthreads();
+    team_distances<kElem, RIF>(P.dataset, P.ld, P.dim, P.metric, P.team_log2, newid, n_new, qlds, newdist);
+    __syncthreads();
+    uint32_t chi[CRC], clo[CRC];
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) {
+        const int c = r * kWave + lane;
+        const bool v = c < n_new;
+        chi[r] = v ? f32_to_ordered(newdist[c]) : kDummyHi;
+        clo[r] = v ? (newid[c] << 1) : kInvalidId;
+    }
+    update_topm<MR, CRC, KIND == kTableSets>(thi, tlo, chi, clo, P.itopk, lost, forgot, newid, newdist, lane, lead);
+    __syncthreads();   // the update used newid / newdist as its staging space
+}
+
 // Candidate lists beyond 256 entries (search_width * degree up to 2048): the pass takes its
 // candidates in chunks of 256 (four per lane), each through the same first-time test, distance
 // computation and top-M update as a whole narrow pass.  The list after the last chunk holds the
@@ -344,47 +396,14 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
         for (int base = 0; base < n_src; base += kChunk) {
             // the next chunk's graph entries travel while this chunk's distances are computed
             if (base + kChunk < n_src) fetch(base + kChunk, nxt);
-            int n_new = 0;
-            bool lost = false;
-            bool fresh[CR];
-            if constexpr (KIND == kTableSets) {
-                uint32_t set[CR], way[CR];
-#pragma unroll
-                for (int r = 0; r < CR; ++r) fresh[r] = sets_lookup(table, sets, raw[r], raw[r] != kInvalidId, set[r]);
-                lds_order();
-#pragma unroll
-                for (int r = 0; r < CR; ++r) way[r] = fresh[r] ? sets_insert(table, cursor, set[r], raw[r], forgot) : 0u;
-                lds_order();
-#pragma unroll
-                for (int r = 0; r < CR; ++r) fresh[r] = fresh[r] && sets_confirm(table, cursor, set[r], way[r], raw[r], forgot, lost);
-            }
-#pragma unroll
-            for (int r = 0; r < CR; ++r) {
-                bool isnew = false;
-                if constexpr (KIND == kTableSets) isnew = fresh[r];
-                else if (raw[r] != kInvalidId) isnew = visited_insert(table, (uint32_t)table_words, raw[r], overflow);
-                const uint64_t m = __ballot(isnew);
-                const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                             __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                if (isnew) newid[pos] = raw[r];
-                n_new += __popcll(m);
-            }
-            n_dist_total += (uint32_t)n_new;
-            __syncthreads();
-            CAGRA_PHASE(1)
-            team_distances<kElem, RIF>(P.dataset, P.ld, P.dim, P.metric, P.team_log2, newid, n_new, qlds, newdist);
-            __syncthreads();
-            CAGRA_PHASE(2)
-            uint32_t chi[CR], clo[CR];
-#pragma unroll
-            for (int r = 0; r < CR; ++r) {
-                const int c = r * kWave + lane;
-                const bool v = c < n_new;
-                chi[r] = v ? f32_to_ordered(newdist[c]) : kDummyHi;
-                clo[r] = v ? (newid[c] << 1) : kInvalidId;
-            }
-            update_topm<MR, CR, KIND == kTableSets>(thi, tlo, chi, clo, P.itopk, lost, forgot, newid, newdist, lane, lead);
-            __syncthreads();   // the update used newid / newdist as its staging space
+            // a last chunk of at most 64 or 128 candidates takes the shorter code
+            const int left = n_src - base;
+            if (left <= kWave)
+                wide_chunk<MR, 1, KIND, RIF>(P, raw, table, qlds, newid, newdist, thi, tlo, n_dist_total, forgot, overflow, lead, lane);
+            else if (left <= 2 * kWave)
+                wide_chunk<MR, 2, KIND, RIF>(P, raw, table, qlds, newid, newdist, thi, tlo, n_dist_total, forgot, overflow, lead, lane);
+            else
+                wide_chunk<MR, 4, KIND, RIF>(P, raw, table, qlds, newid, newdist, thi, tlo, n_dist_total, forgot, overflow, lead, lane);
 #pragma unroll
             for (int r = 0; r < CR; ++r) raw[r] = nxt[r];
             CAGRA_PHASE(3)
