@@ -67,10 +67,11 @@ __device__ __forceinline__ bool visited_resolve_global(uint32_t *table, int bits
 constexpr int kRowsInFlight = CAGRA_ROWS_IN_FLIGHT;
 constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, registers do not
 // Wide passes of fp32 rows: the kernel is bound to 8 wavefronts per CU by its LDS, which leaves each
-// wavefront 256 VGPRs, enough for eight rows in flight (measured 1 to 2 % faster).  Not with the
-// longest lists or the narrow storage types, where eight rows would halve the wavefronts per CU.
+// wavefront 256 VGPRs, enough for eight rows in flight (measured 1 to 2 % faster).  Not with lists
+// beyond 128 entries or the narrow storage types, where eight rows would halve the wavefronts per CU
+// (or, for fp16, gain nothing).
 template <int ELEM, int MR>
-constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= 4) ? 8 : kRowsInFlight; }
+constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= 2) ? 8 : kRowsInFlight; }
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
