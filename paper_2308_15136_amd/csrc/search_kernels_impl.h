@@ -70,6 +70,10 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 // wavefront 256 VGPRs, enough for eight rows in flight (measured 1 to 2 % faster).  Not with lists
 // beyond 128 entries or the narrow storage types, where eight rows would halve the wavefronts per CU
 // (or, for fp16, gain nothing).
+// The same for the narrow kernel with 129 to 256 candidates per pass, whose larger table and candidate
+// buffers bind it to 8 wavefronts per CU as well.
+template <int ELEM, int MR, int CR>
+constexpr int rows_in_flight_single() { return (ELEM == 0 && MR <= 2 && CR == 4) ? 8 : kRowsInFlight; }
 template <int ELEM, int MR>
 constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= 2) ? 8 : kRowsInFlight; }
 
@@ -494,7 +498,7 @@ search_single_kernel(const SearchParams P)
 #ifdef CAGRA_PHASE_CLOCKS
         if (lane == 0 && qi < 131072u) g_query_times[2 * qi] = wall_clock64();
 #endif
-        search_body<MR, CR, KIND, kRowsInFlight>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+        search_body<MR, CR, KIND, rows_in_flight_single<ELEM, MR, CR>()>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                                    thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
 #ifdef CAGRA_PHASE_CLOCKS
