@@ -305,9 +305,11 @@ def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, m
 
 class PreparedSearch:
     """A search call with everything but the launch resolved once: tensors checked, options
-    marshalled, outputs and workspace allocated.  Calling it enqueues one search of the `queries`
-    buffer it was made for (write new queries into that buffer between calls) on the current stream
-    and returns (ids, dists): the same tensors every time.  For loops that issue many small calls."""
+    marshalled, outputs and workspace allocated.  Calling it enqueues one search on the current stream
+    and returns (ids, dists): the same tensors every time.  Without an argument it searches the
+    `queries` buffer it was made for (write new queries into that buffer between calls); with one it
+    searches that tensor instead (same shape, float32, same device; the caller keeps it alive until the
+    search has run).  For loops that issue many small calls."""
 
     def __init__(self, graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,
                  options: Optional[SearchOptions] = None):
@@ -327,12 +329,19 @@ class PreparedSearch:
                                                                      C.byref(self._copts)), dev)
         self._keep = (graph, dataset, queries)          # the call holds raw pointers into these
         self._device = dev
+        self._shape = tuple(queries.shape)
         self._args = (graph.data_ptr(), N, degree, dataset.data_ptr(), dataset.shape[1], dataset.stride(0), metric,
                       queries.data_ptr(), B, queries.stride(0), k, itopk, search_width, C.byref(self._copts),
                       self.ids.data_ptr(), self.dists.data_ptr(), self._ws.data_ptr(), self._ws.numel())
 
-    def __call__(self):
-        rc = self._lib.cagra_search(*self._args, _stream(self._device))
+    def __call__(self, queries=None):
+        args = self._args
+        if queries is not None:
+            queries = _dev_f32(queries, "queries")
+            if tuple(queries.shape) != self._shape or queries.device != self._device:
+                raise ValueError("queries must have the shape and device this call was prepared for")
+            args = args[:7] + (queries.data_ptr(), args[8], queries.stride(0)) + args[10:]
+        rc = self._lib.cagra_search(*args, _stream(self._device))
         if rc != 0:
             _check(rc, "cagra_search")
         return self.ids, self.dists

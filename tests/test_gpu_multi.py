@@ -139,6 +139,11 @@ def test_prepared_search_gives_the_same_answers(cagra):
         ids, dists = prepared()
         e_ids, e_d = cagra.search(gd, bd, qd[lo:lo + 50], 10, 64, 2, w.metric, opts)
         assert torch.equal(ids, e_ids) and torch.equal(dists, e_d)
+        ids, dists = prepared(qd[150 - lo:200 - lo])         # another tensor of the same shape, no copy
+        e_ids, e_d = cagra.search(gd, bd, qd[150 - lo:200 - lo], 10, 64, 2, w.metric, opts)
+        assert torch.equal(ids, e_ids) and torch.equal(dists, e_d)
+    with pytest.raises(ValueError):
+        prepared(qd[:49])
     # multi mode, one query at a time
     mopts = cagra.SearchOptions(seed=3, mode=2, wg_per_query=8, max_iterations=12)
     q1 = qd[:1].clone()
