@@ -547,6 +547,28 @@ search_single_wide_kernel(const SearchParams P)
     }
 }
 
+// Result of a multi-mode query from the heads of its workers' lists: the lists are sorted and disjoint, so
+// the first k of their union are among the first k of each.  W * k keys (at most 64 * R) are read in
+// one go, sorted and the first k written; `stride` is the distance between two lists in keys.
+template <int R>
+__device__ __forceinline__ void result_from_heads(const SearchParams &P, uint32_t qi, const uint64_t *lists, int stride)
+{
+    const int lane = lane_id();
+    const int heads = P.workers * P.k;
+    uint32_t hi[R], lo[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int idx = r * 64 + lane;
+        const int w = idx / P.k;
+        const bool valid = idx < heads;
+        const uint64_t key = valid ? __builtin_nontemporal_load(lists + (size_t)w * stride + (idx - w * P.k)) : 0ull;
+        hi[r] = valid ? (uint32_t)(key >> 32) : kDummyHi;
+        lo[r] = valid ? (uint32_t)key : kInvalidId;
+    }
+    bitonic_sort<R>(hi, lo, lane);
+    write_result<R>(P, qi, hi, lo);
+}
+
 template <int ELEM, int MR, int CR>
 __global__ void __launch_bounds__(kWave)
 search_multi_kernel(const SearchParams P)
@@ -576,8 +598,18 @@ search_multi_kernel(const SearchParams P)
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (uint32_t)P.workers - 1u) return;
     __threadfence();
-    // last worker: fold the other lists into its own, one bitonic merge each; the lists are read
-    // four at a time so that their latencies overlap
+    // last worker.  Few enough heads (W * k <= 512): one sort of the first k of every list
+    const int heads = P.workers * P.k;
+    if (heads <= 512) {
+        const uint64_t *first = P.lists + (size_t)qi * P.workers * (64 * MR);
+        if (heads <= 64) result_from_heads<1>(P, qi, first, 64 * MR);
+        else if (heads <= 128) result_from_heads<2>(P, qi, first, 64 * MR);
+        else if (heads <= 256) result_from_heads<4>(P, qi, first, 64 * MR);
+        else result_from_heads<8>(P, qi, first, 64 * MR);
+        return;
+    }
+    // otherwise fold the other lists into its own, one bitonic merge each; the lists are read four at a
+    // time so that their latencies overlap
     constexpr int kFold = 4;
     for (int w0 = 0; w0 < P.workers; w0 += kFold) {
         uint64_t key[kFold][MR];
