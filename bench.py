@@ -496,7 +496,7 @@ def main() -> int:
     # the minimum list of 32); recall is measured on the first 1000 queries in one call (the seed of
     # a query depends on its index in the call, so that is a separate, untimed launch).
     if not args.no_latency:
-        lat_configs = [(args.latency_workers, 0)] + [(W, i) for W in (8, 16, 32, 64) for i in (3, 4, 5, 6, 8, 12, 16)]
+        lat_configs = [(args.latency_workers, 0)] + [(W, i) for W in (8, 16, 32, 64) for i in (3, 4, 5, 6, 8, 10, 12, 16)]
         nq_rec = min(1000, B)
         small = []
         for W, imax in lat_configs:

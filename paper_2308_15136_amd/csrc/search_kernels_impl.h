@@ -598,14 +598,15 @@ search_multi_kernel(const SearchParams P)
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (uint32_t)P.workers - 1u) return;
     __threadfence();
-    // last worker.  Few enough heads (W * k <= 512): one sort of the first k of every list
+    // last worker.  Few enough heads (W * k <= 1024): one sort of the first k of every list
     const int heads = P.workers * P.k;
-    if (heads <= 512) {
+    if (heads <= 1024) {
         const uint64_t *first = P.lists + (size_t)qi * P.workers * (64 * MR);
         if (heads <= 64) result_from_heads<1>(P, qi, first, 64 * MR);
         else if (heads <= 128) result_from_heads<2>(P, qi, first, 64 * MR);
         else if (heads <= 256) result_from_heads<4>(P, qi, first, 64 * MR);
-        else result_from_heads<8>(P, qi, first, 64 * MR);
+        else if (heads <= 512) result_from_heads<8>(P, qi, first, 64 * MR);
+        else result_from_heads<16>(P, qi, first, 64 * MR);
         return;
     }
     // otherwise fold the other lists into its own, one bitonic merge each; the lists are read four at a
