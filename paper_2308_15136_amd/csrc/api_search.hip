@@ -115,6 +115,10 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
         // 128, 4096 beyond (wider passes insert more per pass, and their candidate buffers already cost
         // wavefronts per CU)
         words = n_cand <= 64 ? kAutoSetTableEntries : n_cand <= 128 ? kAutoSetTableEntries + 512 : kAutoSetTableEntries + 1024;
+        // a long query (many dimensions) must not push the workgroup over an eighth of the CU's LDS: the
+        // eighth wavefront is worth more than the last 512 table entries
+        const size_t rest = (size_t)4 * ((dim + 3) & ~3) + (size_t)8 * 64 * pl.cr + 256;
+        while (words > kAutoSetTableEntries && (size_t)4 * words + words / 4 + 16 + rest > (size_t)160 * 1024 / 8) words -= 512;
         // (also beyond 256 candidates: measured with 320 to 2048 per pass, larger tables lose more to the
         // wavefronts they displace than they save in distances computed twice)
     }
