@@ -171,13 +171,13 @@ size_t cagra_exact_search_workspace_bytes(int64_t N, int64_t B, int32_t k);
 
 /* How the exhaustive search does its arithmetic; the result is the same bit for bit. */
 typedef enum {
-    CAGRA_EXACT_AUTO = 0,      /* filtered for N >= 131072, else plain */
+    CAGRA_EXACT_AUTO = 0,      /* filtered for N >= 131072 (and dim <= 8192), else plain */
     CAGRA_EXACT_PLAIN = 1,     /* every distance by the fused multiply-add chain on the vector units */
     CAGRA_EXACT_FILTERED = 2   /* approximate distances from fp16 copies on the matrix cores (MFMA) pick a few
                                   thousand candidates per query, the chain ranks those; a block of query rows for
                                   which that cannot be shown to give the exact answer (the candidate buffer
                                   overflowed, or fewer than k candidates lie below the filter threshold) is done
-                                  again by the plain kernels inside the same call.  N >= 4096 */
+                                  again by the plain kernels inside the same call.  N >= 4096, dim <= 8192 */
 } cagra_exact_algo;
 
 /* cagra_exact_search with the choice of algorithm (cagra_exact_search itself is the plain one).  The

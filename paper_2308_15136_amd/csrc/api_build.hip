@@ -108,18 +108,21 @@ int cagra_exact_search(const float *dataset, int64_t N, int32_t dim, int64_t ld,
 }
 
 // The algorithm a request resolves to: 1 plain, 2 filtered; 0 for an unusable request.
-static int resolve_exact_algo(int algo, int64_t N)
+// (the filtered algorithm keeps a query row in LDS beside its 32 KB sorting buffer: dim <= 8192)
+static int resolve_exact_algo(int algo, int64_t N, int dim)
 {
-    if (algo == CAGRA_EXACT_AUTO) return N >= 131072 ? CAGRA_EXACT_FILTERED : CAGRA_EXACT_PLAIN;
+    constexpr int kMaxFilteredDim = 8192;
+    if (algo == CAGRA_EXACT_AUTO)
+        return N >= 131072 && dim <= kMaxFilteredDim ? CAGRA_EXACT_FILTERED : CAGRA_EXACT_PLAIN;
     if (algo == CAGRA_EXACT_PLAIN) return CAGRA_EXACT_PLAIN;
-    if (algo == CAGRA_EXACT_FILTERED && N >= 4096) return CAGRA_EXACT_FILTERED;
+    if (algo == CAGRA_EXACT_FILTERED && N >= 4096 && dim <= kMaxFilteredDim) return CAGRA_EXACT_FILTERED;
     return 0;
 }
 
 size_t cagra_exact_search_ex_workspace_bytes(int64_t N, int32_t dim, int64_t B, int32_t k, cagra_exact_algo algo)
 {
     const size_t plain = cagra_exact_search_workspace_bytes(N, B, k);
-    if (N < 1 || B < 1 || k < 1 || dim < 1 || resolve_exact_algo((int)algo, N) != CAGRA_EXACT_FILTERED) return plain;
+    if (N < 1 || B < 1 || k < 1 || dim < 1 || resolve_exact_algo((int)algo, N, dim) != CAGRA_EXACT_FILTERED) return plain;
     // sized for distinct queries; a call with queries == dataset needs less and accepts this too
     return plain + plan_exact_filter(N, dim, B, k, false).bytes;
 }
@@ -131,7 +134,7 @@ int cagra_exact_search_ex(const float *dataset, int64_t N, int32_t dim, int64_t 
                           void *hip_stream)
 {
     if (N < 1) return CAGRA_ERR_BAD_SHAPE;
-    const int resolved = resolve_exact_algo((int)algo, N);
+    const int resolved = resolve_exact_algo((int)algo, N, dim);
     if (resolved == 0) return CAGRA_ERR_BAD_OPTION;
     if (resolved == CAGRA_EXACT_PLAIN) {
         int rc = cagra_exact_search(dataset, N, dim, ld, metric, queries, B, ld_queries, k, exclude_self, self_offset,
@@ -246,7 +249,7 @@ int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cag
     if (init_degree == 0) init_degree = 2 * degree;
     if (o.reorder != CAGRA_REORDER_RANK && o.reorder != CAGRA_REORDER_DISTANCE) return CAGRA_ERR_BAD_OPTION;
     if (o.initial_graph != 0 && o.initial_graph != 1) return CAGRA_ERR_BAD_OPTION;
-    if (o.initial_graph == 0 && resolve_exact_algo(o.exact_algo, N) == 0) return CAGRA_ERR_BAD_OPTION;
+    if (o.initial_graph == 0 && resolve_exact_algo(o.exact_algo, N, dim) == 0) return CAGRA_ERR_BAD_OPTION;
     if (!dataset || !graph_out) return CAGRA_ERR_NULL_POINTER;
     if (N < 2) return CAGRA_ERR_BAD_SHAPE;
     int rc = check_matrix(dataset, N, dim, ld);
@@ -274,7 +277,7 @@ int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cag
         const int rounds = o.nnd_rounds <= 0 ? nn_descent_auto_rounds(N) : o.nnd_rounds;
         e = launch_nn_descent(dataset, N, dim, ld, (int)metric, init_degree, rounds, sample, o.seed, knn, knn_dists,
                               rest, stream);
-    } else if (resolve_exact_algo(o.exact_algo, N) == CAGRA_EXACT_FILTERED) {
+    } else if (resolve_exact_algo(o.exact_algo, N, dim) == CAGRA_EXACT_FILTERED) {
         const FilterPlan pl = plan_exact_filter(N, dim, N, init_degree, true);
         e = launch_exact_filter(dataset, N, dim, ld, (int)metric, dataset, N, ld, init_degree, 1, 0, knn, knn_dists,
                                 reinterpret_cast<float *>(rest), exact_block_rows(N, N),
