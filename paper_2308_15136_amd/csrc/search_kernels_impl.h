@@ -378,6 +378,8 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
     uint32_t n_iter = 0, n_parent_total = 0, n_dist_total = 0, flags = 0;
     bool overflow = false, forgot = false;
     int lead = 0, n_par = 0;
+    // ceil(2^32 / degree); a wide pass has more than 256 candidates from at most 64 parents, so degree >= 5
+    const uint32_t degree_magic = 0xFFFFFFFFu / (uint32_t)P.degree + 1u;
 
     CAGRA_PHASE(0)
     for (int it = 0;; ++it) {
@@ -390,7 +392,7 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
                 if (it == 0) {
                     dst[r] = c < n_src ? seed_slot_id(qh, (uint64_t)c, (uint64_t)P.N) : kInvalidId;
                 } else {
-                    const int pi = c / P.degree;
+                    const int pi = (int)__umulhi((uint32_t)c, degree_magic);   // c / degree, exact for c < 2^16
                     const bool v = c < n_src;
                     dst[r] = v ? P.graph[(size_t)parents[v ? pi : 0] * P.degree + (c - pi * P.degree)] : kInvalidId;
                 }
