@@ -158,6 +158,10 @@ static int single_per_cu(const cagra_search_opts &o, const SinglePlan &pl, const
     return std::max(per_cu, 1);
 }
 
+#ifndef CAGRA_MULTI_TABLE_FACTOR
+#define CAGRA_MULTI_TABLE_FACTOR 4
+#endif
+
 struct MultiPlan {
     int mr, cr, workers, itopk_local, hash_bits, team_log2, max_iterations;
     size_t smem, table_bytes, list_bytes, done_bytes;
@@ -166,7 +170,9 @@ struct MultiPlan {
 
 // Several workgroups per query (Sec. IV-C.2).  Every worker expands one parent per pass and
 // keeps a list of max(k, 32, ceil(itopk / workers)) entries; the shared table is sized for
-// twice the ids the workers can ever offer (Sec. IV-B.3).
+// at least four times the ids the workers can ever offer (Sec. IV-B.3 asks for twice; the sparser
+// table saves second probes, each a round trip to device memory, and a call of one query is
+// bound by such round trips).
 static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int width,
                       const cagra_search_opts &o, MultiPlan &pl)
 {
@@ -189,7 +195,7 @@ static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int widt
     pl.max_iterations = o.max_iterations == 0 ? auto_max_iterations(local, 1) : o.max_iterations;
     const int64_t offered = (int64_t)pl.workers * degree * ((int64_t)pl.max_iterations + 1);
     int bits = 10;
-    while (bits < 27 && ((int64_t)1 << bits) < 2 * offered) ++bits;
+    while (bits < 27 && ((int64_t)1 << bits) < CAGRA_MULTI_TABLE_FACTOR * offered) ++bits;
     if (bits > 26) return CAGRA_ERR_HASH_CAPACITY;
     pl.hash_bits = bits;
     pl.table_bytes = align256(((size_t)B << bits) * 4);
