@@ -303,3 +303,22 @@ def test_filtered_exact_search_over_data_kinds(cagra, i, n, dim, k, metric, kind
         nq = int(rng.choice([1, 100, 129]))
         q = (x[rng.integers(0, n, nq)] + 0.05 * rng.standard_normal((nq, dim)) * np.abs(x).mean()).astype(np.float32)
         _check_filtered(cagra, x, q, k, metric)
+
+
+def test_filtered_exact_search_falls_back_across_slices(cagra):
+    # More than 2^20 dataset rows that are copies of a few vectors: the filter cannot certify, and the plain
+    # kernels that take the block back walk the dataset in slices, carrying the k best from slice to slice.
+    import torch
+    rng = np.random.default_rng(17)
+    n, dim, k = 1_150_000, 16, 70
+    protos = rng.integers(0, 40, size=(5, dim)).astype(np.float32)
+    base = protos[rng.integers(0, 5, size=n)]
+    queries = (protos[[0, 3, 4]] + np.float32(0.5)).astype(np.float32)
+    print("case filtered: duplicates beyond one slice of dataset rows", flush=True)
+    bd = _dev(base)
+    redone = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ids, dists = cagra.exact_search(bd, _dev(queries), k, cagra.L2, algo=cagra.EXACT_FILTERED, blocks_redone=redone)
+    ref, ref_d = oracle.exact_search(base, queries, k, oracle.L2)
+    np.testing.assert_array_equal(_u32(ids), ref)
+    np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
+    assert int(redone.item()) == 1
