@@ -223,6 +223,9 @@ def test_filtered_exact_search_falls_back_when_it_cannot_certify(cagra):
     print("case filtered: massive duplicates", flush=True)
     _check_filtered(cagra, base, queries, 100, oracle.L2, expect_redone=True)
     _check_filtered(cagra, base, None, 16, oracle.L2, exclude_self=True, expect_redone=True)
+    # the same without a distance output: the plain kernels keep their running distances in the workspace
+    ids = cagra.exact_search(_dev(base), _dev(queries), 100, cagra.L2, return_dists=False, algo=cagra.EXACT_FILTERED)
+    np.testing.assert_array_equal(_u32(ids), oracle.exact_search(base, queries, 100, oracle.L2)[0])
 
 
 def test_build_with_either_exact_algorithm_gives_the_same_graph(cagra):
