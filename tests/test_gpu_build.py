@@ -235,6 +235,9 @@ def test_build_with_either_exact_algorithm_gives_the_same_graph(cagra):
     filtered = cagra.build(b, 32, 64, w.metric, exact_algo=cagra.EXACT_FILTERED)
     np.testing.assert_array_equal(_u32(plain), _u32(filtered))
     np.testing.assert_array_equal(_u32(filtered), oracle.build(w.base, 32, 64, w.metric))
+    # distance-based reordering takes the distances of the initial graph from the filtered search's re-rank
+    by_dist = cagra.build(b, 32, 64, w.metric, reorder=cagra.REORDER_DISTANCE, exact_algo=cagra.EXACT_FILTERED)
+    np.testing.assert_array_equal(_u32(by_dist), oracle.build(w.base, 32, 64, w.metric, reorder=oracle.DISTANCE))
     with pytest.raises(cagra.CagraError):
         cagra.exact_search(b[:2000], b[:10], 8, algo=cagra.EXACT_FILTERED)      # N below 4096
     with pytest.raises(cagra.CagraError):
