@@ -255,7 +255,8 @@ def main() -> int:
     achieved = ab["total_bytes"] / (dev_ms * 1e-3) / 1e9
 
     out = {
-        "metric": "QPS at recall@10>=0.95 (1Mx128, batch 10k)", "value": round(value, 1), "unit": "queries/s",
+        "metric": "QPS at recall@10>=0.95 (1Mx128, batch 10k)" if (w.name == "sift1m" and N == 1_000_000 and B == 10_000)
+        else f"QPS at recall@{w.k}>={TARGET_RECALL} ({N}x{dim}, batch {B})", "value": round(value, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
@@ -551,7 +552,8 @@ def main() -> int:
             lat = np.empty(200)
             hit_graph = hit_eager = 0
             for c in range(-10, 200):
-                src = queries[max(c, 0):max(c, 0) + 1]
+                qi_r = max(c, 0) % B
+                src = queries[qi_r:qi_r + 1]
                 t_c = time.perf_counter()
                 q_fix.copy_(src)
                 hg.replay()
@@ -561,9 +563,9 @@ def main() -> int:
                 if c >= 0:
                     # several workers interleave differently from run to run, so replay and eager call are
                     # compared by their recall over the same 200 queries, not id by id
-                    hit_graph += len(np.intersect1d(g_ids.cpu().numpy().view(np.uint32)[0], gt_np[c]))
+                    hit_graph += len(np.intersect1d(g_ids.cpu().numpy().view(np.uint32)[0], gt_np[qi_r]))
                     e_ids, _ = cagra.search(graph, base, src, w.k, 32 * W, 1, w.metric, mopts)
-                    hit_eager += len(np.intersect1d(e_ids.cpu().numpy().view(np.uint32)[0], gt_np[c]))
+                    hit_eager += len(np.intersect1d(e_ids.cpu().numpy().view(np.uint32)[0], gt_np[qi_r]))
             best_lat["graph_replay"] = {"p50_us": round(float(np.percentile(lat, 50)), 1),
                                         "p99_us": round(float(np.percentile(lat, 99)), 1),
                                         "recall_replayed": round(hit_graph / (200.0 * w.k), 4),
