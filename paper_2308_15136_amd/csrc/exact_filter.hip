@@ -264,7 +264,7 @@ mfma_tile_kernel(const FilterParams P)
         // the tile is complete.  Result layout: register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4,
         // column l % 32
         const int64_t tile_c = strip_c + (int64_t)tile * kFT;
-        uint64_t hits = 0;                     // filter: bit nb * 32 + ma * 16 + r of this lane passed the test
+        uint32_t hits[2] = {0u, 0u};           // filter: bit ma * 16 + r of hits[nb]: that output of this lane passed the test
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
             const int64_t col = tile_c + n0 + nb * 32 + (lane & 31);
@@ -288,14 +288,15 @@ mfma_tile_kernel(const FilterParams P)
                             P.out[lr * P.pitch + col] = col_ok ? approx : inf;
                         }
                     } else if (v >= fmaf(0.0f - rc.y, sx, rc.x + cn) && col_ok) {
-                        hits |= 1ull << (nb * 32 + ma * 16 + r);
+                        hits[nb] |= 1u << (ma * 16 + r);
                     }
                 }
         }
         // the few that passed (about one in a thousand): append to the row's candidates
-        while (hits != 0ull) {
-            const int bit = __builtin_ctzll(hits);
-            hits &= hits - 1;
+        uint64_t todo = ((uint64_t)hits[1] << 32) | hits[0];
+        while (todo != 0ull) {
+            const int bit = __builtin_ctzll(todo);
+            todo &= todo - 1;
             const int nb = bit >> 5, ma = (bit >> 4) & 1, r = bit & 15;
             const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
             const int64_t lr = tile_r + lrow, grow = P.q_row0 + lr;
