@@ -74,6 +74,8 @@ def _load():
                                       u64, i32, i32, i32, u32p, f32p, u32p]
         lib.oracle_search_multi.argtypes = [u32p, i64, i32, f32p, i32, i32, f32p, i64, i32, i32,
                                             i32, u64, i32, i32, u32p, f32p, u32p]
+        lib.oracle_search_multi_lists.argtypes = [u32p, i64, i32, f32p, i32, i32, f32p, i64, i32, i32,
+                                                  i32, u64, i32, i32, u32p, f32p, u32p, u32p]
         lib.oracle_num_threads.restype = i32
         _lib = lib
     return _lib
@@ -278,13 +280,23 @@ def search(graph, base, queries, k: int, itopk: int, search_width: int = 1, metr
 
 def search_multi(graph, base, queries, k: int, local_topk: int, n_workers: int, metric: int = L2,
                  seed: int = 0, max_iterations: int = 64, n_threads: int = 0,
-                 return_stats: bool = False):
-    """Multi-CTA search, workers simulated in lock step."""
+                 return_stats: bool = False, return_lists: bool = False):
+    """Multi-CTA search, workers simulated in lock step.  return_lists: also every worker's final
+    list of ids, [B, n_workers, local_topk] (appended to the returned tuple)."""
     graph, base, queries = _u32(graph), _f32(base), _f32(queries)
     B = queries.shape[0]
     ids = np.empty((B, k), np.uint32)
     dists = np.empty((B, k), np.float32)
     stats = np.zeros((B, 4), np.uint32)
+    if return_lists:
+        lists = np.empty((B, n_workers, local_topk), np.uint32)
+        _check(_load().oracle_search_multi_lists(_p(graph, C.c_uint32), base.shape[0], graph.shape[1],
+                                                 _p(base, C.c_float), base.shape[1], metric,
+                                                 _p(queries, C.c_float), B, k, local_topk, n_workers, seed,
+                                                 max_iterations, n_threads, _p(ids, C.c_uint32),
+                                                 _p(dists, C.c_float), _p(stats, C.c_uint32),
+                                                 _p(lists, C.c_uint32)), "search_multi_lists")
+        return (ids, dists, stats, lists) if return_stats else (ids, dists, lists)
     _check(_load().oracle_search_multi(_p(graph, C.c_uint32), base.shape[0], graph.shape[1],
                                        _p(base, C.c_float), base.shape[1], metric,
                                        _p(queries, C.c_float), B, k, local_topk, n_workers, seed,

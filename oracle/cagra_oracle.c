@@ -37,10 +37,16 @@
  * definition of Eq. 3 re-derived from set membership, graph invariants,
  * BFS-closure equivalence of the search when M >= N, complete-graph search =
  * exact top-k, forgetting-independence of the result, published SplitMix64
- * outputs for the seed generator.
+ * outputs for the seed generator.  The multi-worker search: one worker equals
+ * the single search; lists longer than the dataset on a strongly connected
+ * graph give the float64 brute-force answer with every node in exactly one
+ * list; a one-pass run followed by hand (seed slots per worker, ownership in
+ * worker order, distance count); the result recomputed as the first k of the
+ * union of the returned, disjoint worker lists.
  * parity unpinned: the worked example of Fig. 2 (the figure's ranks are not
- * recoverable); the multi-worker search is pinned by invariants only (W = 1
- * equals the single search; outputs sorted, unique, self-consistent).
+ * recoverable).  The lock-step order of the workers is this oracle's reading;
+ * a GPU interleaves them differently, so against the GPU only what does not
+ * depend on the order is compared id for id.
  */
 #include <float.h>
 #include <math.h>
@@ -673,7 +679,7 @@ static void search_one(const uint32_t *graph, int64_t N, int32_t d, const float 
                        int32_t metric, const float *q, int64_t qi, int32_t k, int32_t M_local,
                        int32_t p, int32_t W, uint64_t seed, int32_t max_iter,
                        int32_t reset_interval, visited_t *vis, worker_t *wk,
-                       uint32_t *ids, float *dists, uint32_t *stats)
+                       uint32_t *ids, float *dists, uint32_t *stats, uint32_t *lists)
 {
     uint32_t n_dist = 0, n_parent = 0, n_iter = 0, hit_cap = 0;
     const int n_cand = p * d;
@@ -726,6 +732,10 @@ static void search_one(const uint32_t *graph, int64_t N, int32_t d, const float 
         if (!live) break;
         ++n_iter;
     }
+    /* for inspection: every worker's final list, ids only, [W, M_local] */
+    if (lists)
+        for (int w = 0; w < W; ++w)
+            for (int t = 0; t < M_local; ++t) lists[(size_t)w * M_local + t] = wk[w].buf[t].id;
     /* output: the first k under T of the union of the workers' lists */
     if (W == 1) {
         for (int t = 0; t < k; ++t) {
@@ -756,7 +766,7 @@ static int search_batch(const uint32_t *graph, int64_t N, int32_t d, const float
                         int32_t metric, const float *Q, int64_t B, int32_t k, int32_t M_local,
                         int32_t p, int32_t W, uint64_t seed, int32_t max_iter,
                         int32_t reset_interval, int32_t n_threads,
-                        uint32_t *ids, float *dists, uint32_t *stats)
+                        uint32_t *ids, float *dists, uint32_t *stats, uint32_t *lists)
 {
     if (!graph || !X || !Q || !ids || !dists) return -1;
     if (N < 1 || N >= ((int64_t)1 << 31) || d < 1 || dim < 1 || B < 0) return -1;
@@ -787,7 +797,8 @@ static int search_batch(const uint32_t *graph, int64_t N, int32_t d, const float
             if (!ok) continue;
             search_one(graph, N, d, X, dim, metric, Q + (size_t)b * dim, b, k, M_local, p, W, seed,
                        max_iter, reset_interval, &vis, wk, ids + (size_t)b * k,
-                       dists + (size_t)b * k, stats ? stats + (size_t)b * 4 : NULL);
+                       dists + (size_t)b * k, stats ? stats + (size_t)b * 4 : NULL,
+                       lists ? lists + (size_t)b * W * M_local : NULL);
         }
         if (wk) for (int w = 0; w < W; ++w) free(wk[w].buf);
         free(wk);
@@ -806,7 +817,7 @@ int oracle_search(const uint32_t *graph, int64_t N, int32_t d, const float *X, i
     if (k > itopk) return -1;
     if (max_iter == 0) max_iter = oracle_auto_max_iterations(itopk, search_width);
     return search_batch(graph, N, d, X, dim, metric, Q, B, k, itopk, search_width, 1, seed,
-                        max_iter, reset_interval, n_threads, ids, dists, stats);
+                        max_iter, reset_interval, n_threads, ids, dists, stats, NULL);
 }
 
 /* Multi-CTA search (Sec. IV-C.2): W workers, p = 1 each, local lists of M_local. */
@@ -817,7 +828,20 @@ int oracle_search_multi(const uint32_t *graph, int64_t N, int32_t d, const float
 {
     if (max_iter <= 0) return -1;
     return search_batch(graph, N, d, X, dim, metric, Q, B, k, M_local, 1, W, seed, max_iter, 0,
-                        n_threads, ids, dists, stats);
+                        n_threads, ids, dists, stats, NULL);
+}
+
+/* The same, also returning every worker's final list (ids, [B, W, M_local]; unused slots
+ * ORACLE_INVALID_ID) so that the seed layout, the ownership of nodes and the final merge can
+ * be checked from outside. */
+int oracle_search_multi_lists(const uint32_t *graph, int64_t N, int32_t d, const float *X, int32_t dim,
+                              int32_t metric, const float *Q, int64_t B, int32_t k, int32_t M_local,
+                              int32_t W, uint64_t seed, int32_t max_iter, int32_t n_threads,
+                              uint32_t *ids, float *dists, uint32_t *stats, uint32_t *lists)
+{
+    if (max_iter <= 0 || !lists) return -1;
+    return search_batch(graph, N, d, X, dim, metric, Q, B, k, M_local, 1, W, seed, max_iter, 0,
+                        n_threads, ids, dists, stats, lists);
 }
 
 int32_t oracle_num_threads(void)

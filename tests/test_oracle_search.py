@@ -244,3 +244,102 @@ def test_argument_checks():
     with pytest.raises(ValueError):
         oracle.build(w.base, 7, 14)                          # odd degree
     assert oracle.auto_max_iterations(64, 1) == 160
+
+
+# ---- several workers per query (Sec. IV-C.2) ----------------------------------------------------
+
+def _multi_case(n=300, dim=16, nq=30, degree=8, seed=31):
+    base, qs = _int_data(n, dim, nq, seed)
+    g = oracle.build(base, degree, 2 * degree)
+    return base, qs, g
+
+
+@pytest.mark.parametrize("workers", [2, 4, 7])
+def test_multi_worker_lists_that_hold_every_node_give_brute_force(workers):
+    # Local lists longer than the dataset never drop a node; on a strongly connected graph every node
+    # is reached and owned by exactly one worker, so the merged answer is the exact one (float64 brute
+    # force on integer data, ties by id).  A merge that leaves a worker out cannot pass.
+    base, qs, g = _multi_case()
+    n = base.shape[0]
+    assert oracle.strong_components(g) == 1
+    k = 10
+    ids, dists, st, lists = oracle.search_multi(g, base, qs, k, n, workers, seed=3, max_iterations=10 * n,
+                                                return_stats=True, return_lists=True)
+    contributed = set()
+    for b in range(qs.shape[0]):
+        d64 = _exact_keys(base, qs[b])
+        order = sorted(range(n), key=lambda i: (d64[i], i))[:k]
+        assert ids[b].tolist() == order
+        assert dists[b].astype(np.float64).tolist() == [d64[i] for i in order]
+        # every node sits in exactly one worker's list
+        held = lists[b][lists[b] != oracle.INVALID_ID]
+        assert sorted(held.tolist()) == list(range(n))
+        owner = {int(v): w for w in range(workers) for v in lists[b, w] if v != oracle.INVALID_ID}
+        contributed |= {owner[i] for i in order}
+    assert st[:, 2].tolist() == [n] * qs.shape[0]          # every node measured exactly once
+    assert not st[:, 3].any()
+    assert len(contributed) == workers                      # over the batch every worker fed the result
+
+
+@pytest.mark.parametrize("workers", [2, 5])
+def test_multi_worker_one_pass_by_hand(workers):
+    # One pass (I_max = 1) followed here by hand: worker w draws the seed slots w*d .. w*d + d - 1, a node
+    # belongs to the first worker (in the order 0, 1, ...) that draws it, every worker then expands its
+    # nearest seed, again worker 0 first.  The lists, the number of distances and the result follow.
+    base, qs, g = _multi_case(n=500, nq=20, seed=32)
+    n, d, k, local = base.shape[0], g.shape[1], 5, 64
+    ids, dists, st, lists = oracle.search_multi(g, base, qs, k, local, workers, seed=9, max_iterations=1,
+                                                return_stats=True, return_lists=True)
+    for b in range(qs.shape[0]):
+        d64 = _exact_keys(base, qs[b])
+        seen, own = set(), [[] for _ in range(workers)]
+        for w in range(workers):
+            for t in range(d):
+                v = _seed_id(9, b, w * d + t, n)
+                if v not in seen:
+                    seen.add(v)
+                    own[w].append(v)
+        n_seeds = len(seen)
+        parents = []
+        for w in range(workers):
+            par = min(own[w], key=lambda i: (d64[i], i)) if own[w] else None
+            parents.append(par)
+            if par is None:
+                continue
+            for v in g[par].tolist():
+                if v not in seen:
+                    seen.add(v)
+                    own[w].append(v)
+        for w in range(workers):
+            want = sorted(own[w], key=lambda i: (d64[i], i))
+            got = [int(v) for v in lists[b, w] if v != oracle.INVALID_ID]
+            assert got == want, (b, w)
+        assert st[b, 2] == len(seen) and st[b, 1] == sum(p is not None for p in parents)
+        assert n_seeds <= workers * d
+        merged = sorted(seen, key=lambda i: (d64[i], i))[:k]
+        assert ids[b].tolist() == merged
+        assert st[b, 3] == 1                                   # stopped by the pass limit
+
+
+def test_multi_worker_result_is_the_merge_of_disjoint_lists():
+    # Ordinary list lengths (nodes do get dropped): the lists stay disjoint, each is sorted, and the result
+    # is the first k of their union, recomputed here from float64 distances.
+    base, qs = _int_data(3000, 24, 40, 33)
+    g = oracle.build(base, 16, 32)
+    k, local, workers = 10, 32, 6
+    ids, dists, lists = oracle.search_multi(g, base, qs, k, local, workers, seed=4, max_iterations=80,
+                                            return_lists=True)
+    beyond_first = 0
+    for b in range(qs.shape[0]):
+        d64 = _exact_keys(base, qs[b])
+        held = []
+        for w in range(workers):
+            row = [int(v) for v in lists[b, w] if v != oracle.INVALID_ID]
+            assert row == sorted(row, key=lambda i: (d64[i], i))
+            held += row
+        assert len(held) == len(set(held))
+        merged = sorted(held, key=lambda i: (d64[i], i))[:k]
+        assert ids[b].tolist() == merged
+        assert dists[b].astype(np.float64).tolist() == [d64[i] for i in merged]
+        beyond_first += len(set(merged) - set(int(v) for v in lists[b, 0]))
+    assert beyond_first > 0                                    # the answers do not come from worker 0 alone
