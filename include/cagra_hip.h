@@ -113,6 +113,9 @@ typedef struct {
  * search_width * degree <= 2048 (beyond 256 candidates a pass takes them in chunks of 256, the
  * large-candidate-list case of Sec. IV-B.2); multi mode: see cagra_search_opts.
  * B == 0 is allowed and does nothing.
+ * The workspace belongs to one call at a time: it holds the query counter (single mode) or the
+ * visited tables, published lists and tickets (multi mode), so another call may use the same
+ * workspace only after this call's work on its stream has finished (or behind it on the same stream).
  */
 int cagra_search(const uint32_t *graph, int64_t N, int32_t degree,
                  const void *dataset /* rows of opts->dataset_type, fp32 if opts is NULL */,
@@ -126,6 +129,27 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree,
 size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_t k,
                                     int32_t itopk, int32_t search_width,
                                     const cagra_search_opts *opts /* host, may be NULL */);
+
+/*
+ * cagra_search for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as cagra_search without `workspace`; the scratch memory (the query counter of the
+ * single mode; visited tables, published lists and tickets of the multi mode) is a static device
+ * array of CAGRA_STATIC_SCRATCH_BYTES inside the library, one per GPU, held until the process ends.
+ * The call allocates and frees nothing and clears what it needs with kernels on `hip_stream`.
+ * A search whose cagra_search_workspace_bytes() exceeds CAGRA_STATIC_SCRATCH_BYTES is refused with
+ * CAGRA_ERR_WORKSPACE (single mode needs 256 bytes at any batch size; multi mode about
+ * B * (16 * workers * degree * (max_iterations + 1) rounded up to a power of two + 512 * workers *
+ * ceil(itopk_local / 64)) bytes).  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams or threads) race; issue them on one stream, or one after the other.
+ */
+#define CAGRA_STATIC_SCRATCH_BYTES (64u << 20)
+int cagra_search_static(const uint32_t *graph, int64_t N, int32_t degree,
+                        const void *dataset, int32_t dim, int64_t ld, cagra_metric metric,
+                        const float *queries, int64_t B, int64_t ld_queries,
+                        int32_t k, int32_t itopk, int32_t search_width,
+                        const cagra_search_opts *opts /* host, may be NULL */,
+                        uint32_t *ids_out, float *dists_out, void *hip_stream);
 
 /* What a search with these arguments would run with (host function, nothing is launched):
  * the resolved mode and every automatic parameter.  Same argument checks as cagra_search. */

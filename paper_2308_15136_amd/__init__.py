@@ -79,6 +79,9 @@ def load_library():
     lib.cagra_search.restype = C.c_int
     lib.cagra_search.argtypes = [vp, i64, i32, vp, i32, i64, C.c_int, vp, i64, i64, i32, i32, i32,
                                  opts_p, vp, vp, vp, sz, vp]
+    lib.cagra_search_static.restype = C.c_int
+    lib.cagra_search_static.argtypes = [vp, i64, i32, vp, i32, i64, C.c_int, vp, i64, i64, i32, i32, i32,
+                                        opts_p, vp, vp, vp]
     lib.cagra_search_describe.restype = C.c_int
     lib.cagra_search_describe.argtypes = [i32, i32, i64, i32, i32, i32, opts_p, C.POINTER(_SearchPlan)]
     lib.cagra_search_workspace_bytes.restype = sz
@@ -266,6 +269,33 @@ def search_workspace_bytes(n: int, degree: int, batch: int, k: int, itopk: int, 
                                                            C.byref(copts)))
 
 
+def _search_tensors(graph, dataset, queries, k: int, out, stats):
+    """Checks what the library cannot see behind raw pointers: shapes that belong together, one device,
+    output buffers of the right type and size."""
+    torch = _torch()
+    graph = _dev_i32(graph, "graph")
+    dataset, dtype = _dev_dataset(dataset)
+    queries = _dev_f32(queries, "queries")
+    if graph.dim() != 2 or graph.shape[0] != dataset.shape[0]:
+        raise ValueError(f"graph has {tuple(graph.shape)} entries, dataset {dataset.shape[0]} rows: one graph row per dataset row")
+    if queries.shape[1] != dataset.shape[1]:
+        raise ValueError(f"queries have {queries.shape[1]} dimensions, dataset rows {dataset.shape[1]}")
+    dev = dataset.device
+    if graph.device != dev or queries.device != dev:
+        raise ValueError("graph, dataset and queries must be on the same device")
+    B = queries.shape[0]
+    if stats is not None and not (isinstance(stats, torch.Tensor) and stats.device == dev and stats.dtype == torch.int32
+                                  and stats.is_contiguous() and stats.numel() >= 4 * B):
+        raise TypeError("stats must be a contiguous int32 tensor of at least B * 4 elements on the dataset's device")
+    if out is not None:
+        ids, dists = out
+        for t, dt, name in ((ids, torch.int32, "ids"), (dists, torch.float32, "dists")):
+            if not (isinstance(t, torch.Tensor) and t.device == dev and t.dtype == dt and t.is_contiguous()
+                    and tuple(t.shape) == (B, k)):
+                raise TypeError(f"out {name} must be a contiguous {dt} tensor of shape ({B}, {k}) on the dataset's device")
+    return graph, dataset, dtype, queries
+
+
 def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,
            options: Optional[SearchOptions] = None, return_stats: bool = False,
            out: Optional[Tuple] = None, workspace=None, stats=None):
@@ -273,16 +303,12 @@ def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, m
     `out`, `workspace` and `stats` (int32 [B, 4], implies return_stats) may be preallocated."""
     torch = _torch()
     lib = load_library()
-    graph = _dev_i32(graph, "graph")
-    dataset, dtype = _dev_dataset(dataset)
-    queries = _dev_f32(queries, "queries")
+    graph, dataset, dtype, queries = _search_tensors(graph, dataset, queries, k, out, stats)
     dev = dataset.device
     B = queries.shape[0]
     o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype)
     if stats is not None:
         return_stats = True
-        if not (stats.is_cuda and stats.dtype == torch.int32 and stats.is_contiguous() and stats.numel() >= 4 * B):
-            raise TypeError("stats must be a contiguous int32 device tensor of at least B * 4 elements")
     elif return_stats:
         stats = torch.zeros((B, 4), dtype=torch.int32, device=dev)
     copts = _copts(o, stats.data_ptr() if stats is not None else None)
@@ -295,12 +321,37 @@ def search(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, m
     if workspace is None:
         workspace = _workspace(lib.cagra_search_workspace_bytes(N, degree, B, k, itopk, search_width,
                                                                 C.byref(copts)), dev)
+    elif not (isinstance(workspace, torch.Tensor) and workspace.device == dev and workspace.dtype == torch.uint8
+              and workspace.is_contiguous()):
+        raise TypeError("workspace must be a contiguous uint8 tensor on the dataset's device")
     rc = lib.cagra_search(graph.data_ptr(), N, degree, dataset.data_ptr(), dataset.shape[1],
                           dataset.stride(0), metric, queries.data_ptr(), B, queries.stride(0),
                           k, itopk, search_width, C.byref(copts), ids.data_ptr(), dists.data_ptr(),
                           workspace.data_ptr(), workspace.numel(), _stream(dev))
     _check(rc, "cagra_search")
     return (ids, dists, stats) if return_stats else (ids, dists)
+
+
+def search_static(graph, dataset, queries, k: int, itopk: int, search_width: int = 1, metric: int = L2,
+                  options: Optional[SearchOptions] = None, out: Optional[Tuple] = None, stats=None):
+    """cagra_search_static: the same search with the library's own static scratch array instead of a
+    workspace (nothing is allocated inside the call; give `out` to keep this wrapper from allocating)."""
+    torch = _torch()
+    lib = load_library()
+    graph, dataset, dtype, queries = _search_tensors(graph, dataset, queries, k, out, stats)
+    dev = dataset.device
+    B = queries.shape[0]
+    o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype)
+    copts = _copts(o, stats.data_ptr() if stats is not None else None)
+    if out is None:
+        out = (torch.empty((B, k), dtype=torch.int32, device=dev), torch.empty((B, k), dtype=torch.float32, device=dev))
+    ids, dists = out
+    N, degree = graph.shape
+    rc = lib.cagra_search_static(graph.data_ptr(), N, degree, dataset.data_ptr(), dataset.shape[1],
+                                 dataset.stride(0), metric, queries.data_ptr(), B, queries.stride(0),
+                                 k, itopk, search_width, C.byref(copts), ids.data_ptr(), dists.data_ptr(), _stream(dev))
+    _check(rc, "cagra_search_static")
+    return (ids, dists, stats) if stats is not None else (ids, dists)
 
 
 class PreparedSearch:
@@ -315,9 +366,7 @@ class PreparedSearch:
                  options: Optional[SearchOptions] = None):
         torch = _torch()
         self._lib = load_library()
-        graph = _dev_i32(graph, "graph")
-        dataset, dtype = _dev_dataset(dataset)
-        queries = _dev_f32(queries, "queries")
+        graph, dataset, dtype, queries = _search_tensors(graph, dataset, queries, k, None, None)
         dev = dataset.device
         B = queries.shape[0]
         o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype)

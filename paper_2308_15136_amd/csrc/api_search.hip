@@ -217,9 +217,116 @@ static int resolve_mode(const cagra_search_opts &o, int64_t B, int itopk)
     return (B < device_info().cus || itopk > 512) ? 2 : 1;
 }
 
+// ---- scratch for callers that cannot allocate (cagra_search_static) ----------------------------
+// One array per GPU, held until the process ends.  In host code the array's name only stands for the
+// symbol; its device address is asked once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[CAGRA_STATIC_SCRATCH_BYTES];
+
+static void *static_scratch()
+{
+    static void *ptr[64] = {};
+    static std::once_flag once[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::call_once(once[dev], [dev]() {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) == hipSuccess) ptr[dev] = p;
+    });
+    return ptr[dev];
+}
+
 }  // namespace cagra
 
 using namespace cagra;
+
+// Validation, plan and launch of one search.  workspace == kStaticScratch: the scratch memory is this
+// device's static array (cagra_search_static), looked up only after every argument check has passed.
+static void *const kStaticScratch = reinterpret_cast<void *>(~(uintptr_t)0);
+
+static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const void *dataset, int32_t dim,
+                       int64_t ld, cagra_metric metric, const float *queries, int64_t B, int64_t ld_queries,
+                       int32_t k, int32_t itopk, int32_t search_width, const cagra_search_opts &o,
+                       uint32_t *ids_out, float *dists_out, void *workspace, size_t workspace_bytes,
+                       void *hip_stream)
+{
+    if (!graph || !dataset) return CAGRA_ERR_NULL_POINTER;
+    if (B > 0 && (!queries || !ids_out || !dists_out)) return CAGRA_ERR_NULL_POINTER;
+    const int epp = elems_per_piece(o.dataset_type);
+    if (epp == 0) return CAGRA_ERR_BAD_OPTION;
+    if (N < 1 || N > 0x7FFFFFFFll || dim < 4 || (dim % epp) || ld < dim || (ld % epp) || B < 0 ||
+        B > 0x7FFFFFFFll || ld_queries < dim)
+        return CAGRA_ERR_BAD_SHAPE;
+    if (((uintptr_t)dataset & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
+    if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
+    if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
+    if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
+    if (o.mode < 0 || o.mode > 2) return CAGRA_ERR_BAD_OPTION;
+    if (B == 0) return CAGRA_OK;
+    const int mode = resolve_mode(o, B, itopk);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    SearchParams P = {};
+    P.graph = graph; P.dataset = dataset; P.queries = queries;
+    P.ids_out = ids_out; P.dists_out = dists_out; P.stats = o.stats;
+    P.N = N; P.B = B; P.ld = ld; P.ld_queries = ld_queries; P.seed = o.seed;
+    P.degree = degree; P.dim = dim; P.metric = (int)metric; P.k = k;
+
+    if (mode == 2) {
+        MultiPlan pl;
+        int rc = plan_multi(degree, dim, B, k, itopk, search_width, o, pl);
+        if (rc != CAGRA_OK) return rc;
+        if (workspace == kStaticScratch) {
+            if (pl.table_bytes + pl.list_bytes + pl.done_bytes > (size_t)CAGRA_STATIC_SCRATCH_BYTES) return CAGRA_ERR_WORKSPACE;
+            if (!(workspace = static_scratch())) return CAGRA_ERR_LAUNCH;
+            workspace_bytes = CAGRA_STATIC_SCRATCH_BYTES;
+        }
+        if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+            workspace_bytes < pl.table_bytes + pl.list_bytes + pl.done_bytes)
+            return CAGRA_ERR_WORKSPACE;
+        unsigned char *w = static_cast<unsigned char *>(workspace);
+        P.tables = reinterpret_cast<uint32_t *>(w);
+        P.lists = reinterpret_cast<uint64_t *>(w + pl.table_bytes);
+        P.done = reinterpret_cast<uint32_t *>(w + pl.table_bytes + pl.list_bytes);
+        P.itopk = pl.itopk_local; P.search_width = 1; P.workers = pl.workers;
+        P.max_iterations = pl.max_iterations; P.reset_interval = 0;
+        P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
+        P.off_query = pl.off_query; P.off_newid = pl.off_newid;
+        P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
+        hipError_t e = o.dataset_type == CAGRA_F32   ? launch_search_multi_f32(P, pl.mr, pl.cr, pl.smem, stream)
+                       : o.dataset_type == CAGRA_F16 ? launch_search_multi_f16(P, pl.mr, pl.cr, pl.smem, stream)
+                                                     : launch_search_multi_u8(P, pl.mr, pl.cr, pl.smem, stream);
+        return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+    }
+
+    SinglePlan pl;
+    int rc = plan_single(degree, dim, itopk, search_width, o, pl);
+    if (rc != CAGRA_OK) return rc;
+    if (workspace == kStaticScratch) {
+        if (!(workspace = static_scratch())) return CAGRA_ERR_LAUNCH;
+        workspace_bytes = CAGRA_STATIC_SCRATCH_BYTES;
+    }
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < 256) return CAGRA_ERR_WORKSPACE;
+    P.counter = static_cast<uint32_t *>(workspace);
+    P.itopk = itopk; P.search_width = search_width; P.workers = 1;
+    P.max_iterations = pl.max_iterations; P.reset_interval = pl.reset_interval;
+    P.table_words = pl.table_words; P.team_log2 = pl.team_log2;
+    P.off_query = pl.off_query; P.off_newid = pl.off_newid;
+    P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
+
+    const DeviceInfo &di = device_info();
+    // persistent grid: as many single-wavefront workgroups as fit (LDS-bound, at most 16 per CU)
+    int grid = (int)std::min<int64_t>(B, (int64_t)single_per_cu(o, pl, di) * di.cus);
+    hipError_t e;
+    if (pl.wide)
+        e = o.dataset_type == CAGRA_F32   ? launch_search_wide_f32(P, pl.mr, grid, pl.smem, stream)
+            : o.dataset_type == CAGRA_F16 ? launch_search_wide_f16(P, pl.mr, grid, pl.smem, stream)
+                                          : launch_search_wide_u8(P, pl.mr, grid, pl.smem, stream);
+    else
+        e = o.dataset_type == CAGRA_F32   ? launch_search_single_f32(P, pl.mr, pl.cr, grid, pl.smem, stream)
+            : o.dataset_type == CAGRA_F16 ? launch_search_single_f16(P, pl.mr, pl.cr, grid, pl.smem, stream)
+                                          : launch_search_single_u8(P, pl.mr, pl.cr, grid, pl.smem, stream);
+    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+}
 
 extern "C" {
 
@@ -308,74 +415,20 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const void *d
 {
     cagra_search_opts o = {};
     if (opts) o = *opts;
-    if (!graph || !dataset) return CAGRA_ERR_NULL_POINTER;
-    if (B > 0 && (!queries || !ids_out || !dists_out)) return CAGRA_ERR_NULL_POINTER;
-    const int epp = elems_per_piece(o.dataset_type);
-    if (epp == 0) return CAGRA_ERR_BAD_OPTION;
-    if (N < 1 || N > 0x7FFFFFFFll || dim < 4 || (dim % epp) || ld < dim || (ld % epp) || B < 0 ||
-        B > 0x7FFFFFFFll || ld_queries < dim)
-        return CAGRA_ERR_BAD_SHAPE;
-    if (((uintptr_t)dataset & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
-    if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
-    if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
-    if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
-    if (o.mode < 0 || o.mode > 2) return CAGRA_ERR_BAD_OPTION;
-    if (B == 0) return CAGRA_OK;
-    const int mode = resolve_mode(o, B, itopk);
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (workspace == kStaticScratch) return CAGRA_ERR_WORKSPACE;
+    return search_impl(graph, N, degree, dataset, dim, ld, metric, queries, B, ld_queries, k, itopk, search_width,
+                       o, ids_out, dists_out, workspace, workspace_bytes, hip_stream);
+}
 
-    SearchParams P = {};
-    P.graph = graph; P.dataset = dataset; P.queries = queries;
-    P.ids_out = ids_out; P.dists_out = dists_out; P.stats = o.stats;
-    P.N = N; P.B = B; P.ld = ld; P.ld_queries = ld_queries; P.seed = o.seed;
-    P.degree = degree; P.dim = dim; P.metric = (int)metric; P.k = k;
-
-    if (mode == 2) {
-        MultiPlan pl;
-        int rc = plan_multi(degree, dim, B, k, itopk, search_width, o, pl);
-        if (rc != CAGRA_OK) return rc;
-        if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
-            workspace_bytes < pl.table_bytes + pl.list_bytes + pl.done_bytes)
-            return CAGRA_ERR_WORKSPACE;
-        unsigned char *w = static_cast<unsigned char *>(workspace);
-        P.tables = reinterpret_cast<uint32_t *>(w);
-        P.lists = reinterpret_cast<uint64_t *>(w + pl.table_bytes);
-        P.done = reinterpret_cast<uint32_t *>(w + pl.table_bytes + pl.list_bytes);
-        P.itopk = pl.itopk_local; P.search_width = 1; P.workers = pl.workers;
-        P.max_iterations = pl.max_iterations; P.reset_interval = 0;
-        P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
-        P.off_query = pl.off_query; P.off_newid = pl.off_newid;
-        P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
-        hipError_t e = o.dataset_type == CAGRA_F32   ? launch_search_multi_f32(P, pl.mr, pl.cr, pl.smem, stream)
-                       : o.dataset_type == CAGRA_F16 ? launch_search_multi_f16(P, pl.mr, pl.cr, pl.smem, stream)
-                                                     : launch_search_multi_u8(P, pl.mr, pl.cr, pl.smem, stream);
-        return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
-    }
-
-    SinglePlan pl;
-    int rc = plan_single(degree, dim, itopk, search_width, o, pl);
-    if (rc != CAGRA_OK) return rc;
-    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < 256) return CAGRA_ERR_WORKSPACE;
-    P.counter = static_cast<uint32_t *>(workspace);
-    P.itopk = itopk; P.search_width = search_width; P.workers = 1;
-    P.max_iterations = pl.max_iterations; P.reset_interval = pl.reset_interval;
-    P.table_words = pl.table_words; P.team_log2 = pl.team_log2;
-    P.off_query = pl.off_query; P.off_newid = pl.off_newid;
-    P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
-
-    const DeviceInfo &di = device_info();
-    // persistent grid: as many single-wavefront workgroups as fit (LDS-bound, at most 16 per CU)
-    int grid = (int)std::min<int64_t>(B, (int64_t)single_per_cu(o, pl, di) * di.cus);
-    hipError_t e;
-    if (pl.wide)
-        e = o.dataset_type == CAGRA_F32   ? launch_search_wide_f32(P, pl.mr, grid, pl.smem, stream)
-            : o.dataset_type == CAGRA_F16 ? launch_search_wide_f16(P, pl.mr, grid, pl.smem, stream)
-                                          : launch_search_wide_u8(P, pl.mr, grid, pl.smem, stream);
-    else
-        e = o.dataset_type == CAGRA_F32   ? launch_search_single_f32(P, pl.mr, pl.cr, grid, pl.smem, stream)
-            : o.dataset_type == CAGRA_F16 ? launch_search_single_f16(P, pl.mr, pl.cr, grid, pl.smem, stream)
-                                          : launch_search_single_u8(P, pl.mr, pl.cr, grid, pl.smem, stream);
-    return e == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+int cagra_search_static(const uint32_t *graph, int64_t N, int32_t degree, const void *dataset, int32_t dim,
+                        int64_t ld, cagra_metric metric, const float *queries, int64_t B, int64_t ld_queries,
+                        int32_t k, int32_t itopk, int32_t search_width, const cagra_search_opts *opts,
+                        uint32_t *ids_out, float *dists_out, void *hip_stream)
+{
+    cagra_search_opts o = {};
+    if (opts) o = *opts;
+    return search_impl(graph, N, degree, dataset, dim, ld, metric, queries, B, ld_queries, k, itopk, search_width,
+                       o, ids_out, dists_out, kStaticScratch, 0, hip_stream);
 }
 
 int cagra_convert_dataset(const float *src, int64_t N, int32_t dim, int64_t ld_src, cagra_dtype dst_type,

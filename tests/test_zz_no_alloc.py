@@ -1,0 +1,77 @@
+"""cagra_search_static -- the search for callers that cannot allocate (no workspace argument, the
+scratch memory is a static device array inside the library) -- against cagra_search, through the C ABI:
+two calls in a row, the second with a smaller input; single mode and multi mode."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2308_15136_amd import datagen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def setup():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2308_15136_amd as m
+    m.load_library()
+    w = datagen.workload("sift1m", n=20_000, n_queries=600)
+    g = oracle.build(w.base, 32, 64, w.metric)
+    return m, w, (torch.from_numpy(g.view(np.int32)).cuda(), torch.from_numpy(w.base).cuda(),
+                  torch.from_numpy(w.queries).cuda())
+
+
+def test_static_scratch_single_mode_two_calls(setup):
+    import torch
+    m, w, (gd, bd, qd) = setup
+    # integer data: the search is deterministic and exact, so the two entry points must agree bit for bit
+    for nq, k, itopk, width in ((600, 10, 64, 4), (150, 5, 32, 1)):
+        print(f"case static single B={nq} k={k} itopk={itopk} width={width}", flush=True)
+        opts = m.SearchOptions(seed=13, mode=1)
+        ids = torch.full((nq, k), -7, dtype=torch.int32, device="cuda")
+        dists = torch.full((nq, k), -1.0, dtype=torch.float32, device="cuda")
+        stats = torch.zeros((nq, 4), dtype=torch.int32, device="cuda")
+        m.search_static(gd, bd, qd[:nq], k, itopk, width, w.metric, opts, out=(ids, dists), stats=stats)
+        r_ids, r_d, r_st = m.search(gd, bd, qd[:nq], k, itopk, width, w.metric, opts, return_stats=True)
+        torch.cuda.synchronize()
+        assert torch.equal(ids, r_ids) and torch.equal(dists, r_d) and torch.equal(stats, r_st)
+
+
+def test_static_scratch_multi_mode_two_calls(setup):
+    import torch
+    m, w, (gd, bd, qd) = setup
+    # one worker per query: deterministic, bit for bit.  The second call is smaller and must not see
+    # what the first left in the shared array (tables, tickets).
+    for nq, k, itopk in ((40, 10, 64), (8, 10, 32)):
+        print(f"case static multi W=1 B={nq} itopk={itopk}", flush=True)
+        opts = m.SearchOptions(seed=17, mode=2, wg_per_query=1)
+        ids, dists = m.search_static(gd, bd, qd[:nq], k, itopk, 1, w.metric, opts)
+        r_ids, r_d = m.search(gd, bd, qd[:nq], k, itopk, 1, w.metric, opts)
+        torch.cuda.synchronize()
+        assert torch.equal(ids, r_ids) and torch.equal(dists, r_d)
+    # several workers interleave freely, so the entry points are compared where the answer is unique:
+    # local lists longer than the dataset on a strongly connected graph give the brute-force result
+    n, nq, degree, k = 400, 24, 8, 10
+    ws = datagen.workload("sift1m", n=n, n_queries=nq)
+    g = oracle.build(ws.base, degree, 2 * degree, ws.metric)
+    assert oracle.strong_components(g) == 1
+    g_d, b_d, q_d = (torch.from_numpy(g.view(np.int32)).cuda(), torch.from_numpy(ws.base).cuda(),
+                     torch.from_numpy(ws.queries).cuda())
+    for take, workers in ((nq, 4), (5, 2)):
+        print(f"case static multi exhaustive lists W={workers} B={take}", flush=True)
+        opts = m.SearchOptions(seed=21, mode=2, wg_per_query=workers, max_iterations=600)
+        ids, dists = m.search_static(g_d, b_d, q_d[:take], k, 512 * workers, 1, ws.metric, opts)
+        r_ids, r_d = m.search(g_d, b_d, q_d[:take], k, 512 * workers, 1, ws.metric, opts)
+        torch.cuda.synchronize()
+        assert torch.equal(ids, r_ids) and torch.equal(dists, r_d)
+
+
+def test_static_scratch_refuses_what_does_not_fit(setup):
+    m, w, (gd, bd, qd) = setup
+    # 600 queries x 32 workers with the automatic pass limit: the tables alone are far beyond the array
+    opts = m.SearchOptions(seed=1, mode=2, wg_per_query=32)
+    assert m.search_workspace_bytes(20_000, 32, 600, 10, 1024, 1, opts) > 64 << 20
+    with pytest.raises(m.CagraError, match="workspace"):
+        m.search_static(gd, bd, qd, 10, 1024, 1, w.metric, opts)
