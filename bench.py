@@ -53,19 +53,39 @@ def algorithmic_bytes(stats: np.ndarray, dim: int, degree: int, k: int) -> dict:
             "iterations_mean": float(stats[:, 0].mean()), "hit_cap": int((stats[:, 3] & 1).sum())}
 
 
+def kernel_sources_sha16() -> str:
+    """Hash of everything the search kernels are compiled from; a counter summary under profiles/
+    names the hash of the sources it was measured with."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2308_15136_amd", "csrc")
+    for path in sorted(glob.glob(os.path.join(csrc, "search_*")) + glob.glob(os.path.join(csrc, "*.h"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(workload: str, width: int, itopk: int):
     """HBM bytes per launch of the search kernel from the committed rocprofv3 counter summary
-    (FETCH_SIZE and WRITE_SIZE runs of this same script), if it covers this configuration."""
+    (FETCH_SIZE and WRITE_SIZE runs of this same script), if it covers this configuration AND was
+    measured with the kernel sources as they are now.  Returns (bytes or None, where it came from)."""
     import re
-    path = os.path.join(ROOT, "profiles", f"search_single_{workload}_pmc.md")
+    rel = os.path.join("profiles", f"search_single_{workload}_pmc.md")
     try:
-        text = open(path).read()
+        text = open(os.path.join(ROOT, rel)).read()
     except OSError:
-        return None
+        return None, None
+    m = re.search(r"kernel_sources_sha16:\s*([0-9a-f]{16})", text)
+    src = {"file": rel, "kernel_sources_sha16_of_profile": m.group(1) if m else None,
+           "kernel_sources_sha16_now": kernel_sources_sha16()}
+    src["stale"] = src["kernel_sources_sha16_of_profile"] != src["kernel_sources_sha16_now"]
+    if src["stale"]:
+        return None, src          # the kernels changed since the counters were read: no figure rather than an old one
     for m in re.finditer(r"traffic_bytes_per_launch:\s*(\d+)\s*\(search_width (\d+), itopk (\d+)", text):
         if int(m.group(2)) == width and int(m.group(3)) == itopk:
-            return float(m.group(1))
-    return None
+            return float(m.group(1)), src
+    return None, src
 
 
 def main() -> int:
@@ -76,6 +96,8 @@ def main() -> int:
     ap.add_argument("--workload", default="sift1m")
     ap.add_argument("--n", type=int, default=0, help="shrink the base set (debugging only)")
     ap.add_argument("--queries", type=int, default=0)
+    ap.add_argument("--k", type=int, default=0, help="neighbours per query (default: the workload's)")
+    ap.add_argument("--print-kernel-hash", action="store_true", help="print the hash of the kernel sources and exit")
     ap.add_argument("--itopk", type=int, default=0, help="skip the itopk sweep and time this itopk")
     ap.add_argument("--width", type=int, default=0, help="skip the search_width sweep and use this width")
     ap.add_argument("--full-sweep", action="store_true",
@@ -105,6 +127,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for rocprofv3 counters)")
     args = ap.parse_args()
+    if args.print_kernel_hash:
+        print(kernel_sources_sha16())
+        return 0
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; queries are independent, so more GPUs would "
             "each take a slice of the batch, but no multi-GPU path is part of it.")
@@ -122,6 +147,9 @@ def main() -> int:
 
     t0 = time.time()
     w = datagen.workload(args.workload, n=args.n or None, n_queries=args.queries or None)
+    if args.k:
+        import dataclasses
+        w = dataclasses.replace(w, k=args.k, itopk=tuple(m for m in w.itopk if m >= args.k) or (args.k,))
     N, dim = w.base.shape
     B = w.queries.shape[0]
     log(f"[bench] workload {w.name}: base {N}x{dim}, {B} queries, degree {w.degree}, "
@@ -253,6 +281,13 @@ def main() -> int:
     rec = recall_at_k(gpu_ids, gt_np)
     value = B / (wall_ms * 1e-3)
     achieved = ab["total_bytes"] / (dev_ms * 1e-3) / 1e9
+    if args.traffic_bytes is not None:
+        traffic, traffic_source = args.traffic_bytes, {"file": None, "note": "given on the command line"}
+    else:
+        traffic, traffic_source = measured_traffic(w.name, P_WIDTH, M)
+    # the one-parent-per-pass search (search_width 1, the paper's basic form) at its own crossing of the target
+    p1 = [pt for pt in sweep if pt["search_width"] == 1 and pt["recall"] >= TARGET_RECALL]
+    p1_reference = min(p1, key=lambda pt: pt["itopk"]) if p1 else None
 
     out = {
         "metric": "QPS at recall@10>=0.95 (1Mx128, batch 10k)" if (w.name == "sift1m" and N == 1_000_000 and B == 10_000)
@@ -267,11 +302,15 @@ def main() -> int:
                    "qps_interpolated_at_target": None if qps_at_target is None else round(qps_at_target, 1),
                    "graph_build_s": round(build_s, 2), "reorder": args.reorder, "initial_graph": args.initial_graph,
                    "exact_algo": args.exact_algo,
+                   "p1_reference": p1_reference,
                    "graph_quality": graph_quality},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": args.traffic_bytes if args.traffic_bytes is not None
-                     else measured_traffic(w.name, P_WIDTH, M),
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "what": "algorithmic bytes (rows of first-time candidates, graph rows of parents, queries, results; "
+                             "counted in the kernel) over the kernel's time, against the published HBM peak; the "
+                             f"{N * dim * 4 / 1e6:.0f} MB dataset partly fits the 256 MB Infinity Cache, whose hits the "
+                             "HBM counters do not see, so on datasets of this size the figure is a gather rate, not pure HBM",
                      "kernel": "search_single_wide_kernel" if P_WIDTH * w.degree > 256 else "search_single_kernel",
                      "kernel_ms": round(dev_ms, 4),
                      "algorithmic_bytes_per_launch": ab["total_bytes"],
@@ -417,7 +456,7 @@ def main() -> int:
             return e0.elapsed_time(e1) / reps
         n_read = ab["n_dist"]
         ms_stream = time_probe(10, pattern=0)
-        ref = {"stream_read_GBs": round(N * dim * 4 / (ms_stream * 1e-3) / 1e9, 1), "row_bytes": dim * 4,
+        ref = {"dataset_stream_read_GBs": round(N * dim * 4 / (ms_stream * 1e-3) / 1e9, 1), "row_bytes": dim * 4,
                "rows_gathered": n_read, "row_gather": []}
         best = 0.0
         for rif in (4, 8):
@@ -428,9 +467,44 @@ def main() -> int:
                 ref["row_gather"].append({"rows_in_flight": rif, "waves_per_cu": wpc, "GBs": round(gbs, 1)})
         ref["best_row_gather_GBs"] = round(best, 1)
         ref["search_vs_best_row_gather"] = round(out["roofline"]["gathered_vector_GBs"] / best, 4)
+        # The same two patterns over a buffer far beyond the 256 MB Infinity Cache (8 GiB, several ms per launch):
+        # what the HBM alone delivers.  The stream figure is the achievable peak for reads; the gather figure is the
+        # ceiling for a search over a dataset that no cache holds.
+        row_b = dim * 4
+        big_rows = (8 << 30) // row_b
+        big = torch.empty((big_rows, row_b), dtype=torch.uint8, device=dev)
+        big.view(-1)[: big_rows * row_b].view(torch.int32).fill_(0x3F800000)
+
+        def time_big(reps, **kw):
+            cagra.probe_bandwidth(big, sink=sink, **kw)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for r in range(reps):
+                cagra.probe_bandwidth(big, sink=sink, seed=100 + r, **kw)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        big_stream = []
+        for wpc in (8, 16, 32):
+            ms_b = time_big(5, pattern=0, waves_per_cu=wpc)
+            big_stream.append({"waves_per_cu": wpc, "ms": round(ms_b, 3), "GBs": round(big_rows * row_b / (ms_b * 1e-3) / 1e9, 1)})
+        n_big = max(n_read, 40_000_000)
+        big_gather = []
+        for rif, wpc in ((4, 16), (8, 8), (8, 16)):
+            ms_b = time_big(3, pattern=1, n_read=n_big, rows_in_flight=rif, waves_per_cu=wpc)
+            big_gather.append({"rows_in_flight": rif, "waves_per_cu": wpc, "ms": round(ms_b, 3),
+                               "GBs": round(n_big * row_b / (ms_b * 1e-3) / 1e9, 1)})
+        del big
+        ref["hbm_only"] = {"buffer_bytes": big_rows * row_b, "stream_read": big_stream,
+                           "stream_read_GBs": max(x["GBs"] for x in big_stream),
+                           "row_gather": big_gather, "row_gather_GBs": max(x["GBs"] for x in big_gather),
+                           "rows_gathered": n_big}
+        ref["search_vs_hbm_stream_read"] = round(out["roofline"]["achieved"] / ref["hbm_only"]["stream_read_GBs"], 4)
         out["hbm_reference"] = ref
-        log(f"[bench] reference: stream read {ref['stream_read_GBs']} GB/s, random {dim * 4}-byte rows "
-            f"{ref['best_row_gather_GBs']} GB/s")
+        log(f"[bench] reference: dataset stream read {ref['dataset_stream_read_GBs']} GB/s, random {dim * 4}-byte rows of the "
+            f"dataset {ref['best_row_gather_GBs']} GB/s; 8 GiB buffer: stream {ref['hbm_only']['stream_read_GBs']} GB/s, "
+            f"random rows {ref['hbm_only']['row_gather_GBs']} GB/s")
 
     # ---- the choices the library makes by itself, each against its alternatives (the paper's own
     #      studies of team size, Sec. V-B, of the visited-table management, Sec. IV-B.3, and of the two
@@ -602,6 +676,14 @@ def main() -> int:
                                "kind": "oracle", "cpu_model": cpu_model, "host_cpus": os.cpu_count(), "sample": f"first {ns} of the {B} queries, same graph, "
                                f"itopk={M}, search_width={P_WIDTH}, OpenMP over queries, "
                                f"{cpu_s:.2f}s per pass over the sample, {reps} passes"}
+        if ns == B:
+            # the oracle's visited set never forgets: its distance count is what the method has to compute; the
+            # kernel's LDS table forgets and measures some rows twice (counted in n_dist_per_query above)
+            nd_o = int(o_st[:, 2].astype(np.int64).sum())
+            strict = nd_o * dim * 4 + ab["n_parent"] * w.degree * 4 + B * dim * 4 + B * w.k * 8
+            out["roofline"]["n_dist_oracle_per_query"] = round(nd_o / B, 1)
+            out["roofline"]["achieved_strict"] = round(strict / (dev_ms * 1e-3) / 1e9, 1)
+            out["roofline"]["frac_strict"] = round(strict / (dev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         out["parity_at_full_size"] = {"sample": ns, "id_agreement": round(inter / float(ns * w.k), 6),
                                       "positionwise_equal": round(float(same.mean()), 6),
                                       "max_rel_dist_err": rel,

@@ -16,21 +16,24 @@ namespace cagra {
 
 __device__ __forceinline__ uint32_t fold(const uint4 &v) { return v.x ^ v.y ^ v.z ^ v.w; }
 
-// grid-stride read of n16 16-byte pieces, eight loads in flight per lane
+// streaming read of n16 16-byte pieces: every workgroup takes whole tiles of 32 KB (eight loads of 16 bytes
+// per lane, all in flight at once), tiles handed out round-robin over the grid
 __global__ void __launch_bounds__(256)
 probe_stream_kernel(const uint4 *__restrict__ src, size_t n16, uint32_t *sink)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    constexpr size_t kTile = 256 * 8;   // pieces per tile
+    const size_t n_tiles = n16 / kTile;
     uint32_t acc = 0;
-    for (; i + 7 * stride < n16; i += 8 * stride) {
+    for (size_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint4 *p = src + tile * kTile + threadIdx.x;
         uint4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+        for (int u = 0; u < 8; ++u) v[u] = p[u * 256];
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc ^= fold(v[u]);
     }
-    for (; i < n16; i += stride) acc ^= fold(src[i]);
+    for (size_t i = n_tiles * kTile + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+        acc ^= fold(src[i]);
     if (acc == 0x9E3779B9u) *sink = acc;   // keeps the loads alive; practically never taken
 }
 
