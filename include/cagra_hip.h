@@ -93,7 +93,10 @@ typedef struct {
                                  else 1..16 (clipped to what the LDS allows).  More workgroups hide more latency,
                                  fewer make each query finish sooner, which shortens the start and the end of a
                                  batch during which the device is not full. */
-    int32_t reserved;
+    int32_t waves_per_query;  /* single mode: wavefronts of one workgroup that work on one query together (the paper
+                                 maps a query to a CTA of several warps, Sec. IV-C.1): 0 automatic, 1, 2 or 4.  A team
+                                 shares the LDS visited table (replacement policy only) and splits the candidates of
+                                 a pass; the results are those of one wavefront, bit for bit. */
     uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
                                  flags (bit 0: stopped by I_max, bit 1: visited table overflowed) */
 } cagra_search_opts;
@@ -165,6 +168,7 @@ typedef struct {
     int32_t lds_bytes;        /* dynamic LDS per workgroup */
     int32_t workgroups;       /* launch size */
     int32_t table_policy;     /* single mode: 1 periodic reset, 2 replacement; 0 in multi mode */
+    int32_t waves_per_query;  /* wavefronts per workgroup (1 in multi mode) */
 } cagra_search_plan;
 
 int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,

@@ -44,7 +44,7 @@ class _SearchOpts(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("max_iterations", C.c_int32), ("mode", C.c_int32),
                 ("team_size", C.c_int32), ("hash_bits", C.c_int32), ("reset_interval", C.c_int32),
                 ("wg_per_query", C.c_int32), ("table_entries", C.c_int32), ("dataset_type", C.c_int32),
-                ("table_policy", C.c_int32), ("workgroups_per_cu", C.c_int32), ("reserved", C.c_int32),
+                ("table_policy", C.c_int32), ("workgroups_per_cu", C.c_int32), ("waves_per_query", C.c_int32),
                 ("stats", C.c_void_p)]
 
 
@@ -56,7 +56,7 @@ class _BuildOpts(C.Structure):
 class _SearchPlan(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("mode", "team_size", "table_entries", "reset_interval",
                                          "max_iterations", "wg_per_query", "itopk_local", "lds_bytes",
-                                         "workgroups", "table_policy")]
+                                         "workgroups", "table_policy", "waves_per_query")]
 
 
 def load_library():
@@ -245,11 +245,13 @@ class SearchOptions:
     dataset_type: int = 0      # F32 / F16 / U8; search() sets it from the dataset tensor's dtype
     table_policy: int = 0      # 0 automatic, 1 periodic reset (the paper's), 2 replacement in sets of four
     workgroups_per_cu: int = 0  # single mode: persistent workgroups per compute unit, 0 automatic
+    waves_per_query: int = 0   # single mode: wavefronts per query (0 automatic, 1, 2, 4)
 
 
 def _copts(o: "SearchOptions", stats_ptr=None) -> _SearchOpts:
     return _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
-                       o.wg_per_query, o.table_entries, o.dataset_type, o.table_policy, o.workgroups_per_cu, 0, stats_ptr)
+                       o.wg_per_query, o.table_entries, o.dataset_type, o.table_policy, o.workgroups_per_cu,
+                       o.waves_per_query, stats_ptr)
 
 
 def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width: int = 1,

@@ -61,14 +61,16 @@ constexpr int kAutoSetTableEntries = CAGRA_AUTO_SET_TABLE;
 struct SinglePlan {
     int mr, cr, table_words, table_policy, reset_interval, team_log2, max_iterations;
     bool wide;   // more than 256 candidates per pass: taken in chunks of 256
+    int waves;   // wavefronts per query: 1, or a team of 2 or 4 sharing the visited table
     size_t smem;
     int off_query, off_newid, off_newdist, off_parents;
+    int off_team, off_pub, pub_cap;   // wave teams only
 };
 
 constexpr int kMaxCandidates = 2048;   // search_width * degree, single mode
 constexpr int kMaxWidth = 64;          // parents per pass (their ids sit in a 64-entry LDS array)
 
-static int plan_single(int degree, int dim, int itopk, int width, const cagra_search_opts &o, SinglePlan &pl)
+static int plan_single(int degree, int dim, int64_t B, int itopk, int width, const cagra_search_opts &o, SinglePlan &pl)
 {
     const int pieces = dim / elems_per_piece(o.dataset_type);   // 16-byte pieces per dataset row
     if (itopk > 512) return CAGRA_ERR_BAD_TOPK;
@@ -137,12 +139,39 @@ static int plan_single(int degree, int dim, int itopk, int width, const cagra_se
         pl.reset_interval = interval;
     }
 
+    // wavefronts per query (waves_per_query): 0 automatic
+    if (o.waves_per_query != 0 && o.waves_per_query != 1 && o.waves_per_query != 2 && o.waves_per_query != 4)
+        return CAGRA_ERR_BAD_OPTION;
+    if (o.waves_per_query != 0) {
+        pl.waves = o.waves_per_query;
+        if (pl.waves > 1 && (reset || degree < 2)) return CAGRA_ERR_BAD_OPTION;   // teams share a replacement table
+    } else {
+        // Automatic: a batch that cannot fill the device with one wavefront per query gets a team per query, which
+        // makes every query finish sooner (measured on the 1M x 128 and 1M x 96 workloads: 4 wavefronts are 35 % faster
+        // up to two queries per compute unit, 2 wavefronts 15 % up to four); a full device is served best by one
+        // wavefront per query.  Below 128 candidates per pass there is too little to share out.
+        const int64_t cus = device_info().cus;
+        pl.waves = (reset || degree < 2 || n_cand < 128) ? 1 : B <= 2 * cus ? 4 : B <= 4 * cus ? 2 : 1;
+    }
+    pl.off_team = pl.off_pub = pl.pub_cap = 0;
+
     size_t off = (size_t)4 * words;
     if (!reset) off += (size_t)(words / 4 + 15) & ~(size_t)15;   // one cursor byte per set of four
-    pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
-    pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
-    pl.off_newdist = (int)off;    off += (size_t)4 * 64 * pl.cr;
-    pl.off_parents = (int)off;    off += (size_t)4 * 64;
+    if (pl.waves > 1) {
+        // every wavefront of a team stages up to 256 candidates and publishes at most min(256, list) of them
+        pl.off_team = (int)off;       off += 64;
+        pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
+        pl.off_newid = (int)off;      off += (size_t)4 * 256 * pl.waves;
+        pl.off_newdist = (int)off;    off += (size_t)4 * 256 * pl.waves;
+        pl.off_parents = (int)off;    off += (size_t)4 * 64;
+        pl.pub_cap = std::min(256, 64 * pl.mr);
+        pl.off_pub = (int)off;        off += (size_t)8 * 2 * pl.waves * pl.pub_cap;
+    } else {
+        pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
+        pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
+        pl.off_newdist = (int)off;    off += (size_t)4 * 64 * pl.cr;
+        pl.off_parents = (int)off;    off += (size_t)4 * 64;
+    }
     pl.smem = off;
     if (pl.smem > 64 * 1024) return CAGRA_ERR_BAD_SHAPE;  // dim too large for the LDS query copy
     return CAGRA_OK;
@@ -153,7 +182,7 @@ static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // Persistent single-wavefront workgroups per compute unit: what the LDS allows (at most 16), or fewer on request.
 static int single_per_cu(const cagra_search_opts &o, const SinglePlan &pl, const DeviceInfo &di)
 {
-    int per_cu = (int)std::min<size_t>(16, di.lds_per_cu / align256(pl.smem));
+    int per_cu = (int)std::min<size_t>(16 / pl.waves, di.lds_per_cu / align256(pl.smem));
     if (o.workgroups_per_cu > 0) per_cu = std::min(per_cu, (int)o.workgroups_per_cu);
     return std::max(per_cu, 1);
 }
@@ -299,7 +328,7 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
     }
 
     SinglePlan pl;
-    int rc = plan_single(degree, dim, itopk, search_width, o, pl);
+    int rc = plan_single(degree, dim, B, itopk, search_width, o, pl);
     if (rc != CAGRA_OK) return rc;
     if (workspace == kStaticScratch) {
         if (!(workspace = static_scratch())) return CAGRA_ERR_LAUNCH;
@@ -312,12 +341,17 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
     P.table_words = pl.table_words; P.team_log2 = pl.team_log2;
     P.off_query = pl.off_query; P.off_newid = pl.off_newid;
     P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
+    P.off_team = pl.off_team; P.off_pub = pl.off_pub; P.pub_cap = pl.pub_cap;
 
     const DeviceInfo &di = device_info();
-    // persistent grid: as many single-wavefront workgroups as fit (LDS-bound, at most 16 per CU)
+    // persistent grid: as many workgroups as fit (LDS-bound, at most 16 wavefronts per CU)
     int grid = (int)std::min<int64_t>(B, (int64_t)single_per_cu(o, pl, di) * di.cus);
     hipError_t e;
-    if (pl.wide)
+    if (pl.waves > 1)
+        e = o.dataset_type == CAGRA_F32   ? launch_search_team_f32(P, pl.mr, pl.waves, grid, di.cus, pl.smem, stream)
+            : o.dataset_type == CAGRA_F16 ? launch_search_team_f16(P, pl.mr, pl.waves, grid, di.cus, pl.smem, stream)
+                                          : launch_search_team_u8(P, pl.mr, pl.waves, grid, di.cus, pl.smem, stream);
+    else if (pl.wide)
         e = o.dataset_type == CAGRA_F32   ? launch_search_wide_f32(P, pl.mr, grid, pl.smem, stream)
             : o.dataset_type == CAGRA_F16 ? launch_search_wide_f16(P, pl.mr, grid, pl.smem, stream)
                                           : launch_search_wide_u8(P, pl.mr, grid, pl.smem, stream);
@@ -392,15 +426,15 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
         out.team_size = 1 << pl.team_log2; out.table_entries = 1 << pl.hash_bits; out.reset_interval = 0;
         out.table_policy = 0;
         out.max_iterations = pl.max_iterations; out.wg_per_query = pl.workers; out.itopk_local = pl.itopk_local;
-        out.lds_bytes = (int32_t)pl.smem; out.workgroups = (int32_t)(B * pl.workers);
+        out.lds_bytes = (int32_t)pl.smem; out.workgroups = (int32_t)(B * pl.workers); out.waves_per_query = 1;
     } else {
         SinglePlan pl;
-        int rc = plan_single(degree, dim, itopk, search_width, o, pl);
+        int rc = plan_single(degree, dim, B, itopk, search_width, o, pl);
         if (rc != CAGRA_OK) return rc;
         out.team_size = 1 << pl.team_log2; out.table_entries = pl.table_words; out.reset_interval = pl.reset_interval;
         out.table_policy = pl.table_policy;
         out.max_iterations = pl.max_iterations; out.wg_per_query = 1; out.itopk_local = itopk;
-        out.lds_bytes = (int32_t)pl.smem;
+        out.lds_bytes = (int32_t)pl.smem; out.waves_per_query = pl.waves;
         out.workgroups = (int32_t)std::min<int64_t>(B, (int64_t)single_per_cu(o, pl, di) * di.cus);
     }
     *plan = out;

@@ -44,6 +44,16 @@ __host__ __device__ __forceinline__ uint32_t seed_slot_id(uint64_t qhash, uint64
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 
+// Orders the LDS accesses of ONE wavefront: what lanes wrote before this point, other lanes of the same
+// wavefront read after it.  The hardware executes a wavefront's LDS instructions in order, so this only
+// has to keep the compiler from moving accesses across it; no barrier instruction, and wavefronts of the
+// same workgroup may pass it any number of times independently of each other.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 __device__ __forceinline__ uint32_t shfl_xor_u32(uint32_t v, int mask)
 {
     return (uint32_t)__shfl_xor((int)v, mask, kWave);

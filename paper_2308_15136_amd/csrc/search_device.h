@@ -273,11 +273,11 @@ __device__ __forceinline__ void update_topm(uint32_t (&thi)[MR], uint32_t (&tlo)
             if ((m >> lane) & 1ull) { scratch_id[pos] = clo[r]; scratch_key[pos] = __uint_as_float(chi[r]); }
             before += __popcll(m);
         }
-        __syncthreads();
+        wave_sync();
         uint32_t whi1[1], wlo1[1];
         whi1[0] = lane < n_better ? __float_as_uint(scratch_key[lane]) : kDummyHi;
         wlo1[0] = lane < n_better ? scratch_id[lane] : kInvalidId;
-        __syncthreads();
+        wave_sync();
         bitonic_sort<1>(whi1, wlo1, lane);
         merge_into_topm<MR, 1>(thi, tlo, whi1, wlo1, lane);
     } else {
@@ -354,20 +354,28 @@ __device__ __forceinline__ uint32_t sets_insert(uint32_t *table, uint32_t *curso
     return count;
 }
 
-// true if this lane's insertion makes its id a new node
+// true if this lane's insertion makes its id a new node.  SHARED: the table is shared by several wavefronts,
+// whose writes land in no particular order (an older count's id may replace a newer one's): the lane also checks
+// that its own id is still in its way.
+template <bool SHARED = false>
 __device__ __forceinline__ bool sets_confirm(const uint32_t *table, const uint32_t *cursor, uint32_t set, uint32_t count,
                                              uint32_t id, bool &forgot, bool &lost)
 {
     const uint4 f = *reinterpret_cast<const uint4 *>(table + 4 * set);
     const uint32_t now = (cursor[set >> 2] >> (8u * (set & 3u))) & 0xFFu;
-    if (((now - count) & 0xFFu) > 4u) {
-        // four or more insertions into this set came after this lane's: its way was written again
+    const uint32_t way = count & 3u;
+    const uint32_t fw[4] = {f.x, f.y, f.z, f.w};
+    bool gone = ((now - count) & 0xFFu) > 4u;   // four or more insertions into this set came after this lane's
+    if constexpr (SHARED) {
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) gone |= (k == way) & (fw[k] != id);
+    }
+    if (gone) {
+        // this lane's way was written again
         lost = true;
         forgot = true;
         return true;
     }
-    const uint32_t way = count & 3u;
-    const uint32_t fw[4] = {f.x, f.y, f.z, f.w};
     bool lower = false;
 #pragma unroll
     for (uint32_t k = 0; k < 4; ++k) lower |= (k < way) & (fw[k] == id);

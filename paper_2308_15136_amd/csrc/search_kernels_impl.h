@@ -72,10 +72,13 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 // (or, for fp16, gain nothing).
 // The same for the narrow kernel with 129 to 256 candidates per pass, whose larger table and candidate
 // buffers bind it to 8 wavefronts per CU as well.
+#ifndef CAGRA_ROWS_IN_FLIGHT_MAX
+#define CAGRA_ROWS_IN_FLIGHT_MAX 8
+#endif
 template <int ELEM, int MR, int CR>
-constexpr int rows_in_flight_single() { return (ELEM == 0 && MR <= 2 && CR == 4) ? 8 : kRowsInFlight; }
+constexpr int rows_in_flight_single() { return (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX : kRowsInFlight; }
 template <int ELEM, int MR>
-constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= 2) ? 8 : kRowsInFlight; }
+constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= 2) ? CAGRA_ROWS_IN_FLIGHT_MAX : kRowsInFlight; }
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
@@ -452,6 +455,243 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
     qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
 }
 
+// ---- wave teams: several wavefronts of one workgroup on one query (Sec. IV-C.1 maps a query to a CTA
+// of several warps) ------------------------------------------------------------------------------------
+// Every wavefront of the team keeps its own copy of the top-M list in registers; the copies are identical
+// at the start of every pass.  The candidates of a pass are split evenly among the wavefronts; each tests its
+// share against the shared visited table, computes the distances of the first-time ones and updates its own
+// copy.  It then publishes those of its candidates that are still in its copy (at most itopk), the team meets at
+// a workgroup barrier, and every wavefront takes in what the others published.  Because the itopk best of a
+// union are among the itopk best of each part, all copies are again the itopk best of (list + all candidates
+// of the pass), which is the list of the one-wavefront search.  Parents are then selected by every wavefront
+// for itself (same list, same choice; the number of parents that steers the loop is wavefront 0's), so no list is
+// ever handed over.
+// The shared table is used in three steps per round, separated by workgroup barriers: all wavefronts test their
+// candidates, then all insert the missing ones, then all read their sets again.  One thing differs from one
+// wavefront: the insertions of different wavefronts reach the table in any order, so an id written under an older
+// count may land after, and replace, one written under a newer count of the same way.  sets_confirm<true>
+// therefore also looks whether the lane's own id is still where it put it and reports `lost` if not.  With that,
+// two lanes of one wavefront that both count their (same) node as new always come with a `lost` report in that
+// wavefront, and the complete check runs; the same node counted as new by two wavefronts is caught where a
+// published copy enters the other's list (always checked against the list first).  What the table forgets is
+// caught where candidates enter a list copy, as in the one-wavefront search.
+
+// sets_insert for a table shared by several wavefronts: `forgot` is a workgroup-wide word
+__device__ __forceinline__ uint32_t sets_insert_shared(uint32_t *table, uint32_t *cursor, uint32_t set, uint32_t id,
+                                                       uint32_t *forgot_word)
+{
+    const uint32_t sh = 8u * (set & 3u);
+    const uint32_t count = (atomicAdd(&cursor[set >> 2], 1u << sh) >> sh) & 0xFFu;
+    if (count >= 4u) *forgot_word = 1u;
+    table[4 * set + (count & 3u)] = id;
+    return count;
+}
+
+// This wavefront's share of a round: up to 64 * CRC candidates through the first-time test, the distance
+// computation and the update of its list copy; then the survivors are published in (pub_hi, pub_lo, pub_count).
+template <int MR, int CRC, int RIF>
+__device__ __forceinline__ void team_chunk(const SearchParams &P, const uint32_t (&raw)[4], uint32_t *table,
+                                           uint32_t *forgot_word, float *qlds, uint32_t *newid, float *newdist,
+                                           uint32_t (&thi)[MR], uint32_t (&tlo)[MR], uint32_t &n_dist_total, int &lead, int lane,
+                                           uint32_t *pub_hi, uint32_t *pub_lo, uint32_t *pub_count, int pub_cap)
+{
+    const int table_words = P.table_words;
+    uint32_t *cursor = table + table_words;
+    const uint32_t sets = (uint32_t)table_words >> 2;
+    int n_new = 0;
+    bool lost = false, forgot_lane = false;
+    bool fresh[CRC];
+    uint32_t set[CRC], way[CRC];
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) fresh[r] = sets_lookup(table, sets, raw[r], raw[r] != kInvalidId, set[r]);
+    __syncthreads();   // every wavefront of the team makes the same calls with the same CRC
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) way[r] = fresh[r] ? sets_insert_shared(table, cursor, set[r], raw[r], forgot_word) : 0u;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) fresh[r] = fresh[r] && sets_confirm<true>(table, cursor, set[r], way[r], raw[r], forgot_lane, lost);
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) {
+        const uint64_t m = __ballot(fresh[r]);
+        const int pos = n_new + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        if (fresh[r]) newid[pos] = raw[r];
+        n_new += __popcll(m);
+    }
+    n_dist_total += (uint32_t)n_new;
+    wave_sync();
+    team_distances<kElem, RIF>(P.dataset, P.ld, P.dim, P.metric, P.team_log2, newid, n_new, qlds, newdist);
+    wave_sync();
+    uint32_t chi[CRC], clo[CRC];
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) {
+        const int c = r * kWave + lane;
+        const bool v = c < n_new;
+        chi[r] = v ? f32_to_ordered(newdist[c]) : kDummyHi;
+        clo[r] = v ? (newid[c] << 1) : kInvalidId;
+    }
+    wave_sync();   // the update uses newid / newdist as its staging space
+    const bool forgot = *forgot_word != 0u;
+    update_topm<MR, CRC, true>(thi, tlo, chi, clo, P.itopk, lost, forgot, newid, newdist, lane, lead);
+    // publish the candidates that are in the list now: those not beyond its last entry
+    const int last = P.itopk - 1;
+    uint32_t whi = kDummyHi, wlo = kInvalidId;
+#pragma unroll
+    for (int r = 0; r < MR; ++r)
+        if (r == (last >> 6)) {
+            whi = __builtin_amdgcn_readlane(thi[r], last & 63);
+            wlo = __builtin_amdgcn_readlane(tlo[r], last & 63);
+        }
+    int n_pub = 0;
+#pragma unroll
+    for (int r = 0; r < CRC; ++r) {
+        const bool in = clo[r] != kInvalidId && !key_less(whi, wlo | 1u, chi[r], clo[r]);
+        const uint64_t m = __ballot(in);
+        const int pos = n_pub + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        if (in && pos < pub_cap) { pub_hi[pos] = chi[r]; pub_lo[pos] = clo[r]; }
+        n_pub += __popcll(m);
+    }
+    if (lane == 0) *pub_count = (uint32_t)(n_pub < pub_cap ? n_pub : pub_cap);
+}
+
+// What another wavefront published goes into this wavefront's copy of the list; every arrival is checked
+// against the list first (update_topm with `forgot` set).
+template <int MR, int CRX>
+__device__ __forceinline__ void team_take(const SearchParams &P, const uint32_t *pub_hi, const uint32_t *pub_lo, int first, int count,
+                                          uint32_t (&thi)[MR], uint32_t (&tlo)[MR], uint32_t *scratch_id, float *scratch_key,
+                                          int lane, int &lead)
+{
+    uint32_t chi[CRX], clo[CRX];
+#pragma unroll
+    for (int r = 0; r < CRX; ++r) {
+        const int c = first + r * kWave + lane;
+        const bool v = c < count;
+        chi[r] = v ? pub_hi[c] : kDummyHi;
+        clo[r] = v ? pub_lo[c] : kInvalidId;
+    }
+    update_topm<MR, CRX, true>(thi, tlo, chi, clo, P.itopk, false, true, scratch_id, scratch_key, lane, lead);
+}
+
+#ifndef CAGRA_TEAM_ROWS_IN_FLIGHT
+#define CAGRA_TEAM_ROWS_IN_FLIGHT 4
+#endif
+
+// The search of one query by a team of NW wavefronts (single mode, replacement table).  Called by all
+// wavefronts of the workgroup; on return every one of them holds the sorted top-M list in thi / tlo.
+template <int MR, int NW>
+__device__ __forceinline__ void search_body_team(const SearchParams &P, uint32_t qi, int wave, uint32_t *table,
+                                                 uint32_t *team_words, float *qlds, uint32_t *newid, float *newdist,
+                                                 uint32_t *parents, uint32_t *pub_hi, uint32_t *pub_lo,
+                                                 uint32_t (&thi)[MR], uint32_t (&tlo)[MR], QueryStats &qs)
+{
+    constexpr int CR = 4;
+    constexpr int kChunk = CR * kWave;
+    constexpr int RIF = CAGRA_TEAM_ROWS_IN_FLIGHT;
+    const int lane = lane_id();
+    const int tid = wave * kWave + lane;
+    const int n_cand = P.search_width * P.degree;
+    const int table_words = P.table_words;
+    uint32_t *cursor = table + table_words;
+    const uint32_t sets = (uint32_t)table_words >> 2;
+    const int pub_cap = P.pub_cap;
+    uint32_t *forgot_word = team_words;          // [0]
+    uint32_t *pub_count = team_words + 4;        // [4 .. 4 + 2 * NW)
+
+    const float *q = P.queries + (size_t)qi * P.ld_queries;
+    for (int j = tid; j < P.dim; j += kWave * NW) qlds[j] = q[j];
+    for (int j = 4 * tid; j < table_words; j += 4 * kWave * NW)
+        *reinterpret_cast<uint4 *>(table + j) = make_uint4(kInvalidId, kInvalidId, kInvalidId, kInvalidId);
+    for (int j = tid; j < (int)(sets + 3) / 4; j += kWave * NW) cursor[j] = 0u;
+    if (tid == 0) *forgot_word = 0u;
+#pragma unroll
+    for (int r = 0; r < MR; ++r) { thi[r] = kDummyHi; tlo[r] = kInvalidId; }
+    const uint64_t qh = seed_query_hash(P.seed, qi);
+    __syncthreads();
+
+    uint32_t n_iter = 0, n_parent_total = 0, n_dist_total = 0, flags = 0;
+    int lead = 0, n_par = 0;
+    uint32_t round = 0;
+    const uint32_t degree_magic = 0xFFFFFFFFu / (uint32_t)P.degree + 1u;   // ceil(2^32 / degree), degree >= 2
+
+    for (int it = 0;; ++it) {
+        const int n_src = it == 0 ? n_cand : n_par * P.degree;
+        for (int base = 0; base < n_src; base += NW * kChunk, ++round) {
+            const int n_round = n_src - base < NW * kChunk ? n_src - base : NW * kChunk;
+            const int share = (n_round + NW - 1) / NW;
+            const int lo = base + wave * share;
+            const int hi = lo + share < base + n_round ? lo + share : base + n_round;
+            uint32_t raw[CR];
+#pragma unroll
+            for (int r = 0; r < CR; ++r) {
+                const int c = lo + r * kWave + lane;
+                const bool v = c < hi;
+                if (it == 0) {
+                    raw[r] = v ? seed_slot_id(qh, (uint64_t)c, (uint64_t)P.N) : kInvalidId;
+                } else {
+                    const int pi = (int)__umulhi((uint32_t)c, degree_magic);   // c / degree, exact for c < 2^16
+                    raw[r] = v ? P.graph[(size_t)parents[v ? pi : 0] * P.degree + (c - pi * P.degree)] : kInvalidId;
+                }
+            }
+            const int buf = (int)(round & 1u);
+            uint32_t *my_hi = pub_hi + (buf * NW + wave) * pub_cap;
+            uint32_t *my_lo = pub_lo + (buf * NW + wave) * pub_cap;
+            if (share <= kWave)
+                team_chunk<MR, 1, RIF>(P, raw, table, forgot_word, qlds, newid, newdist, thi, tlo, n_dist_total, lead, lane,
+                                       my_hi, my_lo, pub_count + buf * NW + wave, pub_cap);
+            else if (share <= 2 * kWave)
+                team_chunk<MR, 2, RIF>(P, raw, table, forgot_word, qlds, newid, newdist, thi, tlo, n_dist_total, lead, lane,
+                                       my_hi, my_lo, pub_count + buf * NW + wave, pub_cap);
+            else
+                team_chunk<MR, 4, RIF>(P, raw, table, forgot_word, qlds, newid, newdist, thi, tlo, n_dist_total, lead, lane,
+                                       my_hi, my_lo, pub_count + buf * NW + wave, pub_cap);
+            __syncthreads();
+            // Two publication buffers, used in turn: a wavefront writes a buffer again two rounds later, after the
+            // barrier of the round in between, which every wavefront reaches only once it has read this one.
+#pragma unroll
+            for (int v = 0; v < NW; ++v) {
+                if (v == wave) continue;
+                const int cnt = (int)pub_count[buf * NW + v];
+                const uint32_t *o_hi = pub_hi + (buf * NW + v) * pub_cap;
+                const uint32_t *o_lo = pub_lo + (buf * NW + v) * pub_cap;
+                if (cnt == 0) continue;
+                if (cnt <= kWave) {
+                    team_take<MR, 1>(P, o_hi, o_lo, 0, cnt, thi, tlo, newid, newdist, lane, lead);
+                } else {
+                    for (int first = 0; first < cnt; first += kChunk)
+                        team_take<MR, 4>(P, o_hi, o_lo, first, cnt, thi, tlo, newid, newdist, lane, lead);
+                }
+                wave_sync();
+            }
+        }
+        if (it == P.max_iterations) { flags |= 1u; break; }
+
+        // step 2: parents = first search_width entries without the flag.  Every wavefront marks them in its own
+        // copy; the ids the team expands and the decision to go on are wavefront 0's, handed over through LDS, so
+        // that all wavefronts make the same number of rounds whatever their copies hold.
+        int n_sel = 0;
+#pragma unroll
+        for (int r = 0; r < MR; ++r) {
+            if ((r + 1) * kWave <= lead || n_sel == P.search_width) continue;
+            uint64_t m = __ballot((tlo[r] & 1u) == 0u);
+            while (m != 0ull && n_sel < P.search_width) {
+                const int l = __builtin_ctzll(m);
+                m &= m - 1;
+                const uint32_t w = __builtin_amdgcn_readlane(tlo[r], l);
+                if (lane == l) tlo[r] |= 1u;
+                if (tid == 0) parents[n_sel] = w >> 1;
+                ++n_sel;
+                lead = r * kWave + l + 1;
+            }
+        }
+        if (tid == 0) team_words[3] = (uint32_t)n_sel;
+        __syncthreads();
+        n_par = (int)team_words[3];
+        if (n_par == 0) break;
+        n_parent_total += (uint32_t)n_par;
+        ++n_iter;
+    }
+    qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
+}
+
 // First k of the sorted list -> ids / dists (Sec. IV-A, last sentence).
 template <int MR>
 __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
@@ -483,8 +723,11 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
         slot_nbr[r] = c - slot_parent[r] * P.degree;                             \
     }
 
+#ifndef CAGRA_MIN_WAVES
+#define CAGRA_MIN_WAVES 1
+#endif
 template <int ELEM, int MR, int CR, int KIND>
-__global__ void __launch_bounds__(kWave)
+__global__ void __launch_bounds__(kWave, CAGRA_MIN_WAVES)
 search_single_kernel(const SearchParams P)
 {
     CAGRA_LDS_VIEWS
@@ -516,7 +759,7 @@ search_single_kernel(const SearchParams P)
 
 // Single mode with more than 256 candidates per pass (search_body_wide).
 template <int ELEM, int MR, int KIND>
-__global__ void __launch_bounds__(kWave)
+__global__ void __launch_bounds__(kWave, CAGRA_MIN_WAVES)
 search_single_wide_kernel(const SearchParams P)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -544,6 +787,43 @@ search_single_wide_kernel(const SearchParams P)
         if (P.stats != nullptr && lane == 0) {
             uint32_t *s = P.stats + (size_t)qi * 4;
             s[0] = qs.n_iter; s[1] = qs.n_parent; s[2] = qs.n_dist; s[3] = qs.flags;
+        }
+        __syncthreads();
+    }
+}
+
+// Single mode with a team of NW wavefronts per query (search_body_team).  Workgroups are persistent and
+// take queries from the device counter like the one-wavefront kernels.
+template <int ELEM, int MR, int NW>
+__global__ void __launch_bounds__(kWave * NW)
+search_team_kernel(const SearchParams P)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    uint32_t *table = reinterpret_cast<uint32_t *>(smem);
+    uint32_t *team_words = reinterpret_cast<uint32_t *>(smem + P.off_team);
+    float *qlds = reinterpret_cast<float *>(smem + P.off_query);
+    uint32_t *newid = reinterpret_cast<uint32_t *>(smem + P.off_newid) + wave * 256;
+    float *newdist = reinterpret_cast<float *>(smem + P.off_newdist) + wave * 256;
+    uint32_t *parents = reinterpret_cast<uint32_t *>(smem + P.off_parents);   // one copy, written by wavefront 0
+    uint32_t *pub_hi = reinterpret_cast<uint32_t *>(smem + P.off_pub);
+    uint32_t *pub_lo = pub_hi + 2 * NW * P.pub_cap;
+    for (;;) {
+        if (threadIdx.x == 0) team_words[1] = atomicAdd(P.counter, 1u);
+        __syncthreads();
+        const uint32_t qi = team_words[1];
+        if ((int64_t)qi >= P.B) break;
+        if (threadIdx.x == 0) team_words[2] = 0u;
+        uint32_t thi[MR], tlo[MR];
+        QueryStats qs;
+        search_body_team<MR, NW>(P, qi, wave, table, team_words, qlds, newid, newdist, parents, pub_hi, pub_lo, thi, tlo, qs);
+        if (P.stats != nullptr && lane == 0) atomicAdd(team_words + 2, qs.n_dist);
+        if (wave == 0) write_result<MR>(P, qi, thi, tlo);
+        __syncthreads();
+        if (P.stats != nullptr && threadIdx.x == 0) {
+            uint32_t *s = P.stats + (size_t)qi * 4;
+            s[0] = qs.n_iter; s[1] = qs.n_parent; s[2] = team_words[2]; s[3] = qs.flags;
         }
         __syncthreads();
     }
@@ -667,6 +947,20 @@ static hipError_t launch_multi_one(const SearchParams &P, size_t smem, hipStream
     return hipGetLastError();
 }
 
+// `grid` comes in as (workgroups per CU the caller allows) x (compute units); it is cut down to what the kernel's
+// registers and LDS let reside at once, so that every workgroup of the persistent grid starts at once.
+template <int MR, int NW>
+static hipError_t launch_team_one(const SearchParams &P, int grid, int cus, size_t smem, hipStream_t stream)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_team_kernel<kElem, MR, NW>, kWave * NW, smem) == hipSuccess &&
+        per_cu > 0 && (int64_t)per_cu * cus < grid)
+        grid = per_cu * cus;
+    launch_zero_counter(P.counter, stream);
+    hipLaunchKernelGGL((search_team_kernel<kElem, MR, NW>), dim3(grid), dim3(kWave * NW), smem, stream, P);
+    return hipGetLastError();
+}
+
 #define CAGRA_CAT_(a, b) a##b
 #define CAGRA_CAT(a, b) CAGRA_CAT_(a, b)
 #define CAGRA_DISPATCH(FN, ...)                                                          \
@@ -703,6 +997,21 @@ hipError_t CAGRA_CAT(launch_search_wide_, CAGRA_ELEM_NAME)(const SearchParams &P
         case 2: return launch_wide_one<2>(P, grid, smem, stream);
         case 4: return launch_wide_one<4>(P, grid, smem, stream);
         case 8: return launch_wide_one<8>(P, grid, smem, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t CAGRA_CAT(launch_search_team_, CAGRA_ELEM_NAME)(const SearchParams &P, int mr, int waves, int grid, int cus, size_t smem, hipStream_t stream)
+{
+    switch (mr * 8 + waves) {
+        case 1 * 8 + 2: return launch_team_one<1, 2>(P, grid, cus, smem, stream);
+        case 2 * 8 + 2: return launch_team_one<2, 2>(P, grid, cus, smem, stream);
+        case 4 * 8 + 2: return launch_team_one<4, 2>(P, grid, cus, smem, stream);
+        case 8 * 8 + 2: return launch_team_one<8, 2>(P, grid, cus, smem, stream);
+        case 1 * 8 + 4: return launch_team_one<1, 4>(P, grid, cus, smem, stream);
+        case 2 * 8 + 4: return launch_team_one<2, 4>(P, grid, cus, smem, stream);
+        case 4 * 8 + 4: return launch_team_one<4, 4>(P, grid, cus, smem, stream);
+        case 8 * 8 + 4: return launch_team_one<8, 4>(P, grid, cus, smem, stream);
     }
     return hipErrorInvalidValue;
 }

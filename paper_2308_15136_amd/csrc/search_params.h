@@ -28,6 +28,9 @@ struct SearchParams {
     int32_t table_words;              // single mode: entries of the LDS table (multiple of 64)
     // byte offsets into the dynamic LDS block
     int32_t off_query, off_newid, off_newdist, off_parents;
+    // wave teams (several wavefronts per query): a few workgroup-wide words, the publication buffers
+    // (2 buffers x waves x pub_cap keys, high words then low words) and their capacity per wavefront
+    int32_t off_team, off_pub, pub_cap;
 };
 
 // One set of launchers per storage type of the dataset (fp32, fp16, uint8).
@@ -35,7 +38,8 @@ struct SearchParams {
     hipError_t launch_search_single_##T(const SearchParams &P, int mr, int cr, int grid, size_t smem, \
                                         hipStream_t stream);                                        \
     hipError_t launch_search_multi_##T(const SearchParams &P, int mr, int cr, size_t smem, hipStream_t stream); \
-    hipError_t launch_search_wide_##T(const SearchParams &P, int mr, int grid, size_t smem, hipStream_t stream);
+    hipError_t launch_search_wide_##T(const SearchParams &P, int mr, int grid, size_t smem, hipStream_t stream); \
+    hipError_t launch_search_team_##T(const SearchParams &P, int mr, int waves, int grid, int cus, size_t smem, hipStream_t stream);
 CAGRA_DECLARE_LAUNCHERS(f32)
 CAGRA_DECLARE_LAUNCHERS(f16)
 CAGRA_DECLARE_LAUNCHERS(u8)

@@ -1,7 +1,8 @@
 """A seeded sweep of search configurations on small integer-valued data (exact fp32 arithmetic, so
 GPU and oracle must agree bit for bit): dimensions that leave team lanes idle, degrees that are not
 powers of two, padded row strides, k = itopk, tiny and huge tables, both table policies, every
-storage type, all team sizes."""
+storage type, all team sizes.  One wavefront per query throughout (tests/test_gpu_team.py covers the teams of
+several wavefronts, which small batches would otherwise get automatically)."""
 import numpy as np
 import pytest
 
@@ -81,7 +82,8 @@ def test_sweep(cagra, i, dim, degree, width, itopk, k, storage, policy, entries,
         qd = qwide[:, :dim]
     else:
         qd = torch.from_numpy(queries).cuda()
-    opts = cagra.SearchOptions(seed=1000 + i, mode=1, table_policy=policy, table_entries=entries, team_size=team)
+    opts = cagra.SearchOptions(seed=1000 + i, mode=1, table_policy=policy, table_entries=entries, team_size=team,
+                               waves_per_query=1)
     ids, dists, st = cagra.search(torch.from_numpy(g.view(np.int32)).cuda(), data, qd, k, itopk, width, cagra.L2, opts,
                                   return_stats=True)
     r_ids, r_d, r_st = oracle.search(g, base, queries, k, itopk, width, oracle.L2, seed=1000 + i, return_stats=True)
@@ -126,7 +128,7 @@ def test_wide_passes(cagra, dim, degree, width, itopk, k, storage, policy, entri
     base, queries, g = _wide_index(dim, degree)
     dev_base = torch.from_numpy(base).cuda()
     data = dev_base if storage == "f32" else cagra.convert_dataset(dev_base, cagra.F16 if storage == "f16" else cagra.U8)
-    opts = cagra.SearchOptions(seed=77, mode=1, table_policy=policy, table_entries=entries)
+    opts = cagra.SearchOptions(seed=77, mode=1, table_policy=policy, table_entries=entries, waves_per_query=1)
     ids, dists, st = cagra.search(torch.from_numpy(g.view(np.int32)).cuda(), data, torch.from_numpy(queries).cuda(),
                                   k, itopk, width, cagra.L2, opts, return_stats=True)
     r_ids, r_d, r_st = oracle.search(g, base, queries, k, itopk, width, oracle.L2, seed=77, return_stats=True)
@@ -193,7 +195,8 @@ def test_mixed_sweep(cagra, i, dim, degree, width, itopk, k, storage, policy, en
     base, queries, g = _mixed_index(dim, degree)
     dev_base = torch.from_numpy(base).cuda()
     data = dev_base if storage == "f32" else cagra.convert_dataset(dev_base, cagra.F16 if storage == "f16" else cagra.U8)
-    opts = cagra.SearchOptions(seed=4000 + i, mode=1, table_policy=policy, table_entries=entries, team_size=team)
+    opts = cagra.SearchOptions(seed=4000 + i, mode=1, table_policy=policy, table_entries=entries, team_size=team,
+                               waves_per_query=1)
     ids, dists, st = cagra.search(torch.from_numpy(g.view(np.int32)).cuda(), data, torch.from_numpy(queries).cuda(),
                                   k, itopk, width, cagra.L2, opts, return_stats=True)
     r_ids, r_d, r_st = oracle.search(g, base, queries, k, itopk, width, oracle.L2, seed=4000 + i, return_stats=True)

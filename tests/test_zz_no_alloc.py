@@ -36,7 +36,10 @@ def test_static_scratch_single_mode_two_calls(setup):
         m.search_static(gd, bd, qd[:nq], k, itopk, width, w.metric, opts, out=(ids, dists), stats=stats)
         r_ids, r_d, r_st = m.search(gd, bd, qd[:nq], k, itopk, width, w.metric, opts, return_stats=True)
         torch.cuda.synchronize()
-        assert torch.equal(ids, r_ids) and torch.equal(dists, r_d) and torch.equal(stats, r_st)
+        assert torch.equal(ids, r_ids) and torch.equal(dists, r_d)
+        # passes, parents and flags are the search's own; the number of distances may differ from run to run when a
+        # batch this small is given a team of wavefronts per query (their table accesses interleave freely)
+        assert torch.equal(stats[:, [0, 1, 3]], r_st[:, [0, 1, 3]])
 
 
 def test_static_scratch_multi_mode_two_calls(setup):
