@@ -78,7 +78,9 @@ typedef struct {
                                  largest for which both itopk + interval * search_width * degree and, for the
                                  seeds and the passes before the first reset, (interval + 1) * search_width *
                                  degree stay within 7/8 of the table) */
-    int32_t wg_per_query;     /* multi mode: workgroups per query, 0 => search_width */
+    int32_t wg_per_query;     /* multi mode: workgroups (workers) per query; 0 => automatic: the largest of search_width,
+                                 ceil(itopk / 64) and, for batches below the number of compute units, compute units /
+                                 B (at most 32); cagra_search_describe reports it */
     int32_t table_entries;    /* single mode: entries of the LDS visited table given directly (multiple of 64,
                                  256..8192); 0 => from hash_bits.  Not both. */
     int32_t dataset_type;     /* a cagra_dtype: storage type of the rows behind `dataset` (0 = fp32) */
@@ -97,6 +99,13 @@ typedef struct {
                                  maps a query to a CTA of several warps, Sec. IV-C.1): 0 automatic, 1, 2 or 4.  A team
                                  shares the LDS visited table (replacement policy only) and splits the candidates of
                                  a pass; the results are those of one wavefront, bit for bit. */
+    int32_t workspace_clean;  /* multi mode: 1 = the caller vouches that the workspace is clean for exactly these search
+                                 arguments: cagra_search_workspace_init was run on it with them, or the last thing that
+                                 touched it was a cagra_search with them (every multi-mode search hands its tables and
+                                 tickets back clean) that has finished or precedes this call on the same stream.  The
+                                 search then is one kernel launch.  0 = unknown: the search cleans the workspace first
+                                 (one more launch).  A workspace that is dirty although 1 is given yields wrong results. */
+    int32_t reserved;         /* 0 */
     uint32_t *stats;          /* optional device [B, 4]: passes, parents expanded, distances computed,
                                  flags (bit 0: stopped by I_max, bit 1: visited table overflowed) */
 } cagra_search_opts;
@@ -132,6 +141,14 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree,
 size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_t k,
                                     int32_t itopk, int32_t search_width,
                                     const cagra_search_opts *opts /* host, may be NULL */);
+
+/* Puts a workspace into the clean state a multi-mode search with these arguments expects (empty visited tables,
+ * zero ticket counters); a search on it may then pass opts->workspace_clean = 1 and is a single kernel launch.
+ * Nothing to do, and nothing launched, when the arguments resolve to the single mode.  Same argument checks as
+ * cagra_search_describe, plus the workspace checks of cagra_search. */
+int cagra_search_workspace_init(int64_t N, int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,
+                                int32_t search_width, const cagra_search_opts *opts /* host, may be NULL */,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * cagra_search for callers that cannot allocate device memory and have no workspace to pass: code
@@ -169,6 +186,9 @@ typedef struct {
     int32_t workgroups;       /* launch size */
     int32_t table_policy;     /* single mode: 1 periodic reset, 2 replacement; 0 in multi mode */
     int32_t waves_per_query;  /* wavefronts per workgroup (1 in multi mode) */
+    int32_t reserved;
+    int64_t ws_tickets_offset; /* multi mode: where in the workspace the per-query ticket counters ([B] uint32, clean = 0) */
+    int64_t ws_tables_offset;  /* and the visited tables ([B, table_entries] uint32, clean = 0xFFFFFFFF) begin, in bytes */
 } cagra_search_plan;
 
 int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,

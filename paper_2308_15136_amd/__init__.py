@@ -45,7 +45,7 @@ class _SearchOpts(C.Structure):
                 ("team_size", C.c_int32), ("hash_bits", C.c_int32), ("reset_interval", C.c_int32),
                 ("wg_per_query", C.c_int32), ("table_entries", C.c_int32), ("dataset_type", C.c_int32),
                 ("table_policy", C.c_int32), ("workgroups_per_cu", C.c_int32), ("waves_per_query", C.c_int32),
-                ("stats", C.c_void_p)]
+                ("workspace_clean", C.c_int32), ("reserved", C.c_int32), ("stats", C.c_void_p)]
 
 
 class _BuildOpts(C.Structure):
@@ -56,7 +56,8 @@ class _BuildOpts(C.Structure):
 class _SearchPlan(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("mode", "team_size", "table_entries", "reset_interval",
                                          "max_iterations", "wg_per_query", "itopk_local", "lds_bytes",
-                                         "workgroups", "table_policy", "waves_per_query")]
+                                         "workgroups", "table_policy", "waves_per_query", "reserved")] + \
+               [("ws_tickets_offset", C.c_int64), ("ws_tables_offset", C.c_int64)]
 
 
 def load_library():
@@ -82,6 +83,8 @@ def load_library():
     lib.cagra_search_static.restype = C.c_int
     lib.cagra_search_static.argtypes = [vp, i64, i32, vp, i32, i64, C.c_int, vp, i64, i64, i32, i32, i32,
                                         opts_p, vp, vp, vp]
+    lib.cagra_search_workspace_init.restype = C.c_int
+    lib.cagra_search_workspace_init.argtypes = [i64, i32, i32, i64, i32, i32, i32, opts_p, vp, sz, vp]
     lib.cagra_search_describe.restype = C.c_int
     lib.cagra_search_describe.argtypes = [i32, i32, i64, i32, i32, i32, opts_p, C.POINTER(_SearchPlan)]
     lib.cagra_search_workspace_bytes.restype = sz
@@ -246,12 +249,13 @@ class SearchOptions:
     table_policy: int = 0      # 0 automatic, 1 periodic reset (the paper's), 2 replacement in sets of four
     workgroups_per_cu: int = 0  # single mode: persistent workgroups per compute unit, 0 automatic
     waves_per_query: int = 0   # single mode: wavefronts per query (0 automatic, 1, 2, 4)
+    workspace_clean: int = 0   # multi mode: 1 = the workspace passed in is clean for these arguments (see the header)
 
 
 def _copts(o: "SearchOptions", stats_ptr=None) -> _SearchOpts:
     return _SearchOpts(o.seed, o.max_iterations, o.mode, o.team_size, o.hash_bits, o.reset_interval,
                        o.wg_per_query, o.table_entries, o.dataset_type, o.table_policy, o.workgroups_per_cu,
-                       o.waves_per_query, stats_ptr)
+                       o.waves_per_query, o.workspace_clean, 0, stats_ptr)
 
 
 def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width: int = 1,
@@ -261,7 +265,17 @@ def describe(degree: int, dim: int, batch: int, k: int, itopk: int, search_width
     copts = _copts(options or SearchOptions())
     _check(load_library().cagra_search_describe(degree, dim, batch, k, itopk, search_width,
                                                 C.byref(copts), C.byref(plan)), "cagra_search_describe")
-    return {n: int(getattr(plan, n)) for n, _ in _SearchPlan._fields_}
+    return {n: int(getattr(plan, n)) for n, _ in _SearchPlan._fields_ if n != "reserved"}
+
+
+def search_workspace_init(workspace, n: int, degree: int, dim: int, batch: int, k: int, itopk: int, search_width: int = 1,
+                          options: Optional["SearchOptions"] = None) -> None:
+    """Clean `workspace` (uint8 device tensor) for multi-mode searches with these arguments; such a search may then
+    set SearchOptions.workspace_clean = 1."""
+    copts = _copts(options or SearchOptions())
+    _check(load_library().cagra_search_workspace_init(n, degree, dim, batch, k, itopk, search_width, C.byref(copts),
+                                                      workspace.data_ptr(), workspace.numel(), _stream(workspace.device)),
+           "cagra_search_workspace_init")
 
 
 def search_workspace_bytes(n: int, degree: int, batch: int, k: int, itopk: int, search_width: int = 1,
@@ -371,13 +385,19 @@ class PreparedSearch:
         graph, dataset, dtype, queries = _search_tensors(graph, dataset, queries, k, None, None)
         dev = dataset.device
         B = queries.shape[0]
-        o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype)
+        o = dataclasses.replace(options or SearchOptions(), dataset_type=dtype, workspace_clean=0)
         self._copts = _copts(o)
         self.ids = torch.empty((B, k), dtype=torch.int32, device=dev)
         self.dists = torch.empty((B, k), dtype=torch.float32, device=dev)
         N, degree = graph.shape
         self._ws = _workspace(self._lib.cagra_search_workspace_bytes(N, degree, B, k, itopk, search_width,
                                                                      C.byref(self._copts)), dev)
+        # the workspace belongs to this object alone: cleaned once here, handed back clean by every search, so every
+        # call may vouch for it (multi mode: one kernel launch per call)
+        _check(self._lib.cagra_search_workspace_init(N, degree, dataset.shape[1], B, k, itopk, search_width,
+                                                     C.byref(self._copts), self._ws.data_ptr(), self._ws.numel(),
+                                                     _stream(dev)), "cagra_search_workspace_init")
+        self._copts.workspace_clean = 1
         self._keep = (graph, dataset, queries)          # the call holds raw pointers into these
         self._device = dev
         self._shape = tuple(queries.shape)

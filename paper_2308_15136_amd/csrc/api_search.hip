@@ -192,8 +192,10 @@ static int single_per_cu(const cagra_search_opts &o, const SinglePlan &pl, const
 #endif
 
 struct MultiPlan {
-    int mr, cr, workers, itopk_local, hash_bits, team_log2, max_iterations;
-    size_t smem, table_bytes, list_bytes, done_bytes;
+    int mr, cr, workers, itopk_local, hash_bits, team_log2, max_iterations, log_cap;
+    // workspace: [256 bytes kept free for the single mode's query counter | done | tables | lists | logs]
+    size_t smem, table_bytes, list_bytes, done_bytes, log_bytes;
+    size_t off_done, off_tables, off_lists, off_logs, total_bytes;
     int off_query, off_newid, off_newdist, off_parents;
 };
 
@@ -207,7 +209,15 @@ static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int widt
 {
     const int pieces = dim / elems_per_piece(o.dataset_type);
     if (o.wg_per_query < 0 || o.wg_per_query > 1024) return CAGRA_ERR_BAD_OPTION;
-    pl.workers = o.wg_per_query == 0 ? width : o.wg_per_query;
+    if (o.wg_per_query != 0) {
+        pl.workers = o.wg_per_query;
+    } else {
+        // Automatic: at least search_width workers, enough of them that a worker's list stays within one register
+        // per lane (64 entries), and for batches below the number of compute units as many as fill the device
+        // once (at most 32: beyond that the final merge and the shared table cost more than the workers gain).
+        const int64_t fill = std::min<int64_t>(device_info().cus / std::max<int64_t>(B, 1), 32);
+        pl.workers = (int)std::min<int64_t>(1024, std::max<int64_t>(std::max(width, (itopk + 63) / 64), fill));
+    }
     if (pl.workers > 1024 || B * pl.workers > 0x7FFFFFFFll) return CAGRA_ERR_BAD_OPTION;
     int local = (itopk + pl.workers - 1) / pl.workers;
     local = std::max(local, std::max(k, 32));
@@ -230,6 +240,15 @@ static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int widt
     pl.table_bytes = align256(((size_t)B << bits) * 4);
     pl.list_bytes = align256((size_t)B * pl.workers * 64 * pl.mr * 8);
     pl.done_bytes = align256((size_t)B * 4);
+    // every worker writes down the table slots it fills (at most one per candidate it is offered) so that the
+    // last worker of the query can empty them: the workspace is handed back as clean as it came
+    pl.log_cap = degree * (pl.max_iterations + 1);
+    pl.log_bytes = align256((size_t)B * pl.workers * (8 + (size_t)pl.log_cap) * 4);
+    pl.off_done = 256;
+    pl.off_tables = pl.off_done + pl.done_bytes;
+    pl.off_lists = pl.off_tables + pl.table_bytes;
+    pl.off_logs = pl.off_lists + pl.list_bytes;
+    pl.total_bytes = pl.off_logs + pl.log_bytes;
     size_t off = 0;
     pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
     pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
@@ -264,6 +283,20 @@ static void *static_scratch()
     return ptr[dev];
 }
 
+// Layout (batch size, table size) of the last multi-mode search on this device's static array; a search with the
+// same layout finds its tables and tickets clean.  Remembers the new layout.
+static bool static_layout_is(int64_t B, int hash_bits)
+{
+    static int64_t last_b[64];
+    static int last_bits[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    const bool same = last_b[dev] == B && last_bits[dev] == hash_bits;
+    last_b[dev] = B;
+    last_bits[dev] = hash_bits;
+    return same;
+}
+
 }  // namespace cagra
 
 using namespace cagra;
@@ -276,16 +309,16 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
                        int64_t ld, cagra_metric metric, const float *queries, int64_t B, int64_t ld_queries,
                        int32_t k, int32_t itopk, int32_t search_width, const cagra_search_opts &o,
                        uint32_t *ids_out, float *dists_out, void *workspace, size_t workspace_bytes,
-                       void *hip_stream)
+                       void *hip_stream, bool init_only = false)
 {
-    if (!graph || !dataset) return CAGRA_ERR_NULL_POINTER;
-    if (B > 0 && (!queries || !ids_out || !dists_out)) return CAGRA_ERR_NULL_POINTER;
+    if (!init_only && (!graph || !dataset)) return CAGRA_ERR_NULL_POINTER;
+    if (!init_only && B > 0 && (!queries || !ids_out || !dists_out)) return CAGRA_ERR_NULL_POINTER;
     const int epp = elems_per_piece(o.dataset_type);
     if (epp == 0) return CAGRA_ERR_BAD_OPTION;
     if (N < 1 || N > 0x7FFFFFFFll || dim < 4 || (dim % epp) || ld < dim || (ld % epp) || B < 0 ||
         B > 0x7FFFFFFFll || ld_queries < dim)
         return CAGRA_ERR_BAD_SHAPE;
-    if (((uintptr_t)dataset & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
+    if (!init_only && ((uintptr_t)dataset & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
     if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
     if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
     if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
@@ -304,23 +337,33 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
         MultiPlan pl;
         int rc = plan_multi(degree, dim, B, k, itopk, search_width, o, pl);
         if (rc != CAGRA_OK) return rc;
+        if (o.workspace_clean != 0 && o.workspace_clean != 1) return CAGRA_ERR_BAD_OPTION;
+        bool clean = o.workspace_clean == 1;
         if (workspace == kStaticScratch) {
-            if (pl.table_bytes + pl.list_bytes + pl.done_bytes > (size_t)CAGRA_STATIC_SCRATCH_BYTES) return CAGRA_ERR_WORKSPACE;
+            if (pl.total_bytes > (size_t)CAGRA_STATIC_SCRATCH_BYTES) return CAGRA_ERR_WORKSPACE;
             if (!(workspace = static_scratch())) return CAGRA_ERR_LAUNCH;
             workspace_bytes = CAGRA_STATIC_SCRATCH_BYTES;
+            // The library's own array: it is clean if the last multi-mode search on it had this layout (every search
+            // leaves its tables and tickets clean; single-mode searches only touch the first 256 bytes).
+            clean = static_layout_is(B, pl.hash_bits);
         }
-        if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
-            workspace_bytes < pl.table_bytes + pl.list_bytes + pl.done_bytes)
+        if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total_bytes)
             return CAGRA_ERR_WORKSPACE;
         unsigned char *w = static_cast<unsigned char *>(workspace);
-        P.tables = reinterpret_cast<uint32_t *>(w);
-        P.lists = reinterpret_cast<uint64_t *>(w + pl.table_bytes);
-        P.done = reinterpret_cast<uint32_t *>(w + pl.table_bytes + pl.list_bytes);
+        P.done = reinterpret_cast<uint32_t *>(w + pl.off_done);
+        P.tables = reinterpret_cast<uint32_t *>(w + pl.off_tables);
+        P.lists = reinterpret_cast<uint64_t *>(w + pl.off_lists);
+        P.logs = reinterpret_cast<uint32_t *>(w + pl.off_logs);
+        P.log_cap = pl.log_cap; P.workspace_clean = clean ? 1 : 0;
         P.itopk = pl.itopk_local; P.search_width = 1; P.workers = pl.workers;
         P.max_iterations = pl.max_iterations; P.reset_interval = 0;
         P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
         P.off_query = pl.off_query; P.off_newid = pl.off_newid;
         P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
+        if (init_only) {
+            launch_multi_init(P, stream);
+            return hipGetLastError() == hipSuccess ? CAGRA_OK : CAGRA_ERR_LAUNCH;
+        }
         hipError_t e = o.dataset_type == CAGRA_F32   ? launch_search_multi_f32(P, pl.mr, pl.cr, pl.smem, stream)
                        : o.dataset_type == CAGRA_F16 ? launch_search_multi_f16(P, pl.mr, pl.cr, pl.smem, stream)
                                                      : launch_search_multi_u8(P, pl.mr, pl.cr, pl.smem, stream);
@@ -330,6 +373,7 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
     SinglePlan pl;
     int rc = plan_single(degree, dim, B, itopk, search_width, o, pl);
     if (rc != CAGRA_OK) return rc;
+    if (init_only) return CAGRA_OK;   // the single mode resets its query counter itself
     if (workspace == kStaticScratch) {
         if (!(workspace = static_scratch())) return CAGRA_ERR_LAUNCH;
         workspace_bytes = CAGRA_STATIC_SCRATCH_BYTES;
@@ -402,7 +446,7 @@ size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_
     if (resolve_mode(o, B, itopk) == 1) return 256;  // the persistent-scheduling counter
     MultiPlan pl;
     if (plan_multi(degree, 16, B, k, itopk, search_width, o, pl) != CAGRA_OK) return 256;
-    return pl.table_bytes + pl.list_bytes + pl.done_bytes;
+    return pl.total_bytes;
 }
 
 int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,
@@ -427,6 +471,7 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
         out.table_policy = 0;
         out.max_iterations = pl.max_iterations; out.wg_per_query = pl.workers; out.itopk_local = pl.itopk_local;
         out.lds_bytes = (int32_t)pl.smem; out.workgroups = (int32_t)(B * pl.workers); out.waves_per_query = 1;
+        out.ws_tickets_offset = (int64_t)pl.off_done; out.ws_tables_offset = (int64_t)pl.off_tables;
     } else {
         SinglePlan pl;
         int rc = plan_single(degree, dim, B, itopk, search_width, o, pl);
@@ -452,6 +497,21 @@ int cagra_search(const uint32_t *graph, int64_t N, int32_t degree, const void *d
     if (workspace == kStaticScratch) return CAGRA_ERR_WORKSPACE;
     return search_impl(graph, N, degree, dataset, dim, ld, metric, queries, B, ld_queries, k, itopk, search_width,
                        o, ids_out, dists_out, workspace, workspace_bytes, hip_stream);
+}
+
+int cagra_search_workspace_init(int64_t N, int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,
+                                int32_t search_width, const cagra_search_opts *opts, void *workspace,
+                                size_t workspace_bytes, void *hip_stream)
+{
+    cagra_search_opts o = {};
+    if (opts) o = *opts;
+    if (workspace == kStaticScratch) return CAGRA_ERR_WORKSPACE;
+    if (B == 0) return CAGRA_OK;
+    o.workspace_clean = 0;
+    const int epp = elems_per_piece(o.dataset_type);
+    if (epp == 0) return CAGRA_ERR_BAD_OPTION;
+    return search_impl(nullptr, N, degree, nullptr, dim, dim, CAGRA_L2, nullptr, B, dim, k, itopk, search_width, o, nullptr,
+                       nullptr, workspace, workspace_bytes, hip_stream, true);
 }
 
 int cagra_search_static(const uint32_t *graph, int64_t N, int32_t degree, const void *dataset, int32_t dim,

@@ -18,6 +18,7 @@ struct SearchParams {
     uint32_t *tables;     // [B, 1 << hash_bits]
     uint64_t *lists;      // [B, workers, 64 * MR]
     uint32_t *done;       // [B]
+    uint32_t *logs;       // [B, workers, 8 + log_cap]: per worker a header and the table slots it filled
     int64_t N, B, ld, ld_queries;
     uint64_t seed;
     int32_t degree, dim, metric;
@@ -31,6 +32,8 @@ struct SearchParams {
     // wave teams (several wavefronts per query): a few workgroup-wide words, the publication buffers
     // (2 buffers x waves x pub_cap keys, high words then low words) and their capacity per wavefront
     int32_t off_team, off_pub, pub_cap;
+    int32_t log_cap;                  // multi mode: slots a worker can fill = degree * (max_iterations + 1)
+    int32_t workspace_clean;          // multi mode: the caller vouches for a clean workspace, no init launch
 };
 
 // One set of launchers per storage type of the dataset (fp32, fp16, uint8).

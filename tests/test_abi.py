@@ -65,7 +65,13 @@ def test_describe_reports_the_automatic_parameters():
     assert r["table_policy"] == 1 and r["reset_interval"] >= 1
     assert 128 + r["reset_interval"] * 64 <= r["table_entries"] // 8 * 7
     q = m.describe(32, 96, 1, 10, 64, 4, m.SearchOptions(mode=2))
-    assert q["mode"] == 2 and q["wg_per_query"] == 4 and q["itopk_local"] == 32
+    # one query on an idle device: as many workers as fill it once, at most 32
+    assert q["mode"] == 2 and q["wg_per_query"] == 32 and q["itopk_local"] == 32
+    q = m.describe(32, 96, 100_000, 10, 64, 4, m.SearchOptions(mode=2))
+    assert q["wg_per_query"] == 4 and q["ws_tables_offset"] > q["ws_tickets_offset"] >= 256
+    # lists beyond the one-workgroup limit: enough workers that each keeps at most 64 entries
+    q = m.describe(32, 96, 100_000, 10, 2048, 1, m.SearchOptions())
+    assert q["mode"] == 2 and q["wg_per_query"] == 32 and q["itopk_local"] == 64
     assert q["table_entries"] >= 2 * 4 * 32 * (q["max_iterations"] + 1)     # Sec. IV-B.3: at least twice
     assert m.describe(32, 200, 10_000, 10, 64, 1, m.SearchOptions(mode=1))["team_size"] == 16
     with pytest.raises(m.CagraError):

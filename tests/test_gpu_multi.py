@@ -178,3 +178,67 @@ def test_lists_that_hold_every_node_give_the_exact_answer(cagra, workers):
     assert plan["itopk_local"] >= n and plan["wg_per_query"] == workers
     np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), ref_ids)
     np.testing.assert_array_equal(dists.cpu().numpy(), ref_d)
+
+
+def _workspace_is_clean(cagra, ws, plan, batch):
+    """The clean state of a multi-mode workspace: ticket counters zero, every table slot empty."""
+    import torch
+    words = ws.view(torch.int32)
+    t0, d0 = plan["ws_tables_offset"] // 4, plan["ws_tickets_offset"] // 4
+    tickets = words[d0:d0 + batch]
+    tables = words[t0:t0 + batch * plan["table_entries"]]
+    return bool((tickets == 0).all().item()) and bool((tables == -1).all().item())
+
+
+@pytest.mark.parametrize("workers,itopk,max_it", [(1, 64, 0), (8, 256, 12), (32, 1024, 4)])
+def test_every_search_hands_the_workspace_back_clean(cagra, workers, itopk, max_it):
+    # Sec. IV-C.2's device-memory table is emptied by the last worker of each query, so a caller who keeps the
+    # workspace may vouch for it and the search is one kernel launch.  Checked slot by slot after every call.
+    import torch
+    w, g, gt, (gd, bd, qd) = _setup("sift1m", 20_000, 200, 64)
+    k, nb = 10, 7
+    opts = cagra.SearchOptions(seed=3, mode=2, wg_per_query=workers, max_iterations=max_it)
+    plan = cagra.describe(64, 128, nb, k, itopk, 1, opts)
+    ws = torch.empty(cagra.search_workspace_bytes(20_000, 64, nb, k, itopk, 1, opts), dtype=torch.uint8, device="cuda")
+    ws.random_(0, 256)                                    # whatever was there before
+    cagra.search_workspace_init(ws, 20_000, 64, 128, nb, k, itopk, 1, opts)
+    torch.cuda.synchronize()
+    assert _workspace_is_clean(cagra, ws, plan, nb)
+    import dataclasses
+    vouch = dataclasses.replace(opts, workspace_clean=1)
+    print(f"case clean workspace W={workers} M={itopk} I_max={max_it}", flush=True)
+    hits = 0
+    for call in range(12):
+        lo = call * nb
+        ids, dists, st = cagra.search(gd, bd, qd[lo:lo + nb], k, itopk, 1, w.metric, vouch, workspace=ws, return_stats=True)
+        torch.cuda.synchronize()
+        assert _workspace_is_clean(cagra, ws, plan, nb), f"call {call} left something behind"
+        ids_np = ids.cpu().numpy().view(np.uint32)
+        st_np = st.cpu().numpy().view(np.uint32)
+        assert not np.any(st_np[:, 3] & 2) and np.all(st_np[:, 2] > 0) and np.all(st_np[:, 1] <= st_np[:, 0].astype(np.int64) * workers)
+        if workers == 1:
+            # one worker is deterministic: the vouched-for call must equal the call that cleans first, bit for bit
+            e_ids, e_d, e_st = cagra.search(gd, bd, qd[lo:lo + nb], k, itopk, 1, w.metric, opts, return_stats=True)
+            assert torch.equal(ids, e_ids) and torch.equal(dists, e_d) and torch.equal(st, e_st)
+        srt = np.sort(ids_np, axis=1)
+        assert np.all(srt[:, 1:] != srt[:, :-1]) and np.all(np.diff(dists.cpu().numpy(), axis=1) >= 0)
+        hits += sum(len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ids_np, gt[lo:lo + nb]))
+    assert hits / (12.0 * nb * k) > (0.9 if workers > 1 else 0.85)
+
+
+def test_vouched_workspace_gives_the_exact_answer_call_after_call(cagra):
+    # lists longer than the dataset: the answer is unique whatever the interleaving, so a table slot left behind by an
+    # earlier call (a node wrongly taken for visited) would show as a missing neighbour
+    import torch
+    n, nq, degree, k, workers = 400, 60, 8, 10, 4
+    w = datagen.workload("sift1m", n=n, n_queries=nq)
+    g = oracle.build(w.base, degree, 2 * degree, w.metric)
+    ref_ids, ref_d = oracle.exact_search(w.base, w.queries, k, w.metric)
+    gd, bd, qd = torch.from_numpy(g.view(np.int32)).cuda(), torch.from_numpy(w.base).cuda(), torch.from_numpy(w.queries).cuda()
+    opts = cagra.SearchOptions(seed=21, mode=2, wg_per_query=workers, max_iterations=600)
+    nb = 5
+    call = cagra.PreparedSearch(gd, bd, qd[:nb].clone(), k, 512 * workers, 1, w.metric, opts)
+    for lo in range(0, nq, nb):
+        ids, dists = call(qd[lo:lo + nb])
+        np.testing.assert_array_equal(ids.cpu().numpy().view(np.uint32), ref_ids[lo:lo + nb])
+        np.testing.assert_array_equal(dists.cpu().numpy(), ref_d[lo:lo + nb])

@@ -205,3 +205,63 @@ def test_mixed_sweep(cagra, i, dim, degree, width, itopk, k, storage, policy, en
     st = st.cpu().numpy().view(np.uint32)
     np.testing.assert_array_equal(st[:, :2], r_st[:, :2])
     assert np.all(st[:, 2] >= r_st[:, 2]) and not np.any(st[:, 3] & 2)
+
+
+def _float_cases():
+    # floating-point rows (unit norm) and both metrics through narrow and wide passes: the bars are the stated
+    # ones for data on which rounding can differ (distances within 1e-5, id agreement >= 99.5 % per batch)
+    rng = np.random.default_rng(99)
+    cases = []
+    for i in range(36):
+        dim = int(rng.choice([32, 64, 96, 128, 200]))
+        degree = int(rng.choice([8, 16, 32, 64]))
+        width = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        while width * degree > 2048:
+            width //= 2
+        itopk = int(rng.choice([16, 32, 64, 100, 128, 256]))
+        k = int(rng.choice([1, min(10, itopk), min(100, itopk)]))
+        metric = int(rng.choice([0, 1]))
+        storage = str(rng.choice(["f32", "f32", "f16"]))
+        if storage == "f16" and dim % 8:
+            storage = "f32"
+        waves = int(rng.choice([1, 1, 2, 4]))
+        cases.append((i, dim, degree, width, itopk, k, metric, storage, waves))
+    return cases
+
+
+_float_built = {}
+
+
+def _float_index(dim, degree, metric):
+    key = (dim, degree, metric)
+    if key not in _float_built:
+        base = datagen.unit_mixture(4000, dim, 24, min(32, dim), 1.5, 0.3, seed=900 + dim, stream=1)
+        queries = datagen.unit_mixture(100, dim, 24, min(32, dim), 1.5, 0.3, seed=900 + dim, stream=2)
+        _float_built[key] = (base, queries, oracle.build(base, degree, 2 * degree, metric))
+    return _float_built[key]
+
+
+@pytest.mark.parametrize("i,dim,degree,width,itopk,k,metric,storage,waves", _float_cases())
+def test_float_sweep(cagra, i, dim, degree, width, itopk, k, metric, storage, waves):
+    import torch
+    print(f"case float {i}: dim={dim} d={degree} p={width} M={itopk} k={k} metric={metric} {storage} waves={waves}", flush=True)
+    base, queries, g = _float_index(dim, degree, metric)
+    dev_base = torch.from_numpy(base).cuda()
+    if storage == "f16":
+        data = cagra.convert_dataset(dev_base, cagra.F16)
+        ref_base = base.astype(np.float16).astype(np.float32)      # the search over fp16 rows is the search over their values
+    else:
+        data, ref_base = dev_base, base
+    opts = cagra.SearchOptions(seed=8000 + i, mode=1, waves_per_query=waves)
+    ids, dists, st = cagra.search(torch.from_numpy(g.view(np.int32)).cuda(), data, torch.from_numpy(queries).cuda(),
+                                  k, itopk, width, metric, opts, return_stats=True)
+    ids, dists = ids.cpu().numpy().view(np.uint32), dists.cpu().numpy()
+    r_ids, r_d = oracle.search(g, ref_base, queries, k, itopk, width, metric, seed=8000 + i)
+    agree = sum(len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ids, r_ids)) / float(r_ids.size)
+    assert agree >= 0.995, f"id agreement {agree}"
+    same = ids == r_ids
+    # unit-norm rows and queries: |x||q| = 1, so for the inner product the bar is 1e-5 absolute (a relative bar has
+    # no meaning for values that pass through zero); for L2 it is relative
+    denom = np.maximum(np.abs(r_d), 1.0) if metric == oracle.IP else np.maximum(np.abs(r_d), 1e-30)
+    assert (np.abs(dists - r_d)[same] / denom[same]).max() <= 1e-5
+    assert np.all(np.diff(dists, axis=1) >= 0) and not np.any(st.cpu().numpy().view(np.uint32)[:, 3] & 2)
