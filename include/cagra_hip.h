@@ -101,8 +101,9 @@ typedef struct {
                                  a pass; the results are those of one wavefront, bit for bit. */
     int32_t workspace_clean;  /* multi mode: 1 = the caller vouches that the workspace is clean for exactly these search
                                  arguments: cagra_search_workspace_init was run on it with them, or the last thing that
-                                 touched it was a cagra_search with them (every multi-mode search hands its tables and
-                                 tickets back clean) that has finished or precedes this call on the same stream.  The
+                                 touched it was a cagra_search with them (every multi-mode search hands the workspace
+                                 back clean: each query has two tables, used in turn, and the workers of a search
+                                 empty the one the search before filled) that has finished or precedes this call on the same stream.  The
                                  search then is one kernel launch.  0 = unknown: the search cleans the workspace first
                                  (one more launch).  A workspace that is dirty although 1 is given yields wrong results. */
     int32_t reserved;         /* 0 */
@@ -143,7 +144,7 @@ size_t cagra_search_workspace_bytes(int64_t N, int32_t degree, int64_t B, int32_
                                     const cagra_search_opts *opts /* host, may be NULL */);
 
 /* Puts a workspace into the clean state a multi-mode search with these arguments expects (empty visited tables,
- * zero ticket counters); a search on it may then pass opts->workspace_clean = 1 and is a single kernel launch.
+ * zero ticket counters, table 0 in use); a search on it may then pass opts->workspace_clean = 1 and is a single kernel launch.
  * Nothing to do, and nothing launched, when the arguments resolve to the single mode.  Same argument checks as
  * cagra_search_describe, plus the workspace checks of cagra_search. */
 int cagra_search_workspace_init(int64_t N, int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,
@@ -187,8 +188,9 @@ typedef struct {
     int32_t table_policy;     /* single mode: 1 periodic reset, 2 replacement; 0 in multi mode */
     int32_t waves_per_query;  /* wavefronts per workgroup (1 in multi mode) */
     int32_t reserved;
-    int64_t ws_tickets_offset; /* multi mode: where in the workspace the per-query ticket counters ([B] uint32, clean = 0) */
-    int64_t ws_tables_offset;  /* and the visited tables ([B, table_entries] uint32, clean = 0xFFFFFFFF) begin, in bytes */
+    int64_t ws_tickets_offset; /* multi mode, byte offsets into the workspace: the per-query ticket counters ([B] uint32, */
+    int64_t ws_which_offset;   /* clean = 0); the words that say which of a query's two tables is in use ([B] uint32, 0 or */
+    int64_t ws_tables_offset;  /* 1); the tables ([B, 2, table_entries] uint32; clean = the one in use all 0xFFFFFFFF) */
 } cagra_search_plan;
 
 int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int32_t itopk,

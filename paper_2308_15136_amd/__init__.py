@@ -57,7 +57,7 @@ class _SearchPlan(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("mode", "team_size", "table_entries", "reset_interval",
                                          "max_iterations", "wg_per_query", "itopk_local", "lds_bytes",
                                          "workgroups", "table_policy", "waves_per_query", "reserved")] + \
-               [("ws_tickets_offset", C.c_int64), ("ws_tables_offset", C.c_int64)]
+               [("ws_tickets_offset", C.c_int64), ("ws_which_offset", C.c_int64), ("ws_tables_offset", C.c_int64)]
 
 
 def load_library():

@@ -192,10 +192,10 @@ static int single_per_cu(const cagra_search_opts &o, const SinglePlan &pl, const
 #endif
 
 struct MultiPlan {
-    int mr, cr, workers, itopk_local, hash_bits, team_log2, max_iterations, log_cap;
-    // workspace: [256 bytes kept free for the single mode's query counter | done | tables | lists | logs]
-    size_t smem, table_bytes, list_bytes, done_bytes, log_bytes;
-    size_t off_done, off_tables, off_lists, off_logs, total_bytes;
+    int mr, cr, workers, itopk_local, hash_bits, team_log2, max_iterations;
+    // workspace: [256 bytes kept free for the single mode's query counter | done | which | tables | lists | notes]
+    size_t smem, table_bytes, list_bytes, done_bytes, note_bytes;
+    size_t off_done, off_which, off_tables, off_lists, off_notes, total_bytes;
     int off_query, off_newid, off_newdist, off_parents;
 };
 
@@ -237,18 +237,16 @@ static int plan_multi(int degree, int dim, int64_t B, int k, int itopk, int widt
     while (bits < 27 && ((int64_t)1 << bits) < CAGRA_MULTI_TABLE_FACTOR * offered) ++bits;
     if (bits > 26) return CAGRA_ERR_HASH_CAPACITY;
     pl.hash_bits = bits;
-    pl.table_bytes = align256(((size_t)B << bits) * 4);
+    pl.table_bytes = align256(((size_t)2 * B << bits) * 4);   // two tables per query, used in turn
     pl.list_bytes = align256((size_t)B * pl.workers * 64 * pl.mr * 8);
     pl.done_bytes = align256((size_t)B * 4);
-    // every worker writes down the table slots it fills (at most one per candidate it is offered) so that the
-    // last worker of the query can empty them: the workspace is handed back as clean as it came
-    pl.log_cap = degree * (pl.max_iterations + 1);
-    pl.log_bytes = align256((size_t)B * pl.workers * (8 + (size_t)pl.log_cap) * 4);
+    pl.note_bytes = align256((size_t)B * pl.workers * 8 * 4);
     pl.off_done = 256;
-    pl.off_tables = pl.off_done + pl.done_bytes;
+    pl.off_which = pl.off_done + pl.done_bytes;
+    pl.off_tables = pl.off_which + pl.done_bytes;
     pl.off_lists = pl.off_tables + pl.table_bytes;
-    pl.off_logs = pl.off_lists + pl.list_bytes;
-    pl.total_bytes = pl.off_logs + pl.log_bytes;
+    pl.off_notes = pl.off_lists + pl.list_bytes;
+    pl.total_bytes = pl.off_notes + pl.note_bytes;
     size_t off = 0;
     pl.off_query = (int)off;      off += (size_t)4 * ((dim + 3) & ~3);
     pl.off_newid = (int)off;      off += (size_t)4 * 64 * pl.cr;
@@ -351,10 +349,11 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
             return CAGRA_ERR_WORKSPACE;
         unsigned char *w = static_cast<unsigned char *>(workspace);
         P.done = reinterpret_cast<uint32_t *>(w + pl.off_done);
+        P.which = reinterpret_cast<uint32_t *>(w + pl.off_which);
         P.tables = reinterpret_cast<uint32_t *>(w + pl.off_tables);
         P.lists = reinterpret_cast<uint64_t *>(w + pl.off_lists);
-        P.logs = reinterpret_cast<uint32_t *>(w + pl.off_logs);
-        P.log_cap = pl.log_cap; P.workspace_clean = clean ? 1 : 0;
+        P.notes = reinterpret_cast<uint32_t *>(w + pl.off_notes);
+        P.workspace_clean = clean ? 1 : 0;
         P.itopk = pl.itopk_local; P.search_width = 1; P.workers = pl.workers;
         P.max_iterations = pl.max_iterations; P.reset_interval = 0;
         P.hash_bits = pl.hash_bits; P.team_log2 = pl.team_log2;
@@ -471,7 +470,8 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
         out.table_policy = 0;
         out.max_iterations = pl.max_iterations; out.wg_per_query = pl.workers; out.itopk_local = pl.itopk_local;
         out.lds_bytes = (int32_t)pl.smem; out.workgroups = (int32_t)(B * pl.workers); out.waves_per_query = 1;
-        out.ws_tickets_offset = (int64_t)pl.off_done; out.ws_tables_offset = (int64_t)pl.off_tables;
+        out.ws_tickets_offset = (int64_t)pl.off_done; out.ws_which_offset = (int64_t)pl.off_which;
+        out.ws_tables_offset = (int64_t)pl.off_tables;
     } else {
         SinglePlan pl;
         int rc = plan_single(degree, dim, B, itopk, search_width, o, pl);

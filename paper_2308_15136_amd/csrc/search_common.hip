@@ -7,12 +7,13 @@ namespace cagra {
 
 __global__ void zero_counter_kernel(uint32_t *counter) { *counter = 0u; }
 
-// multi mode: empty visited tables, zero the per-query ticket counters (the clean state every search leaves behind)
-__global__ void multi_init_kernel(uint32_t *tables, size_t table_words_total, uint32_t *done, int64_t B)
+// multi mode: both visited tables of every query empty, ticket counters zero, table 0 in use (a clean workspace;
+// every search leaves the table that is in use next empty and the tickets zero)
+__global__ void multi_init_kernel(uint32_t *tables, size_t table_words_total, uint32_t *done, uint32_t *which, int64_t B)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < table_words_total) tables[i] = kInvalidId;
-    if (i < (size_t)B) done[i] = 0u;
+    if (i < (size_t)B) { done[i] = 0u; which[i] = 0u; }
 }
 
 void launch_zero_counter(uint32_t *counter, hipStream_t stream)
@@ -22,10 +23,10 @@ void launch_zero_counter(uint32_t *counter, hipStream_t stream)
 
 void launch_multi_init(const SearchParams &P, hipStream_t stream)
 {
-    const size_t words = (size_t)P.B << P.hash_bits;
+    const size_t words = (size_t)2 * P.B << P.hash_bits;
     const size_t n = words > (size_t)P.B ? words : (size_t)P.B;
     hipLaunchKernelGGL(multi_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
-                       P.tables, words, P.done, P.B);
+                       P.tables, words, P.done, P.which, P.B);
 }
 
 // fp32 -> fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255)

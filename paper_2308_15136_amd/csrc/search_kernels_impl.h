@@ -44,20 +44,15 @@ constexpr int kElem = CAGRA_ELEM;
 // Multi mode issues the first probe of every candidate before the dataset rows are fetched and
 // looks at its answer afterwards (the row loads do not wait for the table).  `old` is what the
 // first probe at the home slot returned; further probes only after a collision.
-// `slot` receives the table slot this call filled (kInvalidId if it filled none), so that the slot can be
-// emptied again once the query is done.
-__device__ __forceinline__ bool visited_resolve_global(uint32_t *table, int bits, uint32_t id, uint32_t old, bool &overflow,
-                                                       uint32_t &slot)
+__device__ __forceinline__ bool visited_resolve_global(uint32_t *table, int bits, uint32_t id, uint32_t old, bool &overflow)
 {
-    slot = kInvalidId;
-    const uint32_t home = hash_slot(id, bits);
-    if (old == kInvalidId) { slot = home; return true; }
+    if (old == kInvalidId) return true;
     if (old == id) return false;
     const uint32_t mask = (1u << bits) - 1u;
-    uint32_t s = (home + 1) & mask;
+    uint32_t s = (hash_slot(id, bits) + 1) & mask;
     for (uint32_t probe = 1; probe <= mask; ++probe) {
         old = atomicCAS(&table[s], kInvalidId, id);
-        if (old == kInvalidId) { slot = s; return true; }
+        if (old == kInvalidId) return true;
         if (old == id) return false;
         s = (s + 1) & mask;
     }
@@ -117,12 +112,10 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
                                             uint32_t *table, float *qlds, uint32_t *newid,
                                             float *newdist, uint32_t *parents,
                                             const int (&slot_parent)[CR], const int (&slot_nbr)[CR],
-                                            uint32_t (&thi)[MR], uint32_t (&tlo)[MR], QueryStats &qs,
-                                            uint32_t *slot_log = nullptr, uint32_t *slot_log_count = nullptr)
+                                            uint32_t (&thi)[MR], uint32_t (&tlo)[MR], QueryStats &qs)
 {
     const int lane = lane_id();
     const int team_log2 = P.team_log2;
-    uint32_t n_logged = 0;               // kTableGlobal: table slots this worker has filled
     const int n_cand = P.search_width * P.degree;
     constexpr bool MULTI = KIND == kTableGlobal;
     const int table_words = P.table_words;   // single mode: LDS table
@@ -217,14 +210,8 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
             int c = r * 64 + lane;
             bool v = c < n_new;
             if constexpr (KIND == kTableGlobal) {
-                uint32_t slot = kInvalidId;
-                v = raw[r] != kInvalidId && visited_resolve_global(table, P.hash_bits, raw[r], first_probe[r], overflow, slot);
+                v = raw[r] != kInvalidId && visited_resolve_global(table, P.hash_bits, raw[r], first_probe[r], overflow);
                 n_dist_total += (uint32_t)__popcll(__ballot(v));
-                // every slot this worker fills is written down; the last worker of the query empties them all
-                const uint64_t m = __ballot(slot != kInvalidId);
-                const uint32_t pos = n_logged + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                if (slot != kInvalidId && pos < (uint32_t)P.log_cap) slot_log[pos] = slot;
-                n_logged += (uint32_t)__popcll(m);
             }
             chi[r] = v ? f32_to_ordered(newdist[c]) : kDummyHi;
             clo[r] = v ? (newid[c] << 1) : kInvalidId;
@@ -303,7 +290,6 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
     CAGRA_PHASE_END()
     if (__ballot(overflow) != 0ull) flags |= 2u;
     qs.n_iter = n_iter; qs.n_parent = n_parent_total; qs.n_dist = n_dist_total; qs.flags = flags;
-    if constexpr (KIND == kTableGlobal) *slot_log_count = n_logged < (uint32_t)P.log_cap ? n_logged : (uint32_t)P.log_cap;
 }
 
 // One chunk of a wide pass: up to 64 * CRC candidates (raw[], kInvalidId where there is none) through the
@@ -865,14 +851,16 @@ __device__ __forceinline__ void result_from_heads(const SearchParams &P, uint32_
     write_result<R>(P, qi, hi, lo);
 }
 
-// Bookkeeping of a multi-mode worker in the workspace: eight words (slots filled, passes, parents, distances,
-// flags, three unused) followed by the slots themselves.
-constexpr int kLogHeader = 8;
+// What a multi-mode worker leaves in the workspace besides its list: eight words (passes, parents, distances, flags,
+// four unused), summed over the workers by the last one.
+constexpr int kNoteWords = 8;
 
-// The workspace comes in clean (every table slot empty, every ticket counter zero) and is left clean: the last
-// worker of a query, which is the only one that knows all the others are done with the table, empties the slots
-// that the workers wrote down and resets the ticket counter.  Statistics are summed by that worker as well, so
-// nothing has to be zeroed before a call.
+// Every query has two visited tables in the workspace and a word that says which one is in use.  The workers of a
+// query use that one, and each of them, before it starts, empties its share of the other one -- the table the
+// previous search on this workspace filled.  The last worker to finish switches the word over and resets the
+// ticket.  So a workspace that came in clean (table in use empty, ticket zero) goes out clean, the emptying is
+// spread over all workers and overlaps their first memory round trip, and nothing has to be zeroed by a launch
+// of its own before a call.
 template <int ELEM, int MR, int CR>
 __global__ void __launch_bounds__(kWave)
 search_multi_kernel(const SearchParams P)
@@ -880,17 +868,23 @@ search_multi_kernel(const SearchParams P)
     CAGRA_LDS_VIEWS
     const uint32_t qi = blockIdx.x / (uint32_t)P.workers;
     const int worker = (int)(blockIdx.x - qi * (uint32_t)P.workers);
-    uint32_t *table = P.tables + ((size_t)qi << P.hash_bits);
-    const size_t log_stride = (size_t)kLogHeader + (size_t)P.log_cap;
-    uint32_t *my_log = P.logs + ((size_t)qi * P.workers + worker) * log_stride;
+    const uint32_t in_use = __builtin_amdgcn_readfirstlane(P.which[qi]) & 1u;
+    uint32_t *table = P.tables + (((size_t)qi * 2 + in_use) << P.hash_bits);
+    {
+        uint32_t *other = P.tables + (((size_t)qi * 2 + (in_use ^ 1u)) << P.hash_bits);
+        const uint32_t words = 1u << P.hash_bits;                                       // a multiple of 1024
+        const uint32_t share = ((words / 4 + (uint32_t)P.workers - 1) / (uint32_t)P.workers) * 4;
+        const uint32_t lo = (uint32_t)worker * share;
+        const uint32_t hi = lo + share < words ? lo + share : words;
+        for (uint32_t j = lo + 4 * (uint32_t)lane; j < hi; j += 4 * kWave)
+            *reinterpret_cast<uint4 *>(other + j) = make_uint4(kInvalidId, kInvalidId, kInvalidId, kInvalidId);
+    }
+    uint32_t *my_note = P.notes + ((size_t)qi * P.workers + worker) * kNoteWords;
     uint32_t thi[MR], tlo[MR];
     QueryStats qs;
-    uint32_t n_logged = 0;
     search_body<MR, CR, kTableGlobal, kRowsInFlightMulti>(P, qi, worker, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
-                              thi, tlo, qs, my_log + kLogHeader, &n_logged);
-    if (lane == 0) {
-        my_log[0] = n_logged; my_log[1] = qs.n_iter; my_log[2] = qs.n_parent; my_log[3] = qs.n_dist; my_log[4] = qs.flags;
-    }
+                              thi, tlo, qs);
+    if (lane == 0) { my_note[0] = qs.n_iter; my_note[1] = qs.n_parent; my_note[2] = qs.n_dist; my_note[3] = qs.flags; }
     // publish this worker's list, then see whether every worker of the query has done so
     uint64_t *mine = P.lists + ((size_t)qi * P.workers + worker) * (64 * MR);
 #pragma unroll
@@ -901,43 +895,29 @@ search_multi_kernel(const SearchParams P)
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (uint32_t)P.workers - 1u) return;
     __threadfence();
-    // last worker.  First the bookkeeping: empty the slots all workers filled, sum their statistics, reset the ticket
-    {
+    // last worker: the other table is in use from now on, the ticket starts at zero again
+    if (lane == 0) { P.which[qi] = in_use ^ 1u; P.done[qi] = 0u; }
+    if (P.stats != nullptr) {
         uint32_t s_iter = 0, s_parent = 0, s_dist = 0, s_flags = 0;
-        const uint32_t *logs = P.logs + (size_t)qi * P.workers * log_stride;
-        for (int w0 = 0; w0 < P.workers; w0 += kWave) {
-            // one worker's header per lane, then every worker's slots by the whole wavefront
-            const int w = w0 + lane;
-            uint32_t cnt = 0;
-            if (w < P.workers) {
-                const uint32_t *h = logs + (size_t)w * log_stride;
-                cnt = __builtin_nontemporal_load(h);
-                s_iter = max(s_iter, __builtin_nontemporal_load(h + 1));
-                s_parent += __builtin_nontemporal_load(h + 2);
-                s_dist += __builtin_nontemporal_load(h + 3);
-                s_flags |= __builtin_nontemporal_load(h + 4);
-            }
-            const int n_here = P.workers - w0 < kWave ? P.workers - w0 : kWave;
-            for (int u = 0; u < n_here; ++u) {
-                const uint32_t c = __builtin_amdgcn_readlane(cnt, u);   // u is uniform
-                const uint32_t *slots = logs + (size_t)(w0 + u) * log_stride + kLogHeader;
-                for (uint32_t j = lane; j < c; j += kWave) table[__builtin_nontemporal_load(slots + j)] = kInvalidId;
-            }
+        const uint32_t *notes = P.notes + (size_t)qi * P.workers * kNoteWords;
+        for (int w = lane; w < P.workers; w += kWave) {
+            const uint32_t *h = notes + (size_t)w * kNoteWords;
+            s_iter = max(s_iter, __builtin_nontemporal_load(h));
+            s_parent += __builtin_nontemporal_load(h + 1);
+            s_dist += __builtin_nontemporal_load(h + 2);
+            s_flags |= __builtin_nontemporal_load(h + 3);
         }
-        if (P.stats != nullptr) {
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                s_iter = max(s_iter, shfl_xor_u32(s_iter, off));
-                s_parent += shfl_xor_u32(s_parent, off);
-                s_dist += shfl_xor_u32(s_dist, off);
-                s_flags |= shfl_xor_u32(s_flags, off);
-            }
-            if (lane == 0) {
-                uint32_t *s = P.stats + (size_t)qi * 4;
-                s[0] = s_iter; s[1] = s_parent; s[2] = s_dist; s[3] = s_flags;
-            }
+        for (int off = 32; off >= 1; off >>= 1) {
+            s_iter = max(s_iter, shfl_xor_u32(s_iter, off));
+            s_parent += shfl_xor_u32(s_parent, off);
+            s_dist += shfl_xor_u32(s_dist, off);
+            s_flags |= shfl_xor_u32(s_flags, off);
         }
-        if (lane == 0) P.done[qi] = 0u;
+        if (lane == 0) {
+            uint32_t *s = P.stats + (size_t)qi * 4;
+            s[0] = s_iter; s[1] = s_parent; s[2] = s_dist; s[3] = s_flags;
+        }
     }
     // Few enough heads (W * k <= 1024): one sort of the first k of every list
     const int heads = P.workers * P.k;

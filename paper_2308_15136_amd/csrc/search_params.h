@@ -15,10 +15,11 @@ struct SearchParams {
     uint32_t *counter;    // single mode: persistent-scheduling query counter (workspace)
     // multi mode (workspace): one visited table per query, every worker's final list, and a
     // per-query count of workers that have finished
-    uint32_t *tables;     // [B, 1 << hash_bits]
+    uint32_t *tables;     // [B, 2, 1 << hash_bits]: two tables per query, used in turn
+    uint32_t *which;      // [B]: which of a query's two tables is in use (0 / 1)
     uint64_t *lists;      // [B, workers, 64 * MR]
     uint32_t *done;       // [B]
-    uint32_t *logs;       // [B, workers, 8 + log_cap]: per worker a header and the table slots it filled
+    uint32_t *notes;      // [B, workers, 8]: per worker its pass / parent / distance counts and flags
     int64_t N, B, ld, ld_queries;
     uint64_t seed;
     int32_t degree, dim, metric;
@@ -32,7 +33,6 @@ struct SearchParams {
     // wave teams (several wavefronts per query): a few workgroup-wide words, the publication buffers
     // (2 buffers x waves x pub_cap keys, high words then low words) and their capacity per wavefront
     int32_t off_team, off_pub, pub_cap;
-    int32_t log_cap;                  // multi mode: slots a worker can fill = degree * (max_iterations + 1)
     int32_t workspace_clean;          // multi mode: the caller vouches for a clean workspace, no init launch
 };
 

@@ -181,13 +181,17 @@ def test_lists_that_hold_every_node_give_the_exact_answer(cagra, workers):
 
 
 def _workspace_is_clean(cagra, ws, plan, batch):
-    """The clean state of a multi-mode workspace: ticket counters zero, every table slot empty."""
+    """The clean state of a multi-mode workspace: ticket counters zero, and of the two tables of every query the one
+    that is in use next has every slot empty."""
     import torch
     words = ws.view(torch.int32)
-    t0, d0 = plan["ws_tables_offset"] // 4, plan["ws_tickets_offset"] // 4
-    tickets = words[d0:d0 + batch]
-    tables = words[t0:t0 + batch * plan["table_entries"]]
-    return bool((tickets == 0).all().item()) and bool((tables == -1).all().item())
+    t0, d0, w0 = plan["ws_tables_offset"] // 4, plan["ws_tickets_offset"] // 4, plan["ws_which_offset"] // 4
+    tickets, which = words[d0:d0 + batch], words[w0:w0 + batch]
+    tables = words[t0:t0 + 2 * batch * plan["table_entries"]].view(batch, 2, plan["table_entries"])
+    if not (bool((tickets == 0).all().item()) and bool(((which == 0) | (which == 1)).all().item())):
+        return False
+    in_use = tables[torch.arange(batch, device=ws.device), which.long()]
+    return bool((in_use == -1).all().item())
 
 
 @pytest.mark.parametrize("workers,itopk,max_it", [(1, 64, 0), (8, 256, 12), (32, 1024, 4)])
