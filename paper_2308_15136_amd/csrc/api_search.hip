@@ -54,7 +54,7 @@ static int elems_per_piece(int dataset_type)
 }
 
 #ifndef CAGRA_AUTO_SET_TABLE
-#define CAGRA_AUTO_SET_TABLE 3072
+#define CAGRA_AUTO_SET_TABLE 2560
 #endif
 constexpr int kAutoSetTableEntries = CAGRA_AUTO_SET_TABLE;
 
@@ -90,9 +90,8 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
 
     // Visited table in LDS (Sec. IV-B.3), in one of two managements.
     //  - replacement (default): sets of four ids, a new id replaces the oldest of its set.  Any size
-    //    works; automatic size 3072 to 4096 entries (12 to 16 KB plus a byte of cursor per set), the
-    //    measured optimum on the 1M x 128 workload: smaller tables forget more, larger ones cost
-    //    wavefronts per CU.
+    //    works; automatic size 2560 or 4096 entries (10 or 16 KB plus a byte of cursor per set), see below:
+    //    smaller tables forget more, larger ones cost wavefronts per CU.
     //  - periodic reset (the paper's; chosen by table_policy 1, or when hash_bits or reset_interval
     //    are given): open addressing.  Between two resets the table receives at most
     //    itopk + interval * n_cand ids; probing in LDS is cheap, so it may fill up to 7/8.
@@ -113,14 +112,17 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
         const int want = ((itopk + 8 * n_cand) * 8 / 7 + 63) & ~63;
         words = std::min(8192, std::max(4096, want));
     } else {
-        // measured on the 1M x 128 workload: 3072 entries for up to 64 candidates per pass, 3584 for up to
-        // 128, 4096 beyond (wider passes insert more per pass, and their candidate buffers already cost
-        // wavefronts per CU)
-        words = n_cand <= 64 ? kAutoSetTableEntries : n_cand <= 128 ? kAutoSetTableEntries + 512 : kAutoSetTableEntries + 1024;
+        // Up to 128 candidates per pass the kernels need few enough registers for three wavefronts per SIMD, so the
+        // table is what decides how many fit: 2560 entries leave room for twelve per CU (measured on the 1M x 96
+        // workload with 128 candidates per pass: 0.92 ms against 0.98 ms with 3584 entries and nine wavefronts, 0.3 %
+        // more distances; on the 1M x 128 workload with 64 candidates per pass the two are level).  Beyond that the
+        // candidate buffers and the rows in flight bind the kernel to eight wavefronts per CU, and 4096 entries are
+        // the measured optimum (smaller tables forget more, larger ones cost wavefronts).
+        words = n_cand <= 128 ? kAutoSetTableEntries : kAutoSetTableEntries + 1536;
         // a long query (many dimensions) must not push the workgroup over an eighth of the CU's LDS: the
         // eighth wavefront is worth more than the last 512 table entries
         const size_t rest = (size_t)4 * ((dim + 3) & ~3) + (size_t)8 * 64 * pl.cr + 256;
-        while (words > kAutoSetTableEntries && (size_t)4 * words + words / 4 + 16 + rest > (size_t)160 * 1024 / 8) words -= 512;
+        while (words > kAutoSetTableEntries + 1024 && (size_t)4 * words + words / 4 + 16 + rest > (size_t)160 * 1024 / 8) words -= 512;
         // (also beyond 256 candidates: measured with 320 to 2048 per pass, larger tables lose more to the
         // wavefronts they displace than they save in distances computed twice)
     }

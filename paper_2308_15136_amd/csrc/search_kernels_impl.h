@@ -77,8 +77,11 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 #endif
 template <int ELEM, int MR, int CR>
 constexpr int rows_in_flight_single() { return (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX : kRowsInFlight; }
+#ifndef CAGRA_WIDE_LONG_ROWS_MAX_MR
+#define CAGRA_WIDE_LONG_ROWS_MAX_MR 4
+#endif
 template <int ELEM, int MR>
-constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= 2) ? CAGRA_ROWS_IN_FLIGHT_MAX : kRowsInFlight; }
+constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= CAGRA_WIDE_LONG_ROWS_MAX_MR) ? CAGRA_ROWS_IN_FLIGHT_MAX : kRowsInFlight; }
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
@@ -723,8 +726,10 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
         slot_nbr[r] = c - slot_parent[r] * P.degree;                             \
     }
 
+// at least two wavefronts per SIMD: the compiler must stay within 256 registers (a few kernels would otherwise
+// take a handful more and drop to one wavefront per SIMD)
 #ifndef CAGRA_MIN_WAVES
-#define CAGRA_MIN_WAVES 1
+#define CAGRA_MIN_WAVES 2
 #endif
 template <int ELEM, int MR, int CR, int KIND>
 __global__ void __launch_bounds__(kWave, CAGRA_MIN_WAVES)

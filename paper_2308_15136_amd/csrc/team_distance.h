@@ -58,22 +58,29 @@ __device__ __forceinline__ void team_distances(const void *dataset, int64_t ld, 
             acc[u] = 0.f;
         }
         for (int base = 0; base < nchunk; base += 4 * team) {
+            // Every load is issued unconditionally: a lane whose piece lies beyond the row reads the row's last piece
+            // instead (its neighbours read it anyway), a team without a row reads row 0, and what they fetched is
+            // never used.  A load then costs one address addition instead of a predicate, a branch and four
+            // register clears, which is what the instruction stream of this loop mostly consisted of.
+            int ch[4];
+            bool in_row[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ch[i] = base + i * team + t;
+                in_row[i] = ch[i] < nchunk;
+            }
             uint4 x[RIF][4];
 #pragma unroll
             for (int u = 0; u < RIF; ++u)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int ch = base + i * team + t;
-                    x[u][i] = (ok[u] && ch < nchunk) ? *reinterpret_cast<const uint4 *>(row[u] + 16 * ch)
-                                                     : make_uint4(0, 0, 0, 0);
-                }
+                for (int i = 0; i < 4; ++i)
+                    x[u][i] = *reinterpret_cast<const uint4 *>(row[u] + 16 * (in_row[i] ? ch[i] : nchunk - 1));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int ch = base + i * team + t;
-                if (ch < nchunk) {
+                if (in_row[i]) {
 #pragma unroll
                     for (int h = 0; h < kPiece / 4; ++h) {
-                        const float4 qv = *reinterpret_cast<const float4 *>(qlds + kPiece * ch + 4 * h);
+                        const float4 qv = *reinterpret_cast<const float4 *>(qlds + kPiece * ch[i] + 4 * h);
                         if (metric == 0) {
 #pragma unroll
                             for (int u = 0; u < RIF; ++u) {

@@ -196,7 +196,7 @@ def workload(name: str, n: Optional[int] = None, n_queries: Optional[int] = None
         b = n_queries or 1_000
         base = unit_mixture(n, 96, 4096, 40, 1.5, 0.1, seed=4, stream=1)
         qs = unit_mixture(b, 96, 4096, 40, 1.5, 0.1, seed=4, stream=2)
-        return Workload(name, base, qs, L2, 32, 64, 10, (64, 128, 256), search_width=4)
+        return Workload(name, base, qs, L2, 32, 64, 10, (64, 128, 256), search_width=4, search_widths=(1, 2, 4, 8, 16))
     raise ValueError(f"unknown workload {name!r}")
 
 
