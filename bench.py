@@ -611,6 +611,10 @@ def main() -> int:
             mopts = cagra.SearchOptions(seed=20230815, mode=2, wg_per_query=W, max_iterations=imax)
             mws = torch.empty(cagra.search_workspace_bytes(N, w.degree, 1, w.k, 32 * W, 1, mopts),
                               dtype=torch.uint8, device=dev)
+            # cleaned once; every search hands the workspace back clean, so the captured call is one kernel
+            cagra.search_workspace_init(mws, N, w.degree, dim, 1, w.k, 32 * W, 1, mopts)
+            import dataclasses
+            mopts = dataclasses.replace(mopts, workspace_clean=1)
             q_fix = queries[:1].clone()
             g_ids = torch.empty((1, w.k), dtype=torch.int32, device=dev)
             g_d = torch.empty((1, w.k), dtype=torch.float32, device=dev)
@@ -638,7 +642,7 @@ def main() -> int:
                     # several workers interleave differently from run to run, so replay and eager call are
                     # compared by their recall over the same 200 queries, not id by id
                     hit_graph += len(np.intersect1d(g_ids.cpu().numpy().view(np.uint32)[0], gt_np[qi_r]))
-                    e_ids, _ = cagra.search(graph, base, src, w.k, 32 * W, 1, w.metric, mopts)
+                    e_ids, _ = cagra.search(graph, base, src, w.k, 32 * W, 1, w.metric, dataclasses.replace(mopts, workspace_clean=0))
                     hit_eager += len(np.intersect1d(e_ids.cpu().numpy().view(np.uint32)[0], gt_np[qi_r]))
             best_lat["graph_replay"] = {"p50_us": round(float(np.percentile(lat, 50)), 1),
                                         "p99_us": round(float(np.percentile(lat, 99)), 1),

@@ -119,6 +119,10 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
         // candidate buffers and the rows in flight bind the kernel to eight wavefronts per CU, and 4096 entries are
         // the measured optimum (smaller tables forget more, larger ones cost wavefronts).
         words = n_cand <= 128 ? kAutoSetTableEntries : kAutoSetTableEntries + 1536;
+        // Rows of the narrow storage types are short: the memory system is not what limits their search, a third
+        // wavefront per SIMD is (0.90 against 1.05 ms with byte rows at the benchmark's timed point), and with lists of
+        // at most 128 entries the kernels leave registers for it.  2304 entries make the LDS fit twelve per CU.
+        if (o.dataset_type != CAGRA_F32 && pl.mr <= 2 && n_cand > 128) words = 2304;
         // a long query (many dimensions) must not push the workgroup over an eighth of the CU's LDS: the
         // eighth wavefront is worth more than the last 512 table entries
         const size_t rest = (size_t)4 * ((dim + 3) & ~3) + (size_t)8 * 64 * pl.cr + 256;

@@ -72,16 +72,19 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 // (or, for fp16, gain nothing).
 // The same for the narrow kernel with 129 to 256 candidates per pass, whose larger table and candidate
 // buffers bind it to 8 wavefronts per CU as well.
+#ifndef CAGRA_ROWS_IN_FLIGHT_U8
+#define CAGRA_ROWS_IN_FLIGHT_U8 3
+#endif
 #ifndef CAGRA_ROWS_IN_FLIGHT_MAX
 #define CAGRA_ROWS_IN_FLIGHT_MAX 8
 #endif
 template <int ELEM, int MR, int CR>
-constexpr int rows_in_flight_single() { return (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX : kRowsInFlight; }
+constexpr int rows_in_flight_single() { return (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX : ELEM == 2 ? CAGRA_ROWS_IN_FLIGHT_U8 : kRowsInFlight; }
 #ifndef CAGRA_WIDE_LONG_ROWS_MAX_MR
 #define CAGRA_WIDE_LONG_ROWS_MAX_MR 4
 #endif
 template <int ELEM, int MR>
-constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= CAGRA_WIDE_LONG_ROWS_MAX_MR) ? CAGRA_ROWS_IN_FLIGHT_MAX : kRowsInFlight; }
+constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= CAGRA_WIDE_LONG_ROWS_MAX_MR) ? CAGRA_ROWS_IN_FLIGHT_MAX : ELEM == 2 ? CAGRA_ROWS_IN_FLIGHT_U8 : kRowsInFlight; }
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
@@ -726,13 +729,18 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
         slot_nbr[r] = c - slot_parent[r] * P.degree;                             \
     }
 
-// at least two wavefronts per SIMD: the compiler must stay within 256 registers (a few kernels would otherwise
-// take a handful more and drop to one wavefront per SIMD)
-#ifndef CAGRA_MIN_WAVES
-#define CAGRA_MIN_WAVES 2
+// Wavefronts per SIMD the compiler has to leave room for.  Two everywhere (256 registers; a few kernels would
+// otherwise take a handful more and drop to one).  Three (168 registers) for the narrow storage types with lists up
+// to CAGRA_NARROW_3_MAX_MR * 64 entries: their rows are short, the memory system is not what limits them, and a
+// third wavefront per SIMD is worth 12 to 15 % (measured on the 1M x 128 workload).
+#ifndef CAGRA_NARROW_3_MAX_MR
+#define CAGRA_NARROW_3_MAX_MR 2
 #endif
+template <int ELEM, int MR>
+constexpr int min_waves() { return (ELEM != 0 && MR <= CAGRA_NARROW_3_MAX_MR) ? 3 : 2; }
+
 template <int ELEM, int MR, int CR, int KIND>
-__global__ void __launch_bounds__(kWave, CAGRA_MIN_WAVES)
+__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR>()))
 search_single_kernel(const SearchParams P)
 {
     CAGRA_LDS_VIEWS
@@ -764,7 +772,7 @@ search_single_kernel(const SearchParams P)
 
 // Single mode with more than 256 candidates per pass (search_body_wide).
 template <int ELEM, int MR, int KIND>
-__global__ void __launch_bounds__(kWave, CAGRA_MIN_WAVES)
+__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR>()))
 search_single_wide_kernel(const SearchParams P)
 {
     extern __shared__ __align__(16) unsigned char smem[];

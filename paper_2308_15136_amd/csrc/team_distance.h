@@ -33,9 +33,9 @@ __device__ __forceinline__ float4 widen4(const uint4 &p, int i)
 // skipped).  Called by all 64 lanes of a wavefront; qlds holds the query as fp32, `ld` is the row
 // stride in elements, RIF the rows each team keeps in flight (all loads of a round are issued
 // before any is used).  metric 0: squared L2, else 0 - <x, q>.
-template <int ELEM, int RIF>
-__device__ __forceinline__ void team_distances(const void *dataset, int64_t ld, int dim, int metric, int team_log2,
-                                               const uint32_t *newid, int n_new, const float *qlds, float *newdist)
+template <int ELEM, int RIF, int SLOTS>
+__device__ __forceinline__ void team_distances_impl(const void *dataset, int64_t ld, int dim, int metric, int team_log2,
+                                                    const uint32_t *newid, int n_new, const float *qlds, float *newdist)
 {
     constexpr int kPiece = elems_per_piece<ELEM>();
     constexpr int kBytes = 16 / kPiece;
@@ -57,26 +57,26 @@ __device__ __forceinline__ void team_distances(const void *dataset, int64_t ld, 
             row[u] = static_cast<const unsigned char *>(dataset) + (size_t)(ok[u] ? node : 0u) * ld * kBytes;
             acc[u] = 0.f;
         }
-        for (int base = 0; base < nchunk; base += 4 * team) {
-            // Every load is issued unconditionally: a lane whose piece lies beyond the row reads the row's last piece
+        for (int base = 0; base < nchunk; base += SLOTS * team) {
+            // Loads carry no per-lane predicate: a lane whose piece lies beyond the row reads the row's last piece
             // instead (its neighbours read it anyway), a team without a row reads row 0, and what they fetched is
             // never used.  A load then costs one address addition instead of a predicate, a branch and four
             // register clears, which is what the instruction stream of this loop mostly consisted of.
-            int ch[4];
-            bool in_row[4];
+            int ch[SLOTS];
+            bool in_row[SLOTS];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < SLOTS; ++i) {
                 ch[i] = base + i * team + t;
                 in_row[i] = ch[i] < nchunk;
             }
-            uint4 x[RIF][4];
+            uint4 x[RIF][SLOTS];
 #pragma unroll
             for (int u = 0; u < RIF; ++u)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < SLOTS; ++i)
                     x[u][i] = *reinterpret_cast<const uint4 *>(row[u] + 16 * (in_row[i] ? ch[i] : nchunk - 1));
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < SLOTS; ++i) {
                 if (in_row[i]) {
 #pragma unroll
                     for (int h = 0; h < kPiece / 4; ++h) {
@@ -110,6 +110,22 @@ __device__ __forceinline__ void team_distances(const void *dataset, int64_t ld, 
             if (t == 0 && ok[u]) newdist[c0 + u * n_teams + g] = acc[u];
         }
     }
+}
+
+// SLOTS = 16-byte loads per lane and row in one sweep of a team over a row.  Four in general.  Byte rows are
+// often so short that a team's lanes have only two pieces each (128 bytes by a team of four): then two slots
+// issue no load that nobody needs.
+template <int ELEM, int RIF>
+__device__ __forceinline__ void team_distances(const void *dataset, int64_t ld, int dim, int metric, int team_log2,
+                                               const uint32_t *newid, int n_new, const float *qlds, float *newdist)
+{
+    if constexpr (ELEM == 2) {
+        if (dim / elems_per_piece<ELEM>() <= (2 << team_log2)) {
+            team_distances_impl<ELEM, RIF, 2>(dataset, ld, dim, metric, team_log2, newid, n_new, qlds, newdist);
+            return;
+        }
+    }
+    team_distances_impl<ELEM, RIF, 4>(dataset, ld, dim, metric, team_log2, newid, n_new, qlds, newdist);
 }
 
 }  // namespace cagra
