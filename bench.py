@@ -54,13 +54,14 @@ def algorithmic_bytes(stats: np.ndarray, dim: int, degree: int, k: int) -> dict:
 
 
 def kernel_sources_sha16() -> str:
-    """Hash of everything the search kernels are compiled from; a counter summary under profiles/
+    """Hash of the files the search kernels are compiled from; a counter summary under profiles/
     names the hash of the sources it was measured with."""
     import glob
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2308_15136_amd", "csrc")
-    for path in sorted(glob.glob(os.path.join(csrc, "search_*")) + glob.glob(os.path.join(csrc, "*.h"))):
+    names = ("search_kernels_impl.h", "search_device.h", "team_distance.h", "device_util.h", "search_params.h")
+    for path in sorted(glob.glob(os.path.join(csrc, "search_kernels_*.hip")) + [os.path.join(csrc, n) for n in names]):
         h.update(os.path.basename(path).encode())
         h.update(open(path, "rb").read())
     return h.hexdigest()[:16]

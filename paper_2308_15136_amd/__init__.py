@@ -161,11 +161,21 @@ def _dev_dataset(t):
     return t, kinds[t.dtype]
 
 
-def convert_dataset(dataset, dtype: int):
-    """fp32 dataset -> fp16 or uint8 copy (rounded to nearest even; uint8 clamped to 0..255)."""
+def convert_dataset(dataset, dtype: int, row_bytes_multiple: int = 0):
+    """fp32 dataset -> fp16 or uint8 copy (rounded to nearest even; uint8 clamped to 0..255), or an fp32 copy.
+    row_bytes_multiple: pad the row stride of the copy to a multiple of that many bytes (64: rows start on the
+    memory system's sector boundaries); the result is a view [N, dim] into the padded matrix."""
     torch = _torch()
     dataset = _dev_f32(dataset, "dataset")
-    out = torch.empty(dataset.shape, dtype={F16: torch.float16, U8: torch.uint8}[dtype], device=dataset.device)
+    tdt = {F32: torch.float32, F16: torch.float16, U8: torch.uint8}[dtype]
+    n, dim = dataset.shape
+    es = torch.empty(0, dtype=tdt).element_size()
+    ld = dim
+    if row_bytes_multiple:
+        if row_bytes_multiple % es:
+            raise ValueError("row_bytes_multiple must be a multiple of the element size")
+        ld = -(-dim * es // row_bytes_multiple) * row_bytes_multiple // es
+    out = torch.zeros((n, ld), dtype=tdt, device=dataset.device)[:, :dim]
     _check(load_library().cagra_convert_dataset(dataset.data_ptr(), dataset.shape[0], dataset.shape[1],
                                                 dataset.stride(0), dtype, out.data_ptr(), out.stride(0),
                                                 _stream(dataset.device)), "cagra_convert_dataset")

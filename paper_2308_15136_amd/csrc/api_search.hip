@@ -535,7 +535,7 @@ int cagra_convert_dataset(const float *src, int64_t N, int32_t dim, int64_t ld_s
                           void *dst, int64_t ld_dst, void *hip_stream)
 {
     if (!src || !dst) return CAGRA_ERR_NULL_POINTER;
-    if (dst_type != CAGRA_F16 && dst_type != CAGRA_U8) return CAGRA_ERR_BAD_OPTION;
+    if (dst_type != CAGRA_F32 && dst_type != CAGRA_F16 && dst_type != CAGRA_U8) return CAGRA_ERR_BAD_OPTION;
     if (N < 0 || N > 0x7FFFFFFFll || dim < 1 || ld_src < dim || ld_dst < dim) return CAGRA_ERR_BAD_SHAPE;
     if (N == 0) return CAGRA_OK;
     hipError_t e = launch_convert(src, N, dim, ld_src, (int)dst_type, dst, ld_dst, static_cast<hipStream_t>(hip_stream));

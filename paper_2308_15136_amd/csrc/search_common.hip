@@ -29,7 +29,7 @@ void launch_multi_init(const SearchParams &P, hipStream_t stream)
                        P.tables, words, P.done, P.which, P.B);
 }
 
-// fp32 -> fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255)
+// fp32 -> fp32 (another row stride), fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255)
 __global__ void convert_kernel(const float *__restrict__ src, int64_t rows, int dim, int64_t ld_src,
                                int elem, void *__restrict__ dst, int64_t ld_dst)
 {
@@ -38,7 +38,9 @@ __global__ void convert_kernel(const float *__restrict__ src, int64_t rows, int 
     const int64_t r = i / dim;
     const int c = (int)(i - r * dim);
     const float v = src[r * ld_src + c];
-    if (elem == 1) {
+    if (elem == 0) {
+        static_cast<float *>(dst)[r * ld_dst + c] = v;
+    } else if (elem == 1) {
         static_cast<__half *>(dst)[r * ld_dst + c] = __float2half_rn(v);
     } else {
         float t = rintf(v);
