@@ -55,7 +55,8 @@ def algorithmic_bytes(stats: np.ndarray, dim: int, degree: int, k: int) -> dict:
 
 def kernel_sources_sha16() -> str:
     """Hash of the files the search kernels are compiled from; a counter summary under profiles/
-    names the hash of the sources it was measured with."""
+    names the hash of the sources it was measured with.  Blocks under `#ifdef CAGRA_PHASE_CLOCKS`
+    (the phase timers, which the product build does not compile) are left out."""
     import glob
     import hashlib
     h = hashlib.sha256()
@@ -63,7 +64,15 @@ def kernel_sources_sha16() -> str:
     names = ("search_kernels_impl.h", "search_device.h", "team_distance.h", "device_util.h", "search_params.h")
     for path in sorted(glob.glob(os.path.join(csrc, "search_kernels_*.hip")) + [os.path.join(csrc, n) for n in names]):
         h.update(os.path.basename(path).encode())
-        h.update(open(path, "rb").read())
+        skip = False
+        for line in open(path, "rb").read().splitlines(keepends=True):
+            word = line.strip()
+            if word == b"#ifdef CAGRA_PHASE_CLOCKS":
+                skip = True
+            elif skip and word in (b"#else", b"#endif"):
+                skip = False
+            elif not skip:
+                h.update(line)
     return h.hexdigest()[:16]
 
 
@@ -125,6 +134,10 @@ def main() -> int:
     ap.add_argument("--no-scaling", action="store_true", help="skip the larger-batch runs")
     ap.add_argument("--no-storage", action="store_true", help="skip the fp16 / uint8 storage part")
     ap.add_argument("--no-reference", action="store_true", help="skip the stream / row-gather bandwidth references")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-query start / end times of one launch at the timed point, for 1, 2 and 4 wavefronts per query; "
+                         "needs a library built with -DCAGRA_PHASE_CLOCKS (python -m paper_2308_15136_amd.buildlib --define "
+                         "CAGRA_PHASE_CLOCKS --out <file>, then CAGRA_HIP_LIB=<file>)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference dispatch for rocprofv3 counters)")
     args = ap.parse_args()
@@ -694,6 +707,38 @@ def main() -> int:
                                       "max_rel_dist_err": rel,
                                       "oracle_recall": round(recall_at_k(o_ids, gt_np[:ns]), 5),
                                       "gpu_recall_same_sample": round(recall_at_k(gpu_ids[:ns], gt_np[:ns]), 5)}
+    if args.timeline:
+        import ctypes
+        lib = cagra.load_library()
+        if not hasattr(lib, "cagra_debug_query_times_f32"):
+            log("bench.py: --timeline needs a library built with -DCAGRA_PHASE_CLOCKS")
+            return 1
+        rows = []
+        for nw in (1, 2, 4):
+            o = cagra.SearchOptions(seed=opts.seed, mode=1, waves_per_query=nw)
+            for _ in range(3):
+                cagra.search(graph, base, queries, w.k, M, P_WIDTH, w.metric, o, out=(ids, dists), workspace=ws)
+            _, _, st_t = cagra.search(graph, base, queries, w.k, M, P_WIDTH, w.metric, o, out=(ids, dists), workspace=ws,
+                                      return_stats=True)
+            torch.cuda.synchronize()
+            buf = (ctypes.c_ulonglong * (2 * B))()
+            lib.cagra_debug_query_times_f32(buf, B)
+            t = np.array(list(buf), dtype=np.int64).reshape(B, 2)
+            t0 = t[:, 0].min()
+            s_us, e_us = (t[:, 0] - t0) / 100.0, (t[:, 1] - t0) / 100.0      # the wall clock counts at 100 MHz
+            total, dur = float(e_us.max()), e_us - s_us
+            edges = np.linspace(0.0, total, 21)
+            mids = (edges[:-1] + edges[1:]) / 2
+            rows.append({"waves_per_query": nw, "launch_us": round(total, 1), "last_query_started_us": round(float(s_us.max()), 1),
+                         "duration_us": {"mean": round(float(dur.mean()), 1), "p50": round(float(np.percentile(dur, 50)), 1),
+                                         "p99": round(float(np.percentile(dur, 99)), 1), "max": round(float(dur.max()), 1)},
+                         "passes_mean": round(float(st_t[:, 0].float().mean().item()), 2),
+                         "queries_in_flight_in_20_slices": [int(((s_us <= x) & (e_us > x)).sum()) for x in mids],
+                         "queries_finished_by_slice_end": [int((e_us <= x).sum()) for x in edges[1:]]})
+            log(f"[bench] timeline {nw} wavefront(s) per query: launch {total:.0f} us, last start {s_us.max():.0f} us, "
+                f"duration mean {dur.mean():.0f} p99 {np.percentile(dur, 99):.0f} max {dur.max():.0f} us")
+        out["timeline"] = {"note": "one launch at the timed point, phase-clock build (slower than the product build by the "
+                                   "time stamps); times in microseconds from the first query's start", "results": rows}
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read, 1 GiB written
         dst = torch.empty_like(src)

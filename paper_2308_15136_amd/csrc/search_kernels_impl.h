@@ -830,7 +830,13 @@ search_team_kernel(const SearchParams P)
         if (threadIdx.x == 0) team_words[2] = 0u;
         uint32_t thi[MR], tlo[MR];
         QueryStats qs;
+#ifdef CAGRA_PHASE_CLOCKS
+        if (threadIdx.x == 0 && qi < 131072u) g_query_times[2 * qi] = wall_clock64();
+#endif
         search_body_team<MR, NW>(P, qi, wave, table, team_words, qlds, newid, newdist, parents, pub_hi, pub_lo, thi, tlo, qs);
+#ifdef CAGRA_PHASE_CLOCKS
+        if (threadIdx.x == 0 && qi < 131072u) g_query_times[2 * qi + 1] = wall_clock64();
+#endif
         if (P.stats != nullptr && lane == 0) atomicAdd(team_words + 2, qs.n_dist);
         if (wave == 0) write_result<MR>(P, qi, thi, tlo);
         __syncthreads();
