@@ -13,9 +13,13 @@
  *     keeps no pointer after the call returns.  Scratch space is passed in as
  *     `workspace` (device, 256-byte aligned), sized by the matching
  *     *_workspace_bytes() function.
- *   - Matrices are row-major fp32; `ld` is the row stride in elements
- *     (ld >= dim).  dim and ld must be multiples of 4 and the base pointers
- *     16-byte aligned (rows are fetched with 16-byte loads, Sec. IV-B.1).
+ *   - Matrices are row-major fp32; `ld` is the row stride in elements.  Rows
+ *     are fetched with 16-byte loads (Sec. IV-B.1): base pointers must be
+ *     16-byte aligned, ld a multiple of 4 and at least dim rounded up to a
+ *     multiple of 4.  dim itself may be any positive number; where it is not
+ *     a multiple of 4 the floats of every row (dataset and queries alike)
+ *     between dim and that rounded width must be ZERO, which leaves both
+ *     distances unchanged.  cagra_convert_dataset writes rows of that form.
  *   - Graphs are row-major uint32 node ids, values < N, N <= 2^31 - 1
  *     (one bit of the index word carries the parent flag, Sec. IV-B.4).
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
@@ -120,8 +124,11 @@ typedef struct {
  * unexpanded or I_max passes were made; the first k of the top-M list are
  * written.  ids[B, k] / dists[B, k] come out ascending by (distance, id);
  * if fewer than k nodes were reached the tail is (CAGRA_INVALID_ID, FLT_MAX).
- * dim and ld (in elements) must be multiples of the elements in 16 bytes of the storage type
- * (4 for fp32, 8 for fp16, 16 for uint8).
+ * ld (in elements) must be a multiple of the elements in 16 bytes of the storage type (4 for fp32,
+ * 8 for fp16, 16 for uint8) and at least dim rounded up to such a multiple; where dim is not one,
+ * the elements of every DATASET row between dim and the rounded width must be zero (see
+ * cagra_convert_dataset).  Queries are fp32 rows of dim elements, ld_queries >= dim, no alignment
+ * or padding asked: the kernels pad their copy of the query.
  * Requirements: 1 <= k <= itopk; single mode: itopk <= 512, search_width <= 64 and
  * search_width * degree <= 2048 (beyond 256 candidates a pass takes them in chunks of 256, the
  * large-candidate-list case of Sec. IV-B.2); multi mode: see cagra_search_opts.
@@ -356,7 +363,9 @@ int cagra_count_components(const uint32_t *graph_host, int64_t N, int32_t degree
  * (a plain copy to another row stride).  src[N, dim] with stride ld_src, dst[N, dim] of dst_type with stride
  * ld_dst (both in elements).  The fp32 copy serves to pad rows: the search fetches whole rows at random and the
  * memory system fetches 64-byte sectors, so rows of 200 floats (800 bytes) cost 11 % more traffic than their bytes,
- * which a stride of 208 floats on a 64-byte aligned base avoids.  The padding beyond dim is not touched. */
+ * which a stride of 208 floats on a 64-byte aligned base avoids.  Every destination row is written in full:
+ * the elements from dim up to ld_dst are set to ZERO, the form the other entry points ask of rows whose dim is
+ * not a whole number of 16-byte pieces (e.g. 200 dimensions as bytes: ld_dst = 208). */
 int cagra_convert_dataset(const float *src, int64_t N, int32_t dim, int64_t ld_src, cagra_dtype dst_type,
                           void *dst, int64_t ld_dst, void *hip_stream);
 

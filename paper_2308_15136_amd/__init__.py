@@ -164,18 +164,19 @@ def _dev_dataset(t):
 def convert_dataset(dataset, dtype: int, row_bytes_multiple: int = 0):
     """fp32 dataset -> fp16 or uint8 copy (rounded to nearest even; uint8 clamped to 0..255), or an fp32 copy.
     row_bytes_multiple: pad the row stride of the copy to a multiple of that many bytes (64: rows start on the
-    memory system's sector boundaries); the result is a view [N, dim] into the padded matrix."""
+    memory system's sector boundaries; 0: to the next 16 bytes, the least the search accepts); the result is a
+    view [N, dim] into the padded matrix, whose padding the library has set to zero -- the form in which every
+    entry point takes rows whose dim is not a whole number of 16-byte pieces."""
     torch = _torch()
     dataset = _dev_f32(dataset, "dataset")
     tdt = {F32: torch.float32, F16: torch.float16, U8: torch.uint8}[dtype]
     n, dim = dataset.shape
     es = torch.empty(0, dtype=tdt).element_size()
-    ld = dim
-    if row_bytes_multiple:
-        if row_bytes_multiple % es:
-            raise ValueError("row_bytes_multiple must be a multiple of the element size")
-        ld = -(-dim * es // row_bytes_multiple) * row_bytes_multiple // es
-    out = torch.zeros((n, ld), dtype=tdt, device=dataset.device)[:, :dim]
+    row_bytes_multiple = row_bytes_multiple or 16
+    if row_bytes_multiple % 16:
+        raise ValueError("row_bytes_multiple must be a multiple of 16")
+    ld = -(-dim * es // row_bytes_multiple) * row_bytes_multiple // es
+    out = torch.empty((n, ld), dtype=tdt, device=dataset.device)[:, :dim]
     _check(load_library().cagra_convert_dataset(dataset.data_ptr(), dataset.shape[0], dataset.shape[1],
                                                 dataset.stride(0), dtype, out.data_ptr(), out.stride(0),
                                                 _stream(dataset.device)), "cagra_convert_dataset")

@@ -62,9 +62,13 @@ static int check_degrees(int64_t N, int32_t degree, int32_t init_degree)
     return CAGRA_OK;
 }
 
+// Rows are read in 16-byte pieces: a row is `dim` rounded up to a multiple of 4 floats wide, and the caller vouches that
+// the floats beyond `dim` are zero (they add nothing to either distance, in any summation order).
+static int32_t pad4(int32_t dim) { return (dim + 3) & ~3; }
+
 static int check_matrix(const float *p, int64_t rows, int32_t dim, int64_t ld)
 {
-    if (rows < 0 || rows > 0x7FFFFFFFll || dim < 4 || (dim & 3) || ld < dim || (ld & 3)) return CAGRA_ERR_BAD_SHAPE;
+    if (rows < 0 || rows > 0x7FFFFFFFll || dim < 1 || dim > 0x7FFFFFFF - 4 || ld < pad4(dim) || (ld & 3)) return CAGRA_ERR_BAD_SHAPE;
     if (((uintptr_t)p & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
     return CAGRA_OK;
 }
@@ -100,6 +104,7 @@ int cagra_exact_search(const float *dataset, int64_t N, int32_t dim, int64_t ld,
         workspace_bytes < cagra_exact_search_workspace_bytes(N, B, k))
         return CAGRA_ERR_WORKSPACE;
     if (B == 0) return CAGRA_OK;
+    dim = pad4(dim);
     hipError_t e = launch_exact_search(dataset, N, dim, ld, (int)metric, queries, B, ld_queries, k,
                                        exclude_self ? 1 : 0, self_offset, ids_out, dists_out,
                                        static_cast<float *>(workspace), exact_block_rows(N, B),
@@ -154,6 +159,7 @@ int cagra_exact_search_ex(const float *dataset, int64_t N, int32_t dim, int64_t 
     if (k < 1 || k > 512 || k > N) return CAGRA_ERR_BAD_TOPK;
     if (exclude_self && (self_offset < 0 || self_offset + B > N)) return CAGRA_ERR_BAD_SHAPE;
     if (B == 0) return CAGRA_OK;
+    dim = pad4(dim);
     const bool share = queries == dataset && ld_queries == ld && B <= N;
     const size_t plain = cagra_exact_search_workspace_bytes(N, B, k);
     const FilterPlan pl = plan_exact_filter(N, dim, B, k, share);
@@ -263,6 +269,7 @@ int cagra_build_ex(const float *dataset, int64_t N, int32_t dim, int64_t ld, cag
     if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
         workspace_bytes < cagra_build_ex_workspace_bytes(N, dim, degree, init_degree, &o))
         return CAGRA_ERR_WORKSPACE;
+    dim = pad4(dim);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const size_t knn_bytes = up256((size_t)N * init_degree * sizeof(uint32_t));
     uint32_t *knn = static_cast<uint32_t *>(workspace);

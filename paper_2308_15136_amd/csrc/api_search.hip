@@ -61,6 +61,7 @@ constexpr int kAutoSetTableEntries = CAGRA_AUTO_SET_TABLE;
 struct SinglePlan {
     int mr, cr, table_words, table_policy, reset_interval, team_log2, max_iterations;
     bool wide;   // more than 256 candidates per pass: taken in chunks of 256
+    bool short_rows;   // wide passes over fp32 rows of at most 384 bytes: the kernel variant with three wavefronts per SIMD
     int waves;   // wavefronts per query: 1, or a team of 2 or 4 sharing the visited table
     size_t smem;
     int off_query, off_newid, off_newdist, off_parents;
@@ -80,6 +81,7 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
     pl.mr = mr <= 1 ? 1 : mr <= 2 ? 2 : mr <= 4 ? 4 : 8;
     pl.cr = n_cand <= 64 ? 1 : n_cand <= 128 ? 2 : 4;
     pl.wide = n_cand > 256;
+    pl.short_rows = false;   // decided below, once the table management is known
 
     int team = o.team_size == 0 ? auto_team(pieces) : o.team_size;
     if (team != 4 && team != 8 && team != 16 && team != 32) return CAGRA_ERR_BAD_OPTION;
@@ -100,6 +102,7 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
     if (o.hash_bits < 0 || o.reset_interval < 0 || o.table_entries < 0) return CAGRA_ERR_BAD_OPTION;
     const bool reset = o.table_policy == 1 || (o.table_policy == 0 && (o.hash_bits != 0 || o.reset_interval != 0));
     if (!reset && (o.hash_bits != 0 || o.reset_interval != 0)) return CAGRA_ERR_BAD_OPTION;
+    pl.short_rows = pl.wide && !reset && o.dataset_type == CAGRA_F32 && dim * 4 <= 384 && pl.mr <= 2;
     int words;
     if (o.table_entries != 0) {
         if (o.hash_bits != 0 || o.table_entries < 256 || o.table_entries > 8192 || (o.table_entries & 63))
@@ -123,6 +126,11 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
         // wavefront per SIMD is (0.90 against 1.05 ms with byte rows at the benchmark's timed point), and with lists of
         // at most 128 entries the kernels leave registers for it.  2304 entries make the LDS fit twelve per CU.
         if (o.dataset_type != CAGRA_F32 && pl.mr <= 2 && n_cand > 128) words = 2304;
+        // With at most 64 candidates per pass their kernels are built for four wavefronts per SIMD (fp16 rows with lists
+        // up to 64 entries, byte rows up to 128); 2048 entries let sixteen workgroups share a CU's LDS.
+        if (o.dataset_type != CAGRA_F32 && n_cand <= 64 && pl.mr <= (o.dataset_type == CAGRA_F16 ? 1 : 2)) words = 2048;
+        // Wide passes over short fp32 rows: the kernel variant with three wavefronts per SIMD, twelve workgroups per CU.
+        if (pl.short_rows) words = 2304;
         // a long query (many dimensions) must not push the workgroup over an eighth of the CU's LDS: the
         // eighth wavefront is worth more than the last 512 table entries
         const size_t rest = (size_t)4 * ((dim + 3) & ~3) + (size_t)8 * 64 * pl.cr + 256;
@@ -319,9 +327,13 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
     if (!init_only && B > 0 && (!queries || !ids_out || !dists_out)) return CAGRA_ERR_NULL_POINTER;
     const int epp = elems_per_piece(o.dataset_type);
     if (epp == 0) return CAGRA_ERR_BAD_OPTION;
-    if (N < 1 || N > 0x7FFFFFFFll || dim < 4 || (dim % epp) || ld < dim || (ld % epp) || B < 0 ||
-        B > 0x7FFFFFFFll || ld_queries < dim)
+    if (N < 1 || N > 0x7FFFFFFFll || dim < 1 || dim > 0x7FFFFFFF - 16 || B < 0 || B > 0x7FFFFFFFll || ld_queries < dim)
         return CAGRA_ERR_BAD_SHAPE;
+    // The kernels read rows in 16-byte pieces: a row is `dim` rounded up to whole pieces, and the caller vouches that
+    // the elements beyond `dim` are zero (they then add nothing to either distance); the query is padded in LDS.
+    const int32_t dim_query = dim;
+    dim = (dim + epp - 1) / epp * epp;
+    if (ld < dim || (ld % epp)) return CAGRA_ERR_BAD_SHAPE;
     if (!init_only && ((uintptr_t)dataset & 15) != 0) return CAGRA_ERR_BAD_SHAPE;
     if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
     if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
@@ -335,7 +347,7 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
     P.graph = graph; P.dataset = dataset; P.queries = queries;
     P.ids_out = ids_out; P.dists_out = dists_out; P.stats = o.stats;
     P.N = N; P.B = B; P.ld = ld; P.ld_queries = ld_queries; P.seed = o.seed;
-    P.degree = degree; P.dim = dim; P.metric = (int)metric; P.k = k;
+    P.degree = degree; P.dim = dim; P.dim_query = dim_query; P.metric = (int)metric; P.k = k;
 
     if (mode == 2) {
         MultiPlan pl;
@@ -391,6 +403,7 @@ static int search_impl(const uint32_t *graph, int64_t N, int32_t degree, const v
     P.off_query = pl.off_query; P.off_newid = pl.off_newid;
     P.off_newdist = pl.off_newdist; P.off_parents = pl.off_parents;
     P.off_team = pl.off_team; P.off_pub = pl.off_pub; P.pub_cap = pl.pub_cap;
+    P.short_rows = pl.short_rows ? 1 : 0;
 
     const DeviceInfo &di = device_info();
     // persistent grid: as many workgroups as fit (LDS-bound, at most 16 wavefronts per CU)
@@ -461,7 +474,8 @@ int cagra_search_describe(int32_t degree, int32_t dim, int64_t B, int32_t k, int
     if (opts) o = *opts;
     if (!plan) return CAGRA_ERR_NULL_POINTER;
     if (elems_per_piece(o.dataset_type) == 0) return CAGRA_ERR_BAD_OPTION;
-    if (dim < 4 || (dim % elems_per_piece(o.dataset_type)) || B < 0) return CAGRA_ERR_BAD_SHAPE;
+    if (dim < 1 || dim > 0x7FFFFFFF - 16 || B < 0) return CAGRA_ERR_BAD_SHAPE;
+    dim = (dim + elems_per_piece(o.dataset_type) - 1) / elems_per_piece(o.dataset_type) * elems_per_piece(o.dataset_type);
     if (degree < 1 || degree > 256) return CAGRA_ERR_BAD_DEGREE;
     if (k < 1 || itopk < 1 || k > itopk || search_width < 1) return CAGRA_ERR_BAD_TOPK;
     if (o.mode < 0 || o.mode > 2) return CAGRA_ERR_BAD_OPTION;
@@ -516,7 +530,8 @@ int cagra_search_workspace_init(int64_t N, int32_t degree, int32_t dim, int64_t 
     o.workspace_clean = 0;
     const int epp = elems_per_piece(o.dataset_type);
     if (epp == 0) return CAGRA_ERR_BAD_OPTION;
-    return search_impl(nullptr, N, degree, nullptr, dim, dim, CAGRA_L2, nullptr, B, dim, k, itopk, search_width, o, nullptr,
+    const int64_t ld = dim < 1 ? 0 : ((int64_t)dim + epp - 1) / epp * epp;
+    return search_impl(nullptr, N, degree, nullptr, dim, ld, CAGRA_L2, nullptr, B, dim, k, itopk, search_width, o, nullptr,
                        nullptr, workspace, workspace_bytes, hip_stream, true);
 }
 

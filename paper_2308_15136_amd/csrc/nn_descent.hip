@@ -274,8 +274,9 @@ int cagra_nn_descent(const float *dataset, int64_t N, int32_t dim, int64_t ld, c
                      void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!dataset || !knn_out || !dists_out) return CAGRA_ERR_NULL_POINTER;
-    if (N < 2 || N > 0x7FFFFFFFll || dim < 4 || (dim & 3) || ld < dim || (ld & 3) || ((uintptr_t)dataset & 15))
+    if (N < 2 || N > 0x7FFFFFFFll || dim < 1 || dim > 0x7FFFFFFF - 4 || ld < ((dim + 3) & ~3) || (ld & 3) || ((uintptr_t)dataset & 15))
         return CAGRA_ERR_BAD_SHAPE;
+    dim = (dim + 3) & ~3;   // rows are read four floats at a time; the caller vouches for zeros beyond dim
     if (metric != CAGRA_L2 && metric != CAGRA_IP) return CAGRA_ERR_BAD_OPTION;
     if (k < 1 || k > 512 || k >= N) return CAGRA_ERR_BAD_DEGREE;
     if (rounds > 1000) return CAGRA_ERR_BAD_OPTION;

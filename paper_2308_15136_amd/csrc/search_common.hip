@@ -29,30 +29,33 @@ void launch_multi_init(const SearchParams &P, hipStream_t stream)
                        P.tables, words, P.done, P.which, P.B);
 }
 
-// fp32 -> fp32 (another row stride), fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255)
+// fp32 -> fp32 (another row stride), fp16 (round to nearest even) or uint8 (round to nearest even, clamped to 0..255).
+// Every destination row is written in full: the elements from `dim` to the row stride are set to zero, which is what
+// the search kernels ask of a row whose width is not a whole number of 16-byte pieces.
 __global__ void convert_kernel(const float *__restrict__ src, int64_t rows, int dim, int64_t ld_src,
                                int elem, void *__restrict__ dst, int64_t ld_dst)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= rows * dim) return;
-    const int64_t r = i / dim;
-    const int c = (int)(i - r * dim);
-    const float v = src[r * ld_src + c];
+    if (i >= rows * ld_dst) return;
+    const int64_t r = i / ld_dst;
+    const int64_t c = i - r * ld_dst;
+    const float v = c < dim ? src[r * ld_src + c] : 0.f;
     if (elem == 0) {
-        static_cast<float *>(dst)[r * ld_dst + c] = v;
+        static_cast<float *>(dst)[i] = v;
     } else if (elem == 1) {
-        static_cast<__half *>(dst)[r * ld_dst + c] = __float2half_rn(v);
+        static_cast<__half *>(dst)[i] = __float2half_rn(v);
     } else {
         float t = rintf(v);
         t = t < 0.f ? 0.f : (t > 255.f ? 255.f : t);
-        static_cast<unsigned char *>(dst)[r * ld_dst + c] = (unsigned char)t;
+        static_cast<unsigned char *>(dst)[i] = (unsigned char)t;
     }
 }
 
 hipError_t launch_convert(const float *src, int64_t rows, int dim, int64_t ld_src, int elem, void *dst,
                           int64_t ld_dst, hipStream_t stream)
 {
-    const int64_t n = rows * dim;
+    const int64_t n = rows * ld_dst;
+    if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(convert_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, src, rows, dim,
                        ld_src, elem, dst, ld_dst);
     return hipGetLastError();

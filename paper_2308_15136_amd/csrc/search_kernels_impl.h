@@ -72,19 +72,36 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 // (or, for fp16, gain nothing).
 // The same for the narrow kernel with 129 to 256 candidates per pass, whose larger table and candidate
 // buffers bind it to 8 wavefronts per CU as well.
+// Byte rows: three in flight; two where the kernel is built for four wavefronts per SIMD (see min_waves).
 #ifndef CAGRA_ROWS_IN_FLIGHT_U8
 #define CAGRA_ROWS_IN_FLIGHT_U8 3
 #endif
 #ifndef CAGRA_ROWS_IN_FLIGHT_MAX
 #define CAGRA_ROWS_IN_FLIGHT_MAX 8
 #endif
+#ifndef CAGRA_NARROW_4_MAX_MR
+#define CAGRA_NARROW_4_MAX_MR 2
+#endif
 template <int ELEM, int MR, int CR>
-constexpr int rows_in_flight_single() { return (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX : ELEM == 2 ? CAGRA_ROWS_IN_FLIGHT_U8 : kRowsInFlight; }
+constexpr bool narrow_small_pass() { return ELEM != 0 && CR == 1 && MR <= (ELEM == 1 ? 1 : CAGRA_NARROW_4_MAX_MR); }
+template <int ELEM, int MR, int CR>
+constexpr int rows_in_flight_single()
+{
+    return (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX
+         : ELEM == 2 ? (narrow_small_pass<ELEM, MR, CR>() ? 2 : CAGRA_ROWS_IN_FLIGHT_U8) : kRowsInFlight;
+}
 #ifndef CAGRA_WIDE_LONG_ROWS_MAX_MR
 #define CAGRA_WIDE_LONG_ROWS_MAX_MR 4
 #endif
-template <int ELEM, int MR>
-constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= CAGRA_WIDE_LONG_ROWS_MAX_MR) ? CAGRA_ROWS_IN_FLIGHT_MAX : ELEM == 2 ? CAGRA_ROWS_IN_FLIGHT_U8 : kRowsInFlight; }
+// SHORT: fp32 rows of at most 384 bytes with lists up to 128 entries.  There a third wavefront per SIMD is worth more
+// than rows in flight (1M x 96 workload, 512 candidates per pass: 1.14 ms against 1.21 ms), so that variant keeps
+// four rows in flight, which fits 168 registers.  Longer rows (512 and 800 bytes) measured the other way round.
+template <int ELEM, int MR, bool SHORT = false>
+constexpr int rows_in_flight_wide()
+{
+    return SHORT ? kRowsInFlight
+         : (ELEM == 0 && MR <= CAGRA_WIDE_LONG_ROWS_MAX_MR) ? CAGRA_ROWS_IN_FLIGHT_MAX : ELEM == 2 ? CAGRA_ROWS_IN_FLIGHT_U8 : kRowsInFlight;
+}
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
@@ -130,7 +147,7 @@ __device__ __forceinline__ void search_body(const SearchParams &P, uint32_t qi, 
 
     CAGRA_PHASE_BEGIN()
     const float *q = P.queries + (size_t)qi * P.ld_queries;
-    for (int j = lane; j < P.dim; j += kWave) qlds[j] = q[j];
+    for (int j = lane; j < P.dim; j += kWave) qlds[j] = j < P.dim_query ? q[j] : 0.f;
     if (!MULTI) {
         for (int j = 4 * lane; j < table_words; j += 4 * kWave)
             *reinterpret_cast<uint4 *>(table + j) = make_uint4(kInvalidId, kInvalidId, kInvalidId, kInvalidId);
@@ -374,7 +391,7 @@ __device__ __forceinline__ void search_body_wide(const SearchParams &P, uint32_t
 
     CAGRA_PHASE_BEGIN()
     const float *q = P.queries + (size_t)qi * P.ld_queries;
-    for (int j = lane; j < P.dim; j += kWave) qlds[j] = q[j];
+    for (int j = lane; j < P.dim; j += kWave) qlds[j] = j < P.dim_query ? q[j] : 0.f;
     for (int j = 4 * lane; j < table_words; j += 4 * kWave)
         *reinterpret_cast<uint4 *>(table + j) = make_uint4(kInvalidId, kInvalidId, kInvalidId, kInvalidId);
     if (KIND == kTableSets)
@@ -603,7 +620,7 @@ __device__ __forceinline__ void search_body_team(const SearchParams &P, uint32_t
     uint32_t *pub_count = team_words + 4;        // [4 .. 4 + 2 * NW)
 
     const float *q = P.queries + (size_t)qi * P.ld_queries;
-    for (int j = tid; j < P.dim; j += kWave * NW) qlds[j] = q[j];
+    for (int j = tid; j < P.dim; j += kWave * NW) qlds[j] = j < P.dim_query ? q[j] : 0.f;
     for (int j = 4 * tid; j < table_words; j += 4 * kWave * NW)
         *reinterpret_cast<uint4 *>(table + j) = make_uint4(kInvalidId, kInvalidId, kInvalidId, kInvalidId);
     for (int j = tid; j < (int)(sets + 3) / 4; j += kWave * NW) cursor[j] = 0u;
@@ -732,15 +749,22 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
 // Wavefronts per SIMD the compiler has to leave room for.  Two everywhere (256 registers; a few kernels would
 // otherwise take a handful more and drop to one).  Three (168 registers) for the narrow storage types with lists up
 // to CAGRA_NARROW_3_MAX_MR * 64 entries: their rows are short, the memory system is not what limits them, and a
-// third wavefront per SIMD is worth 12 to 15 % (measured on the 1M x 128 workload).
+// third wavefront per SIMD is worth 12 to 15 % (measured on the 1M x 128 workload); three as well for wide passes
+// over short fp32 rows (SHORT, see rows_in_flight_wide).  Four (128 registers) for the narrow types with at most 64
+// candidates per pass, where a pass is a short chain of dependent loads and little else (one parent per pass, itopk
+// 128, 1M x 128: byte rows 2.42 -> 2.09 ms, fp16 rows at itopk 64 1.51 -> 1.39 ms); fp16 only up to 64 entries,
+// beyond that its kernel would spill.
 #ifndef CAGRA_NARROW_3_MAX_MR
 #define CAGRA_NARROW_3_MAX_MR 2
 #endif
-template <int ELEM, int MR>
-constexpr int min_waves() { return (ELEM != 0 && MR <= CAGRA_NARROW_3_MAX_MR) ? 3 : 2; }
+template <int ELEM, int MR, int CR = 4, bool SHORT = false>
+constexpr int min_waves()
+{
+    return narrow_small_pass<ELEM, MR, CR>() ? 4 : ((ELEM != 0 && MR <= CAGRA_NARROW_3_MAX_MR) || SHORT) ? 3 : 2;
+}
 
 template <int ELEM, int MR, int CR, int KIND>
-__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR>()))
+__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR, CR>()))
 search_single_kernel(const SearchParams P)
 {
     CAGRA_LDS_VIEWS
@@ -771,8 +795,8 @@ search_single_kernel(const SearchParams P)
 }
 
 // Single mode with more than 256 candidates per pass (search_body_wide).
-template <int ELEM, int MR, int KIND>
-__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR>()))
+template <int ELEM, int MR, int KIND, bool SHORT = false>
+__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR, 4, SHORT>()))
 search_single_wide_kernel(const SearchParams P)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -792,7 +816,7 @@ search_single_wide_kernel(const SearchParams P)
 #ifdef CAGRA_PHASE_CLOCKS
         if (lane == 0 && qi < 131072u) g_query_times[2 * qi] = wall_clock64();
 #endif
-        search_body_wide<MR, KIND, rows_in_flight_wide<ELEM, MR>()>(P, qi, table, qlds, newid, newdist, parents, thi, tlo, qs);
+        search_body_wide<MR, KIND, rows_in_flight_wide<ELEM, MR, SHORT>()>(P, qi, table, qlds, newid, newdist, parents, thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
 #ifdef CAGRA_PHASE_CLOCKS
         if (lane == 0 && qi < 131072u) g_query_times[2 * qi + 1] = wall_clock64();
@@ -990,6 +1014,12 @@ template <int MR>
 static hipError_t launch_wide_one(const SearchParams &P, int grid, size_t smem, hipStream_t stream)
 {
     launch_zero_counter(P.counter, stream);
+    if constexpr (kElem == 0 && MR <= 2) {
+        if (P.short_rows && P.reset_interval == 0) {
+            hipLaunchKernelGGL((search_single_wide_kernel<kElem, MR, kTableSets, true>), dim3(grid), dim3(kWave), smem, stream, P);
+            return hipGetLastError();
+        }
+    }
     if (P.reset_interval > 0)
         hipLaunchKernelGGL((search_single_wide_kernel<kElem, MR, kTableReset>), dim3(grid), dim3(kWave), smem, stream, P);
     else

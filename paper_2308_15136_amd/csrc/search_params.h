@@ -22,7 +22,9 @@ struct SearchParams {
     uint32_t *notes;      // [B, workers, 8]: per worker its pass / parent / distance counts and flags
     int64_t N, B, ld, ld_queries;
     uint64_t seed;
-    int32_t degree, dim, metric;
+    int32_t degree, dim, metric;      // dim: row width the kernels work on, a whole number of 16-byte pieces
+    int32_t dim_query;                // elements a query really has (<= dim); the LDS copy is zero beyond them
+    int32_t short_rows;               // wide passes: the kernel built for three wavefronts per SIMD (rows up to 384 bytes)
     int32_t k, itopk, search_width;   // multi mode: itopk is the per-worker list length, width is 1
     int32_t workers;                  // multi mode: workgroups per query
     int32_t max_iterations, reset_interval, team_log2;

@@ -112,7 +112,7 @@ def test_build_rejections(cagra):
     with pytest.raises(cagra.CagraError):
         cagra.exact_search(b, b, 513)
     with pytest.raises(cagra.CagraError):
-        cagra.build(b[:, :30], 8, 16)          # dim not a multiple of 4
+        cagra.build(b[:, :30].contiguous(), 8, 16)          # a row stride that is not a multiple of 4 floats
 
 
 def test_exact_search_beyond_one_slice_of_dataset_rows(cagra):

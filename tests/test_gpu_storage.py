@@ -128,7 +128,7 @@ def test_narrow_storage_in_multi_mode_and_rejections(cagra):
     o_ids, _ = oracle.search_multi(g, w.base, w.queries, 10, 32, 4, w.metric, seed=11,
                                    max_iterations=oracle.auto_max_iterations(32, 1))
     assert abs(oracle.recall(ids_np, gt) - oracle.recall(o_ids, gt)) <= 0.01
-    # a row must be whole 16-byte pieces of the storage type: 200 bytes is not
+    # a row stride must be whole 16-byte pieces of the storage type: 200 bytes is not (208 with zeros would be)
     wg, gg, _ = _setup("glove200", 20_000, 300, 64)
     gb = torch.from_numpy(wg.base).cuda()
     bad = torch.zeros(gb.shape, dtype=torch.uint8, device="cuda")
