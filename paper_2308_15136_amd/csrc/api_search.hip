@@ -53,6 +53,9 @@ static int elems_per_piece(int dataset_type)
     return dataset_type == CAGRA_F32 ? 4 : dataset_type == CAGRA_F16 ? 8 : dataset_type == CAGRA_U8 ? 16 : 0;
 }
 
+#ifndef CAGRA_SHORT_MAX_ROW_BYTES
+#define CAGRA_SHORT_MAX_ROW_BYTES 384
+#endif
 #ifndef CAGRA_AUTO_SET_TABLE
 #define CAGRA_AUTO_SET_TABLE 2560
 #endif
@@ -61,7 +64,7 @@ constexpr int kAutoSetTableEntries = CAGRA_AUTO_SET_TABLE;
 struct SinglePlan {
     int mr, cr, table_words, table_policy, reset_interval, team_log2, max_iterations;
     bool wide;   // more than 256 candidates per pass: taken in chunks of 256
-    bool short_rows;   // wide passes over fp32 rows of at most 384 bytes: the kernel variant with three wavefronts per SIMD
+    bool short_rows;   // fp32 rows of at most 384 bytes, up to 64 or 129 to 256 candidates per pass: the kernel variants with one more wavefront per SIMD
     int waves;   // wavefronts per query: 1, or a team of 2 or 4 sharing the visited table
     size_t smem;
     int off_query, off_newid, off_newdist, off_parents;
@@ -102,7 +105,7 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
     if (o.hash_bits < 0 || o.reset_interval < 0 || o.table_entries < 0) return CAGRA_ERR_BAD_OPTION;
     const bool reset = o.table_policy == 1 || (o.table_policy == 0 && (o.hash_bits != 0 || o.reset_interval != 0));
     if (!reset && (o.hash_bits != 0 || o.reset_interval != 0)) return CAGRA_ERR_BAD_OPTION;
-    pl.short_rows = pl.wide && !reset && o.dataset_type == CAGRA_F32 && dim * 4 <= 384 && pl.mr <= 2;
+    pl.short_rows = (n_cand <= 64 || (n_cand > 128 && !pl.wide)) && !reset && o.dataset_type == CAGRA_F32 && dim * 4 <= CAGRA_SHORT_MAX_ROW_BYTES && pl.mr <= 2;
     int words;
     if (o.table_entries != 0) {
         if (o.hash_bits != 0 || o.table_entries < 256 || o.table_entries > 8192 || (o.table_entries & 63))
@@ -129,8 +132,9 @@ static int plan_single(int degree, int dim, int64_t B, int itopk, int width, con
         // With at most 64 candidates per pass their kernels are built for four wavefronts per SIMD (fp16 rows with lists
         // up to 64 entries, byte rows up to 128); 2048 entries let sixteen workgroups share a CU's LDS.
         if (o.dataset_type != CAGRA_F32 && n_cand <= 64 && pl.mr <= (o.dataset_type == CAGRA_F16 ? 1 : 2)) words = 2048;
-        // Wide passes over short fp32 rows: the kernel variant with three wavefronts per SIMD, twelve workgroups per CU.
-        if (pl.short_rows) words = 2304;
+        // Short fp32 rows: the kernel variants with one more wavefront per SIMD; twelve workgroups per CU with 129 to 256
+        // candidates per pass, sixteen with at most 64.
+        if (pl.short_rows) words = n_cand <= 64 ? 2048 : 2304;
         // a long query (many dimensions) must not push the workgroup over an eighth of the CU's LDS: the
         // eighth wavefront is worth more than the last 512 table entries
         const size_t rest = (size_t)4 * ((dim + 3) & ~3) + (size_t)8 * 64 * pl.cr + 256;

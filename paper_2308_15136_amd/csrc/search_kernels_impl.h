@@ -79,29 +79,31 @@ constexpr int kRowsInFlightMulti = 8;   // multi mode: latency matters, register
 #ifndef CAGRA_ROWS_IN_FLIGHT_MAX
 #define CAGRA_ROWS_IN_FLIGHT_MAX 8
 #endif
+// SHORT: variants for fp32 rows of at most 384 bytes with lists up to 128 entries, where one more wavefront per SIMD is
+// worth more than rows in flight (measured on the 1M x 96 workload; rows of 512 and 800 bytes measured the other way
+// round, and so did wide passes in chunks of 256).
+//  - 129 to 256 candidates per pass: three wavefronts per SIMD, four rows in flight, which fits 168 registers
+//    (256 candidates, list of 64: 1.24 -> 1.16 ms; list of 128: 1.69 -> 1.49 ms);
+//  - up to 64 candidates per pass: four wavefronts per SIMD, three rows in flight, 128 registers
+//    (64 candidates, list of 128: 1.49 -> 1.30 ms; 32 candidates: 2.33 -> 1.99 ms).
+constexpr int short_rows_in_flight(int cr) { return cr == 1 ? 3 : 4; }
+constexpr int short_waves(int cr) { return cr == 1 ? 4 : 3; }
 #ifndef CAGRA_NARROW_4_MAX_MR
 #define CAGRA_NARROW_4_MAX_MR 2
 #endif
 template <int ELEM, int MR, int CR>
 constexpr bool narrow_small_pass() { return ELEM != 0 && CR == 1 && MR <= (ELEM == 1 ? 1 : CAGRA_NARROW_4_MAX_MR); }
-template <int ELEM, int MR, int CR>
+template <int ELEM, int MR, int CR, bool SHORT = false>
 constexpr int rows_in_flight_single()
 {
-    return (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX
+    return SHORT ? short_rows_in_flight(CR) : (ELEM == 0 && MR <= 2 && CR == 4) ? CAGRA_ROWS_IN_FLIGHT_MAX
          : ELEM == 2 ? (narrow_small_pass<ELEM, MR, CR>() ? 2 : CAGRA_ROWS_IN_FLIGHT_U8) : kRowsInFlight;
 }
 #ifndef CAGRA_WIDE_LONG_ROWS_MAX_MR
 #define CAGRA_WIDE_LONG_ROWS_MAX_MR 4
 #endif
-// SHORT: fp32 rows of at most 384 bytes with lists up to 128 entries.  There a third wavefront per SIMD is worth more
-// than rows in flight (1M x 96 workload, 512 candidates per pass: 1.14 ms against 1.21 ms), so that variant keeps
-// four rows in flight, which fits 168 registers.  Longer rows (512 and 800 bytes) measured the other way round.
-template <int ELEM, int MR, bool SHORT = false>
-constexpr int rows_in_flight_wide()
-{
-    return SHORT ? kRowsInFlight
-         : (ELEM == 0 && MR <= CAGRA_WIDE_LONG_ROWS_MAX_MR) ? CAGRA_ROWS_IN_FLIGHT_MAX : ELEM == 2 ? CAGRA_ROWS_IN_FLIGHT_U8 : kRowsInFlight;
-}
+template <int ELEM, int MR>
+constexpr int rows_in_flight_wide() { return (ELEM == 0 && MR <= CAGRA_WIDE_LONG_ROWS_MAX_MR) ? CAGRA_ROWS_IN_FLIGHT_MAX : ELEM == 2 ? CAGRA_ROWS_IN_FLIGHT_U8 : kRowsInFlight; }
 
 // Optional phase timers (compile with -DCAGRA_PHASE_CLOCKS): shader-clock cycles that lane 0 of
 // every wavefront spends in each part of the loop, summed over the launch into a device array
@@ -749,8 +751,8 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
 // Wavefronts per SIMD the compiler has to leave room for.  Two everywhere (256 registers; a few kernels would
 // otherwise take a handful more and drop to one).  Three (168 registers) for the narrow storage types with lists up
 // to CAGRA_NARROW_3_MAX_MR * 64 entries: their rows are short, the memory system is not what limits them, and a
-// third wavefront per SIMD is worth 12 to 15 % (measured on the 1M x 128 workload); three as well for wide passes
-// over short fp32 rows (SHORT, see rows_in_flight_wide).  Four (128 registers) for the narrow types with at most 64
+// third wavefront per SIMD is worth 12 to 15 % (measured on the 1M x 128 workload); three as well for the SHORT
+// variant (see rows_in_flight_single).  Four (128 registers) for the narrow types with at most 64
 // candidates per pass, where a pass is a short chain of dependent loads and little else (one parent per pass, itopk
 // 128, 1M x 128: byte rows 2.42 -> 2.09 ms, fp16 rows at itopk 64 1.51 -> 1.39 ms); fp16 only up to 64 entries,
 // beyond that its kernel would spill.
@@ -760,11 +762,11 @@ __device__ __forceinline__ void write_result(const SearchParams &P, uint32_t qi,
 template <int ELEM, int MR, int CR = 4, bool SHORT = false>
 constexpr int min_waves()
 {
-    return narrow_small_pass<ELEM, MR, CR>() ? 4 : ((ELEM != 0 && MR <= CAGRA_NARROW_3_MAX_MR) || SHORT) ? 3 : 2;
+    return narrow_small_pass<ELEM, MR, CR>() ? 4 : SHORT ? short_waves(CR) : (ELEM != 0 && MR <= CAGRA_NARROW_3_MAX_MR) ? 3 : 2;
 }
 
-template <int ELEM, int MR, int CR, int KIND>
-__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR, CR>()))
+template <int ELEM, int MR, int CR, int KIND, bool SHORT = false>
+__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR, CR, SHORT>()))
 search_single_kernel(const SearchParams P)
 {
     CAGRA_LDS_VIEWS
@@ -780,7 +782,7 @@ search_single_kernel(const SearchParams P)
 #ifdef CAGRA_PHASE_CLOCKS
         if (lane == 0 && qi < 131072u) g_query_times[2 * qi] = wall_clock64();
 #endif
-        search_body<MR, CR, KIND, rows_in_flight_single<ELEM, MR, CR>()>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
+        search_body<MR, CR, KIND, rows_in_flight_single<ELEM, MR, CR, SHORT>()>(P, qi, 0, table, qlds, newid, newdist, parents, slot_parent, slot_nbr,
                                    thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
 #ifdef CAGRA_PHASE_CLOCKS
@@ -795,8 +797,8 @@ search_single_kernel(const SearchParams P)
 }
 
 // Single mode with more than 256 candidates per pass (search_body_wide).
-template <int ELEM, int MR, int KIND, bool SHORT = false>
-__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR, 4, SHORT>()))
+template <int ELEM, int MR, int KIND>
+__global__ void __launch_bounds__(kWave, (min_waves<ELEM, MR>()))
 search_single_wide_kernel(const SearchParams P)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -816,7 +818,7 @@ search_single_wide_kernel(const SearchParams P)
 #ifdef CAGRA_PHASE_CLOCKS
         if (lane == 0 && qi < 131072u) g_query_times[2 * qi] = wall_clock64();
 #endif
-        search_body_wide<MR, KIND, rows_in_flight_wide<ELEM, MR, SHORT>()>(P, qi, table, qlds, newid, newdist, parents, thi, tlo, qs);
+        search_body_wide<MR, KIND, rows_in_flight_wide<ELEM, MR>()>(P, qi, table, qlds, newid, newdist, parents, thi, tlo, qs);
         write_result<MR>(P, qi, thi, tlo);
 #ifdef CAGRA_PHASE_CLOCKS
         if (lane == 0 && qi < 131072u) g_query_times[2 * qi + 1] = wall_clock64();
@@ -1003,6 +1005,12 @@ template <int MR, int CR>
 static hipError_t launch_single_one(const SearchParams &P, int grid, size_t smem, hipStream_t stream)
 {
     launch_zero_counter(P.counter, stream);
+    if constexpr (kElem == 0 && MR <= 2 && CR != 2) {
+        if (P.short_rows && P.reset_interval == 0) {
+            hipLaunchKernelGGL((search_single_kernel<kElem, MR, CR, kTableSets, true>), dim3(grid), dim3(kWave), smem, stream, P);
+            return hipGetLastError();
+        }
+    }
     if (P.reset_interval > 0)
         hipLaunchKernelGGL((search_single_kernel<kElem, MR, CR, kTableReset>), dim3(grid), dim3(kWave), smem, stream, P);
     else
@@ -1014,12 +1022,6 @@ template <int MR>
 static hipError_t launch_wide_one(const SearchParams &P, int grid, size_t smem, hipStream_t stream)
 {
     launch_zero_counter(P.counter, stream);
-    if constexpr (kElem == 0 && MR <= 2) {
-        if (P.short_rows && P.reset_interval == 0) {
-            hipLaunchKernelGGL((search_single_wide_kernel<kElem, MR, kTableSets, true>), dim3(grid), dim3(kWave), smem, stream, P);
-            return hipGetLastError();
-        }
-    }
     if (P.reset_interval > 0)
         hipLaunchKernelGGL((search_single_wide_kernel<kElem, MR, kTableReset>), dim3(grid), dim3(kWave), smem, stream, P);
     else

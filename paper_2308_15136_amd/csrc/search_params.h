@@ -24,7 +24,7 @@ struct SearchParams {
     uint64_t seed;
     int32_t degree, dim, metric;      // dim: row width the kernels work on, a whole number of 16-byte pieces
     int32_t dim_query;                // elements a query really has (<= dim); the LDS copy is zero beyond them
-    int32_t short_rows;               // wide passes: the kernel built for three wavefronts per SIMD (rows up to 384 bytes)
+    int32_t short_rows;               // fp32 rows up to 384 bytes, up to 64 or 129 to 256 candidates per pass: the kernels built for one more wavefront per SIMD
     int32_t k, itopk, search_width;   // multi mode: itopk is the per-worker list length, width is 1
     int32_t workers;                  // multi mode: workgroups per query
     int32_t max_iterations, reset_interval, team_log2;
