@@ -24,11 +24,12 @@
 // Bound used for eps (u = 2^-24; x~, q~ the fp16 copies; g = |x| |q|, S = |x|^2 + |q|^2):
 //   fp16 rounding of both operands: |x~.q~ - x.q| <= (2^-10 + 2^-22) sum|x_i q_i| <= 2^-10 * 1.001 * g
 //   (scaled values below the fp16 normal range add at most dim * 2^-38 * g);
-//   fp32 accumulation inside the MFMA (rounded or truncated), of the norms, the final additions, and the
-//   rounding of the exact chain itself: together <= (5 dim + 9) u S for squared L2, <= (3 dim + 4) u g for
-//   the inner product.
-//   squared L2 (the product enters twice):  eps = 2 * 1.01 * 2^-10 * g + (8 dim + 32) u * S
-//   inner product:                          eps = 2 * (1.01 * 2^-10 + (8 dim + 32) u) * g   (twice what is needed)
+//   fp32 accumulation inside the MFMA (rounded or truncated; the accumulators start at minus the right-hand
+//   side of the test, see mfma_tile_kernel, so a partial sum can be as large as S resp. 2 g in scaled units),
+//   of the norms, the start value, the final additions, and the rounding of the exact chain itself: together
+//   <= (8.1 dim + 12) u S for squared L2, <= (5.1 dim + 6) u g for the inner product.
+//   squared L2 (the product enters twice):  eps = 2 * 1.01 * 2^-10 * g + (12 dim + 48) u * S
+//   inner product:                          eps = 2 * (1.01 * 2^-10 + (12 dim + 48) u) * g   (more than twice what is needed)
 // g rather than S in the leading term keeps the filter sharp when queries and dataset rows differ
 // much in norm.
 #include <algorithm>
@@ -136,10 +137,11 @@ struct FilterParams {
     int64_t self_offset;
 };
 
-// One workgroup: a tile of 128 query rows against a strip of kStrip tiles of 128 columns.  The
-// operands travel global -> registers -> LDS in steps of 64 dimensions; the loads of the next step are
-// issued before the matrix instructions of the current one.  Four wavefronts, 64 x 64 outputs each
-// (2 x 2 blocks of v_mfma_f32_32x32x16_f16).
+// One workgroup: a tile of 128 query rows against a strip of kStrip tiles of 128 columns.  Four wavefronts,
+// 64 x 64 outputs each (2 x 2 blocks of v_mfma_f32_32x32x16_f16).  The operands travel global -> registers -> LDS
+// in steps of 64 dimensions; the loads of the next step are issued before the matrix instructions of the current
+// one.  (Keeping the query rows in LDS for the whole strip and fetching the dataset rows two steps ahead was tried
+// and is slower: 1.03 against 0.84 ms per block of 2,048 x 1M x 128.)
 //
 // Filter test without forming the distance: with inv = 1 / (scale_q scale_x) and acc the raw product,
 //   squared L2:     |q|^2 + |x|^2 - 2 acc inv <= thr + 2 c16 |q||x| + c32 (|q|^2 + |x|^2)
@@ -148,15 +150,35 @@ struct FilterParams {
 //   inner product:  -acc inv <= thr + 2 (c16 + c32) |q||x|
 //              <=>  acc >= Rr[row] - Xr[row] |x|,   Rr = -thr / inv,  Xr = 2 (c16 + c32) |q| / inv
 // (c32 leaves room for the few roundings of this rearrangement.)
+// The filter instance does not even form the right-hand side at the end: the accumulators of a tile START at
+// minus that value (one add and one fused multiply-add per output, which also spares clearing them), the matrix
+// instructions add the product, and what is left to test is the sign: one compare per output whose lane mask
+// lands in scalar registers, and a branch around everything else where no lane passed -- about one output in a
+// thousand does.  A column that does not exist starts at minus infinity.
+// The outputs that pass are not appended to their rows' candidate buffers one by one: an append is an atomic on device
+// memory whose answer the wavefront would await (a few microseconds, longer than the matrix instructions of a whole
+// tile, with its three companions waiting at the next barrier).  Each wavefront notes (row, id) in a list of its own in
+// LDS -- positions from a count it keeps in a register, no atomics -- and empties the list into the buffers at the end
+// of its strip of tiles, all lanes at once: one round trip for some thirty candidates.  A list that fills up is
+// emptied early.
+constexpr int kHitCap = 256;      // entries of a wavefront's list (about 33 are expected per strip)
+constexpr size_t kFilterSmem = 1024 + (size_t)2 * kFT * kFRow * 2 + (size_t)4 * kHitCap * 8 + (size_t)kStrip * kFT * 4;
+
 template <bool DENSE>
-__global__ void __launch_bounds__(256, 2)     // two wavefronts per SIMD: two workgroups per CU
+__global__ void __launch_bounds__(256, 2)     // at least two wavefronts per SIMD: two workgroups per CU
 mfma_tile_kernel(const FilterParams P)
 {
-    __shared__ __align__(16) _Float16 As[kFT * kFRow];
-    __shared__ __align__(16) _Float16 Xs[kFT * kFRow];
-    __shared__ float2 s_row[kFT];     // filter: (Rr, Xr); dense: (|q|^2, unused)
+    extern __shared__ __align__(16) unsigned char f_smem[];
+    float2 *s_row = reinterpret_cast<float2 *>(f_smem);     // [kFT]  filter: (Rr, Xr); dense: (|q|^2, unused)
+    _Float16 *Xs = reinterpret_cast<_Float16 *>(f_smem + 1024);          // [kFT][kFRow]
+    _Float16 *As = Xs + kFT * kFRow;                                       // [kFT][kFRow]
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
+    uint2 *hit_list = reinterpret_cast<uint2 *>(As + kFT * kFRow) + wave * kHitCap;   // this wavefront's (row, id) notes
+    // squared norms of the strip's columns, +inf for a column that does not exist: fetched once, so that no tile has to
+    // wait for device memory (a wait for one load is a wait for every load issued before it, the staged pieces included)
+    float *nx_s = reinterpret_cast<float *>(reinterpret_cast<uint2 *>(As + kFT * kFRow) + 4 * kHitCap);   // [kStrip * kFT]
+    int n_listed = 0;                                                                    // the same in every lane
     // Workgroups are handed to the eight XCDs in turn, and each XCD has its own L2: the row tiles of
     // one column strip are numbered so that they all run on the same XCD, one after the other, and
     // the strip is fetched from memory once instead of once per row tile.
@@ -168,6 +190,7 @@ mfma_tile_kernel(const FilterParams P)
     const int m0 = (wave >> 1) * 64, n0 = (wave & 1) * 64;
     const float inv = 1.0f / (scale_of(*P.q_maxbits) * scale_of(*P.x_maxbits));   // powers of two: exact
     const float half_inv = 0.5f / inv;
+    const float inf = __uint_as_float(0x7F800000u);
 
     if (tid < kFT) {
         const int64_t grow = P.q_row0 + tile_r + tid;
@@ -182,6 +205,11 @@ mfma_tile_kernel(const FilterParams P)
                                        : make_float2((0.0f - thr) / inv, 2.0f * (P.c16 + P.c32) * sq / inv);
         }
     }
+    for (int i = tid; i < kStrip * kFT; i += 256) {
+        const int64_t col = strip_c + i;
+        nx_s[i] = col < P.n_cols ? P.nx[col * P.col_step] : inf;
+    }
+    __syncthreads();
 
     // staging: 1024 16-byte pieces per operand and step, four per thread
     const int n_chunks = (P.dimP + kFK - 1) / kFK;       // dimP is a multiple of 32: the last step may be half a step
@@ -191,58 +219,95 @@ mfma_tile_kernel(const FilterParams P)
     const int total = (int)n_tiles * n_chunks;
     int dst[4];
     const _Float16 *src_a[4];
-    bool ok_a[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int p = tid + 256 * u;
         const int row = p >> 3, part = p & 7;
         const int64_t grow = P.q_row0 + tile_r + row;
-        ok_a[u] = grow < P.q_rows;
-        src_a[u] = P.Q16 + (ok_a[u] ? grow : 0) * P.dimP + part * 8;
+        src_a[u] = P.Q16 + (grow < P.q_rows ? grow : P.q_rows - 1) * P.dimP;
         dst[u] = row * kFRow + part * 8;
     }
-    // the 16-byte pieces this thread stages in one step: piece tid + 256 u of the 128 x 64 block of each operand
-    u32x4_t va[4], vx[4];
-#define CAGRA_FETCH_ONE(U)                                                                                       \
-    {                                                                                                            \
-        const int f_row = (tid + 256 * U) >> 3, f_part = (tid + 256 * U) & 7;                                    \
-        const int64_t f_col = strip_c + (int64_t)f_tile * kFT + f_row;                                           \
-        const bool f_in = f_part * 8 + f_k0 < P.dimP;                                                            \
-        va[U] = ok_a[U] && f_in ? *reinterpret_cast<const u32x4_t *>(src_a[U] + f_k0) : zero4;                   \
-        vx[U] = f_col < P.n_cols && f_in                                                                         \
-                    ? *reinterpret_cast<const u32x4_t *>(P.X16 + f_col * P.col_step * P.dimP + f_part * 8 + f_k0) \
-                    : zero4;                                                                                     \
-    }
-#define CAGRA_FETCH_STEP(STEP)                                                                                   \
-    {                                                                                                            \
-        const int f_step = (STEP);                                                                               \
-        const int f_tile = f_step / n_chunks, f_k0 = (f_step - f_tile * n_chunks) * kFK;                         \
-        CAGRA_FETCH_ONE(0) CAGRA_FETCH_ONE(1) CAGRA_FETCH_ONE(2) CAGRA_FETCH_ONE(3)                              \
-    }
-    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+    // The 16-byte pieces this thread stages in one step: piece tid + 256 u of the 128 x 64 block of each operand.  The
+    // loads carry no predicate: a row or column that does not exist reads the last one that does, a piece beyond the
+    // row's dimensions reads the row's last piece, and none of that is ever used (the outputs of such rows and columns
+    // are ignored, the matrix instructions stop at the row's dimensions).
+    const int64_t last_col = P.n_cols - 1;
+    auto fetch = [&](int f_step, u32x4_t (&xa)[4], u32x4_t (&xx)[4]) __attribute__((always_inline)) {
+        const int f_tile = f_step / n_chunks, f_k0 = (f_step - f_tile * n_chunks) * kFK;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int f_row = (tid + 256 * u) >> 3, f_part = (tid + 256 * u) & 7;
+            int64_t f_col = strip_c + (int64_t)f_tile * kFT + f_row;
+            f_col = f_col < last_col ? f_col : last_col;
+            int f_k = f_part * 8 + f_k0;
+            f_k = f_k < P.dimP ? f_k : P.dimP - 8;
+            xa[u] = *reinterpret_cast<const u32x4_t *>(src_a[u] + f_k);
+            xx[u] = *reinterpret_cast<const u32x4_t *>(P.X16 + f_col * P.col_step * P.dimP + f_k);
+        }
+    };
     floatx16_t acc[2][2];
+    // Start values of a tile's accumulators: minus the right-hand side of the test (filter), zero (dense).
+    auto start_tile = [&](int tile) __attribute__((always_inline)) {
+        // (the 32 row constants of a lane are read anew for every tile: kept in registers they would cost 64 of them,
+        // which is what the compiler does unless the address is opaque to it)
+        int row_base = m0 + 4 * (lane >> 5);
+        if (!DENSE) asm volatile("" : "+v"(row_base));
+        float sx[2], cn[2];
+        bool col_ok[2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int nb = 0; nb < 2; ++nb) {
+            const float nxv = DENSE ? 0.f : nx_s[tile * kFT + n0 + nb * 32 + (lane & 31)];   // this lane's column of each 32-wide block
+            // a column that does not exist: cn = +inf, so that its outputs start at minus infinity and stay there
+            col_ok[nb] = nxv != inf;
+            sx[nb] = sqrtf(col_ok[nb] ? nxv : 0.f);
+            cn[nb] = !col_ok[nb] ? inf : P.metric == 0 ? nxv * (1.0f - P.c32) * half_inv : 0.f;
+        }
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int ma = 0; ma < 2; ++ma)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    CAGRA_FETCH_STEP(0)
-    const float inf = __uint_as_float(0x7F800000u);
+            for (int r = 0; r < 16; ++r) {
+                if (DENSE) {
+                    acc[ma][0][r] = 0.f;
+                    acc[ma][1][r] = 0.f;
+                } else {
+                    const float2 rc = s_row[row_base + ma * 32 + 8 * (r >> 2) + (r & 3)];
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        acc[ma][nb][r] = fmaf(rc.y, sx[nb], 0.0f - (rc.x + cn[nb]));
+                }
+            }
+    };
     // operand layout of v_mfma_f32_32x32x16_f16: lane l holds row (l % 32), k = 8 * (l / 32) .. + 7
     const int fr = lane & 31, fk = (lane >> 5) * 8;
-    for (int step = 0; step < total; ++step) {
+
+    // Empties this wavefront's list into the rows' candidate buffers.
+    auto flush_hits = [&]() __attribute__((always_inline)) {
+        wave_sync();                                     // the notes of all lanes are in LDS
+        const int n = n_listed < kHitCap ? n_listed : kHitCap;
+        for (int i = lane; i < n; i += 64) {
+            const uint2 e = hit_list[i];
+            const uint32_t at = atomicAdd(&P.count[e.x], 1u);
+            if (at < (uint32_t)kCap) P.buf[(int64_t)e.x * kCap + at] = e.y;
+        }
+        wave_sync();                                     // read before the next notes overwrite them
+        n_listed = 0;
+    };
+
+    // One step: the staged pieces go to LDS, the loads of a later step are issued into the registers they
+    // leave, the matrix instructions of this step run, and a tile that is complete is tested (or written).
+    auto do_step = [&](int step, u32x4_t (&xa)[4], u32x4_t (&xx)[4]) __attribute__((always_inline)) {
         __syncthreads();                       // the previous step's fragments have been read
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            *reinterpret_cast<u32x4_t *>(&As[dst[u]]) = va[u];
-            *reinterpret_cast<u32x4_t *>(&Xs[dst[u]]) = vx[u];
+            *reinterpret_cast<u32x4_t *>(&As[dst[u]]) = xa[u];
+            *reinterpret_cast<u32x4_t *>(&Xs[dst[u]]) = xx[u];
         }
         __syncthreads();
-        // (the last step fetches itself once more rather than branch around the loads)
-        CAGRA_FETCH_STEP(step + 1 < total ? step + 1 : step)
-        const int k0 = (step % n_chunks) * kFK;
+        // (a step without successor fetches itself once more rather than branch around the loads)
+        fetch(step + 1 < total ? step + 1 : step, xa, xx);
+        const int tile = step / n_chunks;
+        const int chunk = step - tile * n_chunks;
+        const int k0 = chunk * kFK;
 #pragma unroll
         for (int ks = 0; ks < kFK / 16; ++ks) {
             if (k0 + ks * 16 >= P.dimP) break;          // the half step: its second half holds zeros
@@ -258,59 +323,90 @@ mfma_tile_kernel(const FilterParams P)
                 for (int nb = 0; nb < 2; ++nb)
                     acc[ma][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ma], b[nb], acc[ma][nb], 0, 0, 0);
         }
-        const int tile = step / n_chunks;
-        if (step - tile * n_chunks != n_chunks - 1) continue;
+        if (chunk != n_chunks - 1) return;
 
         // the tile is complete.  Result layout: register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4,
         // column l % 32
         const int64_t tile_c = strip_c + (int64_t)tile * kFT;
-        uint32_t hits[2] = {0u, 0u};           // filter: bit ma * 16 + r of hits[nb]: that output of this lane passed the test
+        if (DENSE) {
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            const int64_t col = tile_c + n0 + nb * 32 + (lane & 31);
-            const bool col_ok = col < P.n_cols;
-            const float nxv = col_ok ? P.nx[col * P.col_step] : 0.f;
-            const float sx = sqrtf(nxv);
-            const float cn = P.metric == 0 ? nxv * (1.0f - P.c32) * half_inv : 0.f;
+            for (int nb = 0; nb < 2; ++nb) {
+                const int64_t col = tile_c + n0 + nb * 32 + (lane & 31);
+                const bool col_ok = col < P.n_cols;
+                const float nxv = col_ok ? nx_s[tile * kFT + n0 + nb * 32 + (lane & 31)] : 0.f;
 #pragma unroll
-            for (int ma = 0; ma < 2; ++ma)
+                for (int ma = 0; ma < 2; ++ma)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    const float2 rc = s_row[lrow];
-                    const float v = acc[ma][nb][r];
-                    acc[ma][nb][r] = 0.f;
-                    if (DENSE) {
+                    for (int r = 0; r < 16; ++r) {
+                        const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                         const int64_t lr = tile_r + lrow;
                         if (P.q_row0 + lr < P.q_rows) {
-                            const float dot = v * inv;
-                            const float approx = P.metric == 0 ? (rc.x + nxv) - 2.0f * dot : 0.0f - dot;
+                            const float dot = acc[ma][nb][r] * inv;
+                            const float approx = P.metric == 0 ? (s_row[lrow].x + nxv) - 2.0f * dot : 0.0f - dot;
                             P.out[lr * P.pitch + col] = col_ok ? approx : inf;
                         }
-                    } else if (v >= fmaf(0.0f - rc.y, sx, rc.x + cn) && col_ok) {
-                        hits[nb] |= 1u << (ma * 16 + r);
+                    }
+            }
+        } else {
+            // The few that passed (about one in a thousand) are first only noted, bit nb * 32 + ma * 16 + r of `hits`,
+            // where no lane of eight registers passed behind one scalar branch; then all lanes append theirs together,
+            // so that the wavefront waits for one atomic round trip per pass of that loop, not per register.
+            uint32_t hits[2] = {0u, 0u};
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int ma = 0; ma < 2; ++ma)
+#pragma unroll
+                    for (int r0 = 0; r0 < 16; r0 += 8) {
+                        uint64_t passed[8], any = 0ull;
+#pragma unroll
+                        for (int r = 0; r < 8; ++r) {
+                            passed[r] = __ballot(acc[ma][nb][r0 + r] >= 0.f);
+                            any |= passed[r];
+                        }
+                        if (any == 0ull) continue;
+#pragma unroll
+                        for (int r = 0; r < 8; ++r)
+                            if (passed[r] != 0ull && acc[ma][nb][r0 + r] >= 0.f) hits[nb] |= 1u << (ma * 16 + r0 + r);
+                    }
+            uint64_t todo = ((uint64_t)hits[1] << 32) | hits[0];
+            while (__ballot(todo != 0ull) != 0ull) {
+                bool valid = false;
+                uint32_t row = 0u, id32 = 0u;
+                if (todo != 0ull) {
+                    const int bit = __builtin_ctzll(todo);
+                    todo &= todo - 1;
+                    const int nb = bit >> 5, ma = (bit >> 4) & 1, r = bit & 15;
+                    const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const int64_t lr = tile_r + lrow, grow = P.q_row0 + lr;
+                    const int64_t id = (tile_c + n0 + nb * 32 + (lane & 31)) * P.col_step;
+                    valid = grow < P.q_rows && !(P.exclude_self && id == P.self_offset + grow);
+                    row = (uint32_t)lr; id32 = (uint32_t)id;
+                }
+                const uint64_t mv = __ballot(valid);
+                const int pos = n_listed + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mv >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mv, 0u));
+                if (valid) {
+                    if (pos < kHitCap) {
+                        hit_list[pos] = make_uint2(row, id32);
+                    } else {      // the list is full (a threshold that lets thousands pass): straight to the buffer
+                        const uint32_t at = atomicAdd(&P.count[row], 1u);
+                        if (at < (uint32_t)kCap) P.buf[(int64_t)row * kCap + at] = id32;
                     }
                 }
-        }
-        // the few that passed (about one in a thousand): append to the row's candidates
-        uint64_t todo = ((uint64_t)hits[1] << 32) | hits[0];
-        while (todo != 0ull) {
-            const int bit = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const int nb = bit >> 5, ma = (bit >> 4) & 1, r = bit & 15;
-            const int lrow = m0 + ma * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            const int64_t lr = tile_r + lrow, grow = P.q_row0 + lr;
-            const int64_t id = (tile_c + n0 + nb * 32 + (lane & 31)) * P.col_step;
-            if (grow < P.q_rows && !(P.exclude_self && id == P.self_offset + grow)) {
-                const uint32_t pos = atomicAdd(&P.count[lr], 1u);
-                if (pos < (uint32_t)kCap) P.buf[lr * kCap + pos] = (uint32_t)id;
+                n_listed += __popcll(mv);
             }
+            if (n_listed >= kHitCap / 2) flush_hits();
         }
-    }
-}
+        if (step + 1 < total) start_tile(tile + 1);
+    };
 
-#undef CAGRA_FETCH_STEP
-#undef CAGRA_FETCH_ONE
+    if (total <= 0) return;
+    start_tile(0);
+    u32x4_t va[4], vx[4];
+    fetch(0, va, vx);
+    for (int step = 0; step < total; ++step) do_step(step, va, vx);
+    if (!DENSE) flush_hits();
+}
 
 // ---- step 4: exact distances of the candidates, order, certificate ----------------------------
 
@@ -407,6 +503,8 @@ void launch_fill_u32(uint32_t *p, int64_t n, uint32_t value, hipStream_t stream)
 
 static size_t up256f(size_t v) { return (v + 255) & ~(size_t)255; }
 
+
+
 FilterPlan plan_exact_filter(int64_t N, int dim, int64_t B, int k, bool share_queries)
 {
     FilterPlan pl = {};
@@ -470,7 +568,7 @@ hipError_t launch_exact_filter(const float *X, int64_t N, int dim, int64_t ldX, 
     P.q_maxbits = share_queries ? maxbits : maxbits + 1; P.x_maxbits = maxbits;
     P.q_rows = B; P.dimP = pl.dimP; P.metric = metric;
     P.c16 = 1.01f / 1024.0f;
-    P.c32 = (float)(8 * dim + 32) / 16777216.0f;
+    P.c32 = (float)(12 * dim + 48) / 16777216.0f;
     P.thr = thr_d + (pl.t - 1); P.thr_stride = pl.t;
     P.count = count; P.buf = buf; P.exclude_self = exclude_self; P.self_offset = self_offset;
 
@@ -483,7 +581,7 @@ hipError_t launch_exact_filter(const float *X, int64_t N, int dim, int64_t ldX, 
         FilterParams S = P;
         S.n_cols = pl.n_sample; S.col_step = pl.stride; S.out = plain_scratch; S.pitch = pl.sample_pitch;
         S.row_tiles = (int)row_tiles; S.n_strips = (pl.sample_pitch + kFT * kStrip - 1) / (kFT * kStrip);
-        hipLaunchKernelGGL(mfma_tile_kernel<true>, dim3((unsigned)((S.n_strips + 7) / 8 * 8 * row_tiles)), dim3(256), 0,
+        hipLaunchKernelGGL(mfma_tile_kernel<true>, dim3((unsigned)((S.n_strips + 7) / 8 * 8 * row_tiles)), dim3(256), kFilterSmem,
                            stream, S);
         launch_row_select(plain_scratch, pl.sample_pitch, rows, pl.t, thr_ids, thr_d, stream);
         // step 3
@@ -491,7 +589,7 @@ hipError_t launch_exact_filter(const float *X, int64_t N, int dim, int64_t ldX, 
         FilterParams F = P;
         F.n_cols = N; F.col_step = 1;
         F.row_tiles = (int)row_tiles; F.n_strips = (N + kFT * kStrip - 1) / (kFT * kStrip);
-        hipLaunchKernelGGL(mfma_tile_kernel<false>, dim3((unsigned)((F.n_strips + 7) / 8 * 8 * row_tiles)), dim3(256), 0,
+        hipLaunchKernelGGL(mfma_tile_kernel<false>, dim3((unsigned)((F.n_strips + 7) / 8 * 8 * row_tiles)), dim3(256), kFilterSmem,
                            stream, F);
         // step 4
         hipLaunchKernelGGL(rerank_kernel, dim3((unsigned)rows), dim3(256), (size_t)dim * 4, stream, X, dim, ldX, metric,

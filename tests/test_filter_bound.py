@@ -1,8 +1,8 @@
 """The error bound behind the matrix-core filter of the exhaustive search, checked on the CPU with
 numpy's fp16 rounding: for vectors x, q scaled by a power of two that brings the largest magnitude into
 [2^13, 2^14) and rounded to fp16, the distance formed from the rounded copies and fp32 norms stays within
-    eps = 2 * 1.01 * 2^-10 * |x||q| + (8 dim + 32) * 2^-24 * (|x|^2 + |q|^2)        (squared L2)
-    eps = 2 * (1.01 * 2^-10 + (8 dim + 32) * 2^-24) * |x||q|                          (inner product)
+    eps = 2 * 1.01 * 2^-10 * |x||q| + (12 dim + 48) * 2^-24 * (|x|^2 + |q|^2)       (squared L2)
+    eps = 2 * (1.01 * 2^-10 + (12 dim + 48) * 2^-24) * |x||q|                         (inner product)
 of the true distance, with the share of eps that is reserved for the rounding of the exact fp32 chain
 and of the MFMA's own accumulation left unused.  The filter keeps a dataset row when its approximate
 distance is at most threshold + eps, so a bound that failed here would let it drop true neighbours."""
@@ -21,7 +21,7 @@ def _scale(m):
 
 def _approx(x, q, metric):
     """What the filter computes, its dot product in float64 (the hardware accumulates in fp32: covered by
-    the (8 dim + 32) u term, of which this test only grants the part for norms and final additions)."""
+    the (12 dim + 48) u term, of which this test only grants the part for norms and final additions)."""
     sx, sq = _scale(x), _scale(q)
     x16 = (x * np.float32(sx)).astype(np.float16).astype(np.float64)
     q16 = (q * np.float32(sq)).astype(np.float16).astype(np.float64)
@@ -66,13 +66,16 @@ def test_fp16_filter_error_bound(name, x, q, metric):
     nq = (q.astype(np.float64) ** 2).sum(axis=1)
     g = np.sqrt(nq[:, None] * nx[None, :])
     s = nq[:, None] + nx[None, :]
-    c16, c32 = 1.01 * 2.0 ** -10, (8 * dim + 32) * U
-    # reserved and not granted here: the chain's own rounding ((2 dim + 4) u S resp. (dim + 2) u g) and the
-    # accumulation inside the matrix instruction (2 dim u g)
+    c16, c32 = 1.01 * 2.0 ** -10, (12 * dim + 48) * U
+    # reserved and not granted here: the chain's own rounding ((2 dim + 4) u S resp. (dim + 2) u g), and the
+    # accumulation inside the matrix instruction, whose accumulators start at minus the right-hand side of the
+    # test, so that a partial sum is bounded by 1.01 S resp. 2.01 g in scaled units and every one of the dim
+    # additions errs by at most 2 u of that (truncation), plus the two roundings of the start value:
+    # (4.1 dim + 3) u S resp. (4.1 dim + 3) u g
     if metric == "l2":
-        eps = 2 * c16 * g + c32 * s - (2 * dim + 4) * U * s - 2 * dim * U * g
+        eps = 2 * c16 * g + c32 * s - (2 * dim + 4) * U * s - (4.1 * dim + 3) * U * s
     else:
-        eps = 2 * (c16 + c32) * g - (dim + 2) * U * g - 2 * dim * U * g
+        eps = 2 * (c16 + c32) * g - (dim + 2) * U * g - (4.1 * dim + 3) * U * g
     err = np.abs(_approx(x, q, metric) - _true(x, q, metric))
     assert np.all(eps >= 0)
     assert np.all(err <= eps), f"{name}: the bound fails for {int(np.sum(err > eps))} pairs"
