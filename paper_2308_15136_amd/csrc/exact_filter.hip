@@ -232,17 +232,25 @@ mfma_tile_kernel(const FilterParams P)
     // row's dimensions reads the row's last piece, and none of that is ever used (the outputs of such rows and columns
     // are ignored, the matrix instructions stop at the row's dimensions).
     const int64_t last_col = P.n_cols - 1;
+    const _Float16 *src_x[4];        // this thread's four dataset rows of the tile being fetched
+    int src_tile = -1;
     auto fetch = [&](int f_step, u32x4_t (&xa)[4], u32x4_t (&xx)[4]) __attribute__((always_inline)) {
         const int f_tile = f_step / n_chunks, f_k0 = (f_step - f_tile * n_chunks) * kFK;
+        if (f_tile != src_tile) {    // (uniform) the row addresses are formed once per tile, not once per step
+            src_tile = f_tile;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int64_t f_col = strip_c + (int64_t)f_tile * kFT + ((tid + 256 * u) >> 3);
+                f_col = f_col < last_col ? f_col : last_col;
+                src_x[u] = P.X16 + f_col * P.col_step * P.dimP;
+            }
+        }
+        int f_k = (tid & 7) * 8 + f_k0;          // (tid + 256 u) & 7 is the same for all four pieces
+        f_k = f_k < P.dimP ? f_k : P.dimP - 8;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int f_row = (tid + 256 * u) >> 3, f_part = (tid + 256 * u) & 7;
-            int64_t f_col = strip_c + (int64_t)f_tile * kFT + f_row;
-            f_col = f_col < last_col ? f_col : last_col;
-            int f_k = f_part * 8 + f_k0;
-            f_k = f_k < P.dimP ? f_k : P.dimP - 8;
             xa[u] = *reinterpret_cast<const u32x4_t *>(src_a[u] + f_k);
-            xx[u] = *reinterpret_cast<const u32x4_t *>(P.X16 + f_col * P.col_step * P.dimP + f_k);
+            xx[u] = *reinterpret_cast<const u32x4_t *>(src_x[u] + f_k);
         }
     };
     floatx16_t acc[2][2];
@@ -349,7 +357,7 @@ mfma_tile_kernel(const FilterParams P)
             }
         } else {
             // The few that passed (about one in a thousand) are first only noted, bit nb * 32 + ma * 16 + r of `hits`,
-            // where no lane of eight registers passed behind one scalar branch; then all lanes append theirs together,
+            // where no lane of four registers passed behind one scalar branch; then all lanes append theirs together,
             // so that the wavefront waits for one atomic round trip per pass of that loop, not per register.
             uint32_t hits[2] = {0u, 0u};
 #pragma unroll
@@ -357,16 +365,16 @@ mfma_tile_kernel(const FilterParams P)
 #pragma unroll
                 for (int ma = 0; ma < 2; ++ma)
 #pragma unroll
-                    for (int r0 = 0; r0 < 16; r0 += 8) {
-                        uint64_t passed[8], any = 0ull;
+                    for (int r0 = 0; r0 < 16; r0 += 4) {
+                        uint64_t passed[4], any = 0ull;
 #pragma unroll
-                        for (int r = 0; r < 8; ++r) {
+                        for (int r = 0; r < 4; ++r) {
                             passed[r] = __ballot(acc[ma][nb][r0 + r] >= 0.f);
                             any |= passed[r];
                         }
                         if (any == 0ull) continue;
 #pragma unroll
-                        for (int r = 0; r < 8; ++r)
+                        for (int r = 0; r < 4; ++r)
                             if (passed[r] != 0ull && acc[ma][nb][r0 + r] >= 0.f) hits[nb] |= 1u << (ma * 16 + r0 + r);
                     }
             uint64_t todo = ((uint64_t)hits[1] << 32) | hits[0];
