@@ -83,8 +83,8 @@ def test_large_batch_workload_at_full_size():
 
 
 @pytest.mark.parametrize("name,cases", [
-    ("deep1m", ((10, 128, 1), (100, 256, 1), (10, 64, 4), (10, 32, 16))),   # 1M x 96 unit-norm rows, L2, degree 32
-    ("glove200", ((10, 256, 1), (10, 128, 2), (10, 64, 8))),                 # 1,183,514 x 200 unit-norm rows, inner product
+    ("deep1m", ((10, 128, 1), (100, 256, 1), (10, 64, 4), (10, 32, 16), (10, 64, 8), (100, 128, 4))),   # 1M x 96 unit-norm rows, L2, degree 32; the last two cases: bench.py's timed points
+    ("glove200", ((10, 256, 1), (10, 128, 2), (10, 64, 8), (10, 256, 16))),   # 1,183,514 x 200 unit-norm rows, inner product; the last case: bench.py's timed point
 ])
 def test_float_workloads_at_full_size(name, cases):
     """The lower-dimensional and the inner-product configuration at their full sizes: whole batch on
@@ -210,7 +210,7 @@ def test_small_batch_workload_at_full_size():
                     assert abs(d_np[b, t] - ref) <= 1e-5 * abs(ref)
 
     print("  single mode", flush=True)
-    for itopk, width in ((64, 1), (128, 4), (64, 16)):
+    for itopk, width in ((64, 1), (128, 4), (64, 16), (128, 2)):     # the last: bench.py's timed point at batch 10,000
         opts = cagra.SearchOptions(seed=7, mode=1)
         ids, dists, st = cagra.search(graph, base, queries, k, itopk, width, w.metric, opts, return_stats=True)
         ids_np, d_np = _u32(ids), dists.cpu().numpy()
