@@ -29,6 +29,31 @@ __device__ __forceinline__ float4 widen4(const uint4 &p, int i)
     }
 }
 
+// acc += sum of (x_j - q_j)^2 over the i-th group of four elements of a 16-byte piece, one subtraction and one fused
+// multiply-add per element in fp32, in order.  fp16 rows: the subtraction is written as fma(x, one, -q) with `one` a
+// register that holds 1.0 but is opaque to the compiler -- the same value with the same single rounding as
+// float(x) - q, but a form the hardware evaluates straight from the fp16 half of a register (v_fma_mix_f32), which
+// spares the conversion: two vector instructions per element instead of three.  (The inner product needs no such
+// help: fma(float(x), q, acc) is that instruction already.)
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+template <int ELEM>
+__device__ __forceinline__ void l2_accumulate4(const uint4 &p, int i, const float4 &qv, float one, float &acc)
+{
+    if constexpr (ELEM == 1) {
+        const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+        const half2_t a = __builtin_bit_cast(half2_t, w[2 * i]), b = __builtin_bit_cast(half2_t, w[2 * i + 1]);
+        const float d0 = fmaf((float)a[0], one, 0.0f - qv.x), d1 = fmaf((float)a[1], one, 0.0f - qv.y);
+        const float d2 = fmaf((float)b[0], one, 0.0f - qv.z), d3 = fmaf((float)b[1], one, 0.0f - qv.w);
+        acc = fmaf(d0, d0, acc); acc = fmaf(d1, d1, acc);
+        acc = fmaf(d2, d2, acc); acc = fmaf(d3, d3, acc);
+    } else {
+        const float4 xv = widen4<ELEM>(p, i);
+        const float d0 = xv.x - qv.x, d1 = xv.y - qv.y, d2 = xv.z - qv.z, d3 = xv.w - qv.w;
+        acc = fmaf(d0, d0, acc); acc = fmaf(d1, d1, acc);
+        acc = fmaf(d2, d2, acc); acc = fmaf(d3, d3, acc);
+    }
+}
+
 // newdist[c] = distance(query, dataset row newid[c]) for c < n_new (entries equal to kInvalidId are
 // skipped).  Called by all 64 lanes of a wavefront; qlds holds the query as fp32, `ld` is the row
 // stride in elements, RIF the rows each team keeps in flight (all loads of a round are issued
@@ -45,6 +70,8 @@ __device__ __forceinline__ void team_distances_impl(const void *dataset, int64_t
     const int g = lane >> team_log2;       // team of this lane
     const int t = lane & (team - 1);       // lane within the team
     const int nchunk = dim / kPiece;       // 16-byte pieces per row
+    float one = 1.0f;                      // see l2_accumulate4
+    if constexpr (ELEM == 1) asm volatile("" : "+v"(one));
     for (int c0 = 0; c0 < n_new; c0 += RIF * n_teams) {
         const unsigned char *row[RIF];
         bool ok[RIF];
@@ -83,12 +110,7 @@ __device__ __forceinline__ void team_distances_impl(const void *dataset, int64_t
                         const float4 qv = *reinterpret_cast<const float4 *>(qlds + kPiece * ch[i] + 4 * h);
                         if (metric == 0) {
 #pragma unroll
-                            for (int u = 0; u < RIF; ++u) {
-                                const float4 xv = widen4<ELEM>(x[u][i], h);
-                                const float d0 = xv.x - qv.x, d1 = xv.y - qv.y, d2 = xv.z - qv.z, d3 = xv.w - qv.w;
-                                acc[u] = fmaf(d0, d0, acc[u]); acc[u] = fmaf(d1, d1, acc[u]);
-                                acc[u] = fmaf(d2, d2, acc[u]); acc[u] = fmaf(d3, d3, acc[u]);
-                            }
+                            for (int u = 0; u < RIF; ++u) l2_accumulate4<ELEM>(x[u][i], h, qv, one, acc[u]);
                         } else {
 #pragma unroll
                             for (int u = 0; u < RIF; ++u) {
