@@ -20,6 +20,7 @@ from typing import Optional, Tuple
 _PKG = os.path.dirname(os.path.abspath(__file__))
 # CAGRA_HIP_LIB names another build of the same library (e.g. one with the phase timers compiled in)
 LIB_PATH = os.environ.get("CAGRA_HIP_LIB") or os.path.join(_PKG, "libcagra_hip.so")
+PROBE_LIB_PATH = os.path.join(_PKG, "libcagra_probe.so")
 
 L2 = 0
 IP = 1
@@ -124,10 +125,25 @@ def load_library():
     lib.cagra_two_hop_counts.argtypes = [vp, i64, i32, vp, vp]
     lib.cagra_count_components.restype = C.c_int
     lib.cagra_count_components.argtypes = [vp, i64, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
-    lib.cagra_probe_bandwidth.restype = C.c_int
-    lib.cagra_probe_bandwidth.argtypes = [vp, i64, i64, i64, i32, i64, i32, i32, i32, C.c_uint64, vp, vp]
     _lib = lib
     return lib
+
+
+_probe_lib = None
+
+
+def load_probe_library():
+    """Load libcagra_probe.so, the bandwidth probe built beside the product library (include/cagra_probe.h)."""
+    global _probe_lib
+    if _probe_lib is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            raise CagraError(f"{PROBE_LIB_PATH} is missing: run `python -m paper_2308_15136_amd.buildlib`")
+        lib = C.CDLL(PROBE_LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        lib.cagra_probe_bandwidth.restype = C.c_int
+        lib.cagra_probe_bandwidth.argtypes = [vp, i64, i64, i64, i32, i64, i32, i32, i32, C.c_uint64, vp, vp]
+        _probe_lib = lib
+    return _probe_lib
 
 
 def strerror(code: int) -> str:
@@ -215,7 +231,7 @@ def probe_bandwidth(data, pattern: int, n_read: int = 0, team_size: int = 0, row
     es = data.element_size()
     if sink is None:
         sink = torch.zeros(1, dtype=torch.int32, device=data.device)
-    _check(load_library().cagra_probe_bandwidth(data.data_ptr(), data.shape[0], data.shape[1] * es,
+    _check(load_probe_library().cagra_probe_bandwidth(data.data_ptr(), data.shape[0], data.shape[1] * es,
                                                 data.stride(0) * es, pattern, n_read, team_size, rows_in_flight,
                                                 waves_per_cu, seed, sink.data_ptr(), _stream(data.device)),
            "cagra_probe_bandwidth")

@@ -1,4 +1,5 @@
-"""Builds libcagra_hip.so (gfx950) from csrc/*.hip with hipcc, in-tree."""
+"""Builds libcagra_hip.so (gfx950) from csrc/*.hip with hipcc, in-tree, and beside it libcagra_probe.so, the
+bandwidth probe that bench.py uses (csrc/probe.hip alone: a measurement aid, not part of the product library)."""
 from __future__ import annotations
 
 import concurrent.futures as cf
@@ -9,6 +10,8 @@ import subprocess
 _PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_PKG, "csrc")
 LIB = os.path.join(_PKG, "libcagra_hip.so")
+PROBE_LIB = os.path.join(_PKG, "libcagra_probe.so")
+_PROBE_SRC = "probe.hip"
 _OBJ_DIR = os.path.join(_PKG, "_build")
 
 HIPCC_FLAGS = [
@@ -27,14 +30,15 @@ def _hipcc() -> str:
 
 
 def sources() -> list:
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    """Sources of the product library."""
+    return sorted(f for f in glob.glob(os.path.join(CSRC, "*.hip")) if os.path.basename(f) != _PROBE_SRC)
 
 
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    if not os.path.exists(LIB) or not os.path.exists(PROBE_LIB):
         return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + \
+    t = min(os.path.getmtime(LIB), os.path.getmtime(PROBE_LIB))
+    deps = sources() + [os.path.join(CSRC, _PROBE_SRC)] + glob.glob(os.path.join(CSRC, "*.h")) + \
         glob.glob(os.path.join(_PKG, "..", "include", "*.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
@@ -58,6 +62,11 @@ def build_library(verbose: bool = False, defines=(), out: str = LIB) -> str:
     subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs], check=True)
     if verbose:
         print("built", out)
+    if out == LIB:
+        probe_obj = compile_one(os.path.join(CSRC, _PROBE_SRC))
+        subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB, probe_obj], check=True)
+        if verbose:
+            print("built", PROBE_LIB)
     return out
 
 

@@ -9,7 +9,8 @@
 #include <algorithm>
 #include <cstdint>
 
-#include "../../include/cagra_hip.h"
+#include "../../include/cagra_hip.h"     // status codes
+#include "../../include/cagra_probe.h"
 #include "device_util.h"
 
 namespace cagra {

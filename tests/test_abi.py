@@ -8,27 +8,28 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    names = []
-    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
-        if not fn.endswith(".h"):
-            continue
-        text = open(os.path.join(ROOT, "include", fn)).read()
-        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names += re.findall(r"\b(cagra_\w+)\s*\(", text)
-    return sorted(set(names))
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cagra_\w+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():
+    # one library per header: the product (cagra_hip.h) and the bandwidth probe beside it (cagra_probe.h)
     import paper_2308_15136_amd as m
-    if not os.path.exists(m.LIB_PATH):
+    if not os.path.exists(m.LIB_PATH) or not os.path.exists(m.PROBE_LIB_PATH):
         from paper_2308_15136_amd import buildlib as build
         build.build_library()
-    lib = ctypes.CDLL(m.LIB_PATH)
-    names = _declared()
-    assert len(names) >= 10
-    for n in names:
-        assert hasattr(lib, n), f"{n} declared in include/ but not exported"
+    headers = sorted(fn for fn in os.listdir(os.path.join(ROOT, "include")) if fn.endswith(".h"))
+    assert headers == ["cagra_hip.h", "cagra_probe.h"]
+    for header, path, least in (("cagra_hip.h", m.LIB_PATH, 10), ("cagra_probe.h", m.PROBE_LIB_PATH, 1)):
+        lib = ctypes.CDLL(path)
+        names = _declared(header)
+        assert len(names) >= least
+        for n in names:
+            assert hasattr(lib, n), f"{n} declared in include/{header} but not exported by {os.path.basename(path)}"
+    # and the product library carries no measurement aid
+    assert not hasattr(ctypes.CDLL(m.LIB_PATH), "cagra_probe_bandwidth")
 
 
 def test_host_only_entry_points_work_without_gpu():
